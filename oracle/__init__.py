@@ -1,0 +1,24 @@
+"""CPU oracle for the W8A8 / W4A8 quantized linear layer -- TEST INFRASTRUCTURE.
+
+A plain, slow, obviously-correct implementation of what the hot path computes,
+written from the paper's definitions (its Eq. 1-2 quantizer, the per-token /
+per-channel / group-wise granularities of its Preliminary section, the
+symmetric setting of its Experimental Setup, and Y = XW of its Eq. 3).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may use this
+package.  It shares no code with the HIP path and imports nothing from it.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against
+hand-derived vectors (tests/golden/), closed forms, brute force in exact
+Python arithmetic and an exact float64-BLAS integer product.  No function is
+"parity unpinned".
+"""
+from .quantizers import (  # noqa: F401
+    quant_act_per_token,
+    quant_weight_int8,
+    quant_weight_int4,
+    pack_int4,
+    unpack_int4,
+    quant_eq2_literal,
+)
+from .linear import igemm, igemm_grouped, linear_w8a8, linear_w4a8  # noqa: F401
