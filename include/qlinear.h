@@ -1,0 +1,154 @@
+/* qlinear.h -- C ABI of the MI355X (gfx950) quantized linear layer.
+ *
+ * The layer is the W8A8 / W4A8 linear of the paper's unified low-bit inference
+ * framework (Method, "Unified Low-Bit Inference Framework for INT8 and W4A8"):
+ *
+ *   xq, sx = per-token symmetric int8 quantization of x        (Eq. 1-2, n = 8;
+ *            one scale per token: Preliminary, granularity paragraph)
+ *   acc    = xq * wq^T  in exact integer arithmetic, int32 accumulators
+ *   y      = fp16( acc * sx[m] * sw[n] + bias[n] )              (W8A8, per-output-channel sw)
+ *   y      = fp16( sx[m] * sum_g acc_g * sw[n,g] + bias[n] )    (W4A8, one fp16 sw per group of
+ *                                                                128 consecutive k per channel)
+ *
+ * Reading of Eq. 2 used throughout (symmetric setting of the paper's
+ * Experimental Setup): scale = max|X| / (2^(n-1) - 1); codes = round-half-to-even,
+ * clamped to +-127 (int8) or +-7 (int4); an all-zero token/channel/group stores
+ * scale 1.  Activations use code = rne(x * (127/amax)) (one fp32 multiply per
+ * element); weights, quantized offline, use code = rne(w / stored_scale).
+ *
+ * Conventions
+ *   - every pointer is a DEVICE pointer unless its comment says "host"
+ *   - the caller owns every buffer; the library never allocates, frees or
+ *     synchronizes; all work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and is asynchronous
+ *   - every call returns a ql_status; arguments are validated on the host
+ *     before anything is launched, so a failing call has no side effects;
+ *     ql_last_error() gives a thread-local message for the last failure
+ *   - x is fp16 [M,K] row-major with leading dimension ldx (elements);
+ *     w is fp16 [N,K] row-major, row n = output channel n (so y = x w^T);
+ *     y is fp16 [M,N] row-major with leading dimension ldy
+ *   - alignment: x, y 16-byte aligned, ldx % 8 == 0, ldy % 8 == 0; every other
+ *     device buffer 16-byte aligned (256-byte for workspaces and weight blobs)
+ *   - limits: K % 64 == 0 (int8 weights) or K % 128 == 0 (int4, group = 128);
+ *     K <= 131072 so that no int32 accumulator can overflow; padded sizes
+ *     ceil32(M)*K and ceil32(N)*K below 2^31
+ *   - M == 0 is a valid no-op
+ *
+ * "Kernel layout": weights and quantized activations are consumed by the GEMM
+ * kernels as 32-row x 32-k tiles of 1024 bytes, each tile stored in the order a
+ * 64-lane wavefront feeds the 32x32x32 int8 matrix instruction (lane = row % 32
+ * + 32 * ((k % 32) / 16), 16 consecutive k per lane); tiles are ordered
+ * row-block-major, then k-block.  Rows are padded to a multiple of 32.  int4
+ * tiles hold two k-blocks per 1024 bytes with the nibbles pre-ordered for a
+ * shift/mask unpack, followed in the same blob by the group scales transposed to
+ * [K/128][ceil32(N)].  The layout is opaque to callers: build it with
+ * ql_quant_weight / ql_quant_act_per_token / ql_act_repack and read it back with
+ * ql_export_canonical.
+ */
+#ifndef QLINEAR_H
+#define QLINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ql_status {
+    QL_OK = 0,
+    QL_ERR_NULL = 1,        /* a required pointer is NULL */
+    QL_ERR_SHAPE = 2,       /* a size is negative, zero where it may not be, or violates a divisibility rule */
+    QL_ERR_ALIGN = 3,       /* a pointer or leading dimension violates the alignment rules above */
+    QL_ERR_UNSUPPORTED = 4, /* bits/group combination or size beyond the stated limits */
+    QL_ERR_WORKSPACE = 5,   /* workspace smaller than ql_workspace_bytes reports */
+    QL_ERR_HIP = 6          /* a HIP runtime call failed (message in ql_last_error) */
+} ql_status;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int ql_version(void);
+
+/* Host pointer to a thread-local, NUL-terminated description of the last error on this thread. */
+const char *ql_last_error(void);
+
+/* Size queries (host outputs, any may be NULL).
+ *   canonical: int8 [N,K] (bits 8) or packed nibbles [N,K/2] (bits 4)
+ *   scales:    fp32 [N] (bits 8, group 0) or fp16 [N,K/group] (bits 4)
+ *   kernel:    the opaque kernel-layout blob
+ * bits/group: (8, 0) or (4, 128). */
+int ql_weight_bytes(int N, int K, int bits, int group,
+                    size_t *canonical, size_t *scales, size_t *kernel);
+
+/* Bytes of the kernel-layout copy of xq for M tokens: ceil32(M) * K. */
+int ql_act_kernel_bytes(int M, int K, size_t *bytes /* host */);
+
+/* Workspace needed by ql_w8a8_linear / ql_w4a8_linear / the *_gemm calls for these sizes
+ * (quantized activations in kernel layout, their scales, split-K scratch). */
+int ql_workspace_bytes(int M, int N, int K, int bits, size_t *bytes /* host */);
+
+/* Per-token dynamic int8 activation quantization (Eq. 1-2 with n = 8, one scale per token).
+ *   x           fp16 [M,K], leading dimension ldx
+ *   xq_rowmajor int8 [M,K] contiguous, may be NULL
+ *   xq_kernel   int8 kernel layout (ql_act_kernel_bytes), may be NULL; at least one of the two
+ *   sx          fp32 [M]: amax/127 (1 for an all-zero token)
+ * Non-finite inputs give unspecified codes. */
+int ql_quant_act_per_token(const void *x, int64_t ldx, int M, int K,
+                           int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx, void *stream);
+
+/* Row-major int8 [M,K] -> kernel layout (lets a caller supply its own quantized activations). */
+int ql_act_repack(const int8_t *xq_rowmajor, int M, int K, int8_t *xq_kernel, void *stream);
+
+/* Offline weight quantization (Eq. 1-2; per-output-channel for int8, group-wise along K for int4)
+ * and conversion to the kernel layout ("weight layout" of the paper's framework).
+ *   w            fp16 [N,K] contiguous
+ *   bits, group  (8, 0): int8 codes, fp32 scale per output channel
+ *                (4, 128): int4 codes in [-7,7], two's-complement nibbles packed two per byte
+ *                along K (even k in bits 3:0), fp16 scale per (channel, group of 128 k)
+ *   wq_canonical may be NULL; scales may be NULL for bits 4 only (they are also kept in the blob)
+ *   wq_kernel    kernel-layout blob, may be NULL */
+int ql_quant_weight(const void *w, int N, int K, int bits, int group,
+                    void *wq_canonical, void *scales, void *wq_kernel, void *stream);
+
+/* Kernel-layout blob -> canonical codes (and, for bits 4, canonical fp16 group scales; `scales`
+ * is ignored for bits 8 and may be NULL for bits 4).  Inverse of the repack in ql_quant_weight. */
+int ql_export_canonical(const void *wq_kernel, int N, int K, int bits, int group,
+                        void *wq_canonical, void *scales, void *stream);
+
+/* W8A8 linear layer: activation quantization + int8 GEMM + dequantization epilogue.
+ *   sw   fp32 [N] per-output-channel weight scales;  bias fp16 [N] or NULL
+ *   ws   workspace of at least ql_workspace_bytes(M,N,K,8) bytes */
+int ql_w8a8_linear(const void *x, int64_t ldx, int M, int K,
+                   const void *wq_kernel, const float *sw, const void *bias, int N,
+                   void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/* W4A8 linear layer (group scales live in the blob). */
+int ql_w4a8_linear(const void *x, int64_t ldx, int M, int K,
+                   const void *w4_kernel, int group, const void *bias, int N,
+                   void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/* GEMM + epilogue on already-quantized activations (xq in kernel layout, sx fp32 [M]). */
+int ql_w8a8_gemm(const int8_t *xq_kernel, const float *sx, int M, int K,
+                 const void *wq_kernel, const float *sw, const void *bias, int N,
+                 void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+int ql_w4a8_gemm(const int8_t *xq_kernel, const float *sx, int M, int K,
+                 const void *w4_kernel, int group, const void *bias, int N,
+                 void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
+/* Test hooks: the same main loops with the raw integer accumulators written out.
+ *   acc      int32 [M,N] contiguous: sum over all k (W4A8: sum over groups of the group partials)
+ *   partials (W4A8 only, may be NULL) int32 [nrows, K/group, N] for tokens row0 .. row0+nrows-1 */
+int ql_w8a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *wq_kernel, int N,
+                         int32_t *acc, void *ws, size_t ws_bytes, void *stream);
+int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_kernel, int group,
+                         int N, int32_t *acc, int32_t *partials, int row0, int nrows,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* Kernel selection, for tests and tuning (process-wide, not thread-safe):
+ *   0 = automatic (decode kernels for M <= 32, otherwise a prefill tile chosen from the shape)
+ *   other values pick one implementation; unknown values -> QL_ERR_UNSUPPORTED. */
+int ql_set_kernel_variant(int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QLINEAR_H */

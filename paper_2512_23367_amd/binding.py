@@ -1,0 +1,205 @@
+"""ctypes binding of libqlinear.so: same names as include/qlinear.h, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used as plain device buffers; every call is enqueued on
+torch's current stream.  There is no fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqlinear.so")
+
+QL_OK = 0
+STATUS_NAMES = {0: "QL_OK", 1: "QL_ERR_NULL", 2: "QL_ERR_SHAPE", 3: "QL_ERR_ALIGN",
+                4: "QL_ERR_UNSUPPORTED", 5: "QL_ERR_WORKSPACE", 6: "QL_ERR_HIP"}
+
+EXPORTS = [
+    "ql_version", "ql_last_error", "ql_weight_bytes", "ql_act_kernel_bytes", "ql_workspace_bytes",
+    "ql_quant_act_per_token", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
+    "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
+    "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant",
+]
+
+
+class QlError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (python -m paper_2512_23367_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2512_23367_amd.build` "
+                "(there is no CPU or PyTorch fallback)")
+        l = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        vp, i, i64, sz = c.c_void_p, c.c_int, c.c_int64, c.c_size_t
+        szp = c.POINTER(c.c_size_t)
+        l.ql_version.restype = i
+        l.ql_version.argtypes = []
+        l.ql_last_error.restype = c.c_char_p
+        l.ql_last_error.argtypes = []
+        sigs = {
+            "ql_set_kernel_variant": [i],
+            "ql_weight_bytes": [i, i, i, i, szp, szp, szp],
+            "ql_act_kernel_bytes": [i, i, szp],
+            "ql_workspace_bytes": [i, i, i, i, szp],
+            "ql_quant_act_per_token": [vp, i64, i, i, vp, vp, vp, vp],
+            "ql_act_repack": [vp, i, i, vp, vp],
+            "ql_quant_weight": [vp, i, i, i, i, vp, vp, vp, vp],
+            "ql_export_canonical": [vp, i, i, i, i, vp, vp, vp],
+            "ql_w8a8_linear": [vp, i64, i, i, vp, vp, vp, i, vp, i64, vp, sz, vp],
+            "ql_w4a8_linear": [vp, i64, i, i, vp, i, vp, i, vp, i64, vp, sz, vp],
+            "ql_w8a8_gemm": [vp, vp, i, i, vp, vp, vp, i, vp, i64, vp, sz, vp],
+            "ql_w4a8_gemm": [vp, vp, i, i, vp, i, vp, i, vp, i64, vp, sz, vp],
+            "ql_w8a8_gemm_acc_i32": [vp, i, i, vp, i, vp, vp, sz, vp],
+            "ql_w4a8_gemm_acc_i32": [vp, i, i, vp, i, i, vp, vp, i, i, vp, sz, vp],
+        }
+        for name, args in sigs.items():
+            fn = getattr(l, name)
+            fn.restype = i
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+def _check(status: int):
+    if status != QL_OK:
+        raise QlError(status, lib().ql_last_error().decode())
+
+
+def _p(t):
+    """Device pointer of a tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _want(t, dtype, name):
+    if t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    return t
+
+
+def ql_version() -> int:
+    return lib().ql_version()
+
+
+def ql_last_error() -> str:
+    return lib().ql_last_error().decode()
+
+
+def ql_set_kernel_variant(variant: int):
+    _check(lib().ql_set_kernel_variant(variant))
+
+
+def ql_weight_bytes(N, K, bits, group):
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().ql_weight_bytes(N, K, bits, group, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
+
+
+def ql_act_kernel_bytes(M, K) -> int:
+    a = ctypes.c_size_t()
+    _check(lib().ql_act_kernel_bytes(M, K, ctypes.byref(a)))
+    return a.value
+
+
+def ql_workspace_bytes(M, N, K, bits) -> int:
+    a = ctypes.c_size_t()
+    _check(lib().ql_workspace_bytes(M, N, K, bits, ctypes.byref(a)))
+    return a.value
+
+
+def _ld(t):
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError("2-D tensor with unit inner stride expected")
+    return t.stride(0)
+
+
+def ql_quant_act_per_token(x, xq_rowmajor=None, xq_kernel=None, sx=None):
+    _want(x, torch.float16, "x")
+    M, K = x.shape
+    _check(lib().ql_quant_act_per_token(_p(x), _ld(x) if M else K, M, K, _p(xq_rowmajor), _p(xq_kernel), _p(sx),
+                                        _stream()))
+
+
+def ql_act_repack(xq_rowmajor, xq_kernel):
+    _want(xq_rowmajor, torch.int8, "xq_rowmajor")
+    M, K = xq_rowmajor.shape
+    _check(lib().ql_act_repack(_p(xq_rowmajor), M, K, _p(xq_kernel), _stream()))
+
+
+def ql_quant_weight(w, bits, group, wq_canonical=None, scales=None, wq_kernel=None):
+    _want(w, torch.float16, "w")
+    N, K = w.shape
+    if not w.is_contiguous():
+        raise ValueError("w must be contiguous")
+    _check(lib().ql_quant_weight(_p(w), N, K, bits, group, _p(wq_canonical), _p(scales), _p(wq_kernel), _stream()))
+
+
+def ql_export_canonical(wq_kernel, N, K, bits, group, wq_canonical=None, scales=None):
+    _check(lib().ql_export_canonical(_p(wq_kernel), N, K, bits, group, _p(wq_canonical), _p(scales), _stream()))
+
+
+def _ws(ws):
+    return (_p(ws), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
+
+
+def ql_w8a8_linear(x, wq_kernel, sw, bias, N, y, ws):
+    _want(x, torch.float16, "x"), _want(y, torch.float16, "y"), _want(sw, torch.float32, "sw")
+    M, K = x.shape
+    wsp, wsb = _ws(ws)
+    _check(lib().ql_w8a8_linear(_p(x), _ld(x) if M else K, M, K, _p(wq_kernel), _p(sw), _p(bias), N, _p(y),
+                                _ld(y) if M else N, wsp, wsb, _stream()))
+
+
+def ql_w4a8_linear(x, w4_kernel, group, bias, N, y, ws):
+    _want(x, torch.float16, "x"), _want(y, torch.float16, "y")
+    M, K = x.shape
+    wsp, wsb = _ws(ws)
+    _check(lib().ql_w4a8_linear(_p(x), _ld(x) if M else K, M, K, _p(w4_kernel), group, _p(bias), N, _p(y),
+                                _ld(y) if M else N, wsp, wsb, _stream()))
+
+
+def ql_w8a8_gemm(xq_kernel, sx, M, K, wq_kernel, sw, bias, N, y, ws=None):
+    wsp, wsb = _ws(ws)
+    _check(lib().ql_w8a8_gemm(_p(xq_kernel), _p(sx), M, K, _p(wq_kernel), _p(sw), _p(bias), N, _p(y),
+                              _ld(y) if M else N, wsp, wsb, _stream()))
+
+
+def ql_w4a8_gemm(xq_kernel, sx, M, K, w4_kernel, group, bias, N, y, ws=None):
+    wsp, wsb = _ws(ws)
+    _check(lib().ql_w4a8_gemm(_p(xq_kernel), _p(sx), M, K, _p(w4_kernel), group, _p(bias), N, _p(y),
+                              _ld(y) if M else N, wsp, wsb, _stream()))
+
+
+def ql_w8a8_gemm_acc_i32(xq_kernel, M, K, wq_kernel, N, acc, ws=None):
+    _want(acc, torch.int32, "acc")
+    wsp, wsb = _ws(ws)
+    _check(lib().ql_w8a8_gemm_acc_i32(_p(xq_kernel), M, K, _p(wq_kernel), N, _p(acc), wsp, wsb, _stream()))
+
+
+def ql_w4a8_gemm_acc_i32(xq_kernel, M, K, w4_kernel, group, N, acc, partials=None, row0=0, nrows=0, ws=None):
+    _want(acc, torch.int32, "acc")
+    wsp, wsb = _ws(ws)
+    _check(lib().ql_w4a8_gemm_acc_i32(_p(xq_kernel), M, K, _p(w4_kernel), group, N, _p(acc), _p(partials), row0,
+                                      nrows, wsp, wsb, _stream()))

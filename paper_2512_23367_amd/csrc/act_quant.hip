@@ -1,0 +1,176 @@
+// Per-token dynamic int8 activation quantization (paper Eq. 1-2 with n = 8; one scale per token
+// over its whole feature dimension, Preliminary section) for gfx950.
+//
+// One workgroup per token.  The row is read once: each lane keeps its 16-element chunks in
+// registers, the row maximum is reduced across the wavefronts, then the codes are produced from
+// the registers and written both row-major and/or in the GEMM's tile order.
+//
+// Arithmetic (every step a single correctly rounded fp32 operation):
+//   amax = max_k |x|            sx = amax / 127          inv = 127 / amax
+//   code = clamp(rne(x * inv), -127, 127)                (all-zero token: sx = 1, codes 0)
+#include "common.h"
+
+namespace ql {
+namespace {
+
+constexpr int CHUNK = 16;               // elements per lane per step: 32 B in, 16 B out
+
+struct alignas(16) Half16 {
+    uint4 lo, hi;                       // 16 fp16 values
+};
+
+__device__ inline unsigned abs_max_bits(const Half16 &v, unsigned m)
+{
+    // |h| as an integer is monotonic in |value| for finite fp16, so the maximum can be taken on bits
+    const unsigned w[8] = {v.lo.x, v.lo.y, v.lo.z, v.lo.w, v.hi.x, v.hi.y, v.hi.z, v.hi.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        m = max(m, w[i] & 0x7fffu);
+        m = max(m, (w[i] >> 16) & 0x7fffu);
+    }
+    return m;
+}
+
+__device__ inline float half_bits_to_float(unsigned bits)
+{
+    return __half2float(__ushort_as_half((unsigned short)bits));
+}
+
+__device__ inline int quant_code(unsigned hbits, float inv)
+{
+    const float t = half_bits_to_float(hbits) * inv;    // one fp32 multiply
+    float r = rintf(t);                                 // round half to even
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+__device__ inline unsigned quant_word(unsigned w0, unsigned w1, float inv)   // 4 halves -> 4 codes
+{
+    const unsigned a = quant_code(w0 & 0xffffu, inv) & 0xff;
+    const unsigned b = quant_code(w0 >> 16, inv) & 0xff;
+    const unsigned c = quant_code(w1 & 0xffffu, inv) & 0xff;
+    const unsigned d = quant_code(w1 >> 16, inv) & 0xff;
+    return a | (b << 8) | (c << 16) | (d << 24);
+}
+
+__device__ inline uint4 quant_chunk(const Half16 &v, float inv)
+{
+    uint4 q;
+    q.x = quant_word(v.lo.x, v.lo.y, inv);
+    q.y = quant_word(v.lo.z, v.lo.w, inv);
+    q.z = quant_word(v.hi.x, v.hi.y, inv);
+    q.w = quant_word(v.hi.z, v.hi.w, inv);
+    return q;
+}
+
+// Reduces `m` over the workgroup (blockDim.x a multiple of 64, at most 1024).
+__device__ inline unsigned block_max(unsigned m, unsigned *lds)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        m = max(m, (unsigned)__shfl_xor((int)m, off, 64));
+    const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    if ((threadIdx.x & 63) == 0) lds[wave] = m;
+    __syncthreads();
+    unsigned r = 0;
+    for (int i = 0; i < nwaves; ++i) r = max(r, lds[i]);
+    return r;
+}
+
+// NIT: chunks per lane kept in registers (blockDim.x * NIT * 16 >= K); NIT == 0: re-read the row.
+template <int NIT>
+__global__ void act_quant_kernel(const __half *__restrict__ x, int64_t ldx, int K,
+                                 int8_t *__restrict__ xq_rm, int8_t *__restrict__ xq_kl,
+                                 float *__restrict__ sx)
+{
+    __shared__ unsigned red[16];
+    const int m = blockIdx.x;
+    const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)m * ldx);
+    const int nchunks = K / CHUNK;
+
+    Half16 v[NIT > 0 ? NIT : 1];
+    unsigned mx = 0;
+    if (NIT > 0) {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = threadIdx.x + i * blockDim.x;
+            if (c < nchunks) {
+                v[i] = row[c];
+                mx = abs_max_bits(v[i], mx);
+            }
+        }
+    } else {
+        for (int c = threadIdx.x; c < nchunks; c += blockDim.x) mx = abs_max_bits(row[c], mx);
+    }
+    mx = block_max(mx, red);
+
+    const float amax = half_bits_to_float(mx);
+    const bool zero = (mx == 0);
+    const float scale = zero ? 1.0f : amax / 127.0f;    // IEEE fp32 division
+    const float inv = zero ? 0.0f : 127.0f / amax;      // IEEE fp32 division
+    if (threadIdx.x == 0) sx[m] = scale;
+
+    auto emit = [&](int c, const Half16 &h) {
+        const uint4 q = quant_chunk(h, inv);
+        if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK) = q;
+        if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = q;
+    };
+    if (NIT > 0) {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = threadIdx.x + i * blockDim.x;
+            if (c < nchunks) emit(c, v[i]);
+        }
+    } else {
+        for (int c = threadIdx.x; c < nchunks; c += blockDim.x) emit(c, row[c]);
+    }
+}
+
+__global__ void act_repack_kernel(const int8_t *__restrict__ xq_rm, int M, int K,
+                                  int8_t *__restrict__ xq_kl)
+{
+    const int nchunks = K / CHUNK;
+    const size_t total = (size_t)M * nchunks;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int m = (int)(i / nchunks), c = (int)(i % nchunks);
+        const uint4 q = *reinterpret_cast<const uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK);
+        *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = q;
+    }
+}
+
+}  // namespace
+
+int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, int8_t *xq_kl,
+                     float *sx, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    const int nchunks = K / CHUNK;
+    int threads = round_up(nchunks < 64 ? 64 : nchunks, 64);
+    if (threads > 256) threads = 256;
+    const int nit = ceil_div(nchunks, threads);
+    dim3 grid(M), block(threads);
+    if (nit <= 1)
+        hipLaunchKernelGGL(act_quant_kernel<1>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
+    else if (nit <= 2)
+        hipLaunchKernelGGL(act_quant_kernel<2>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
+    else if (nit <= 4)
+        hipLaunchKernelGGL(act_quant_kernel<4>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
+    else if (nit <= 8)
+        hipLaunchKernelGGL(act_quant_kernel<8>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
+    else
+        hipLaunchKernelGGL(act_quant_kernel<0>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
+    return check_hip(hipGetLastError(), "act_quant launch");
+}
+
+int launch_act_repack(const int8_t *xq_rm, int M, int K, int8_t *xq_kl, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    const size_t total = (size_t)M * (K / CHUNK);
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(act_repack_kernel, dim3(blocks), dim3(256), 0, st, xq_rm, M, K, xq_kl);
+    return check_hip(hipGetLastError(), "act_repack launch");
+}
+
+}  // namespace ql

@@ -1,0 +1,338 @@
+// C ABI of libqlinear: argument validation and dispatch.  Declarations and the meaning of every
+// argument are in include/qlinear.h; nothing here allocates, frees or synchronizes.
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "common.h"
+
+namespace ql {
+
+static thread_local char g_err[512] = "";
+static int g_variant = 0;
+
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int check_hip(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return QL_OK;
+    return fail(QL_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+namespace {
+
+constexpr int MAX_K = 131072;          // 131072 * 127 * 127 < 2^31: no int32 accumulator can overflow
+constexpr int DECODE_MAX_M = 32;
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_bits(int bits, int group)
+{
+    if (bits == 8 && group == 0) return QL_OK;
+    if (bits == 4 && group == 128) return QL_OK;
+    return fail(QL_ERR_UNSUPPORTED, "unsupported (bits, group) = (%d, %d): use (8, 0) or (4, 128)", bits, group);
+}
+
+int check_nk(int N, int K, int bits)
+{
+    if (N <= 0 || K <= 0) return fail(QL_ERR_SHAPE, "N and K must be positive (N=%d K=%d)", N, K);
+    const int kmul = bits == 4 ? 128 : 64;
+    if (K % kmul) return fail(QL_ERR_SHAPE, "K=%d must be a multiple of %d for %d-bit weights", K, kmul, bits);
+    if (K > MAX_K) return fail(QL_ERR_UNSUPPORTED, "K=%d exceeds %d (int32 accumulator range)", K, MAX_K);
+    if ((double)round_up(N, TILE_ROWS) * K >= 2147483648.0)
+        return fail(QL_ERR_UNSUPPORTED, "ceil32(N)*K must be below 2^31 (N=%d K=%d)", N, K);
+    return QL_OK;
+}
+
+int check_mk(int M, int K)
+{
+    if (M < 0) return fail(QL_ERR_SHAPE, "M must be non-negative (M=%d)", M);
+    if (K <= 0 || K % 64) return fail(QL_ERR_SHAPE, "K=%d must be a positive multiple of 64", K);
+    if (K > MAX_K) return fail(QL_ERR_UNSUPPORTED, "K=%d exceeds %d", K, MAX_K);
+    if ((double)round_up(M, TILE_ROWS) * K >= 2147483648.0)
+        return fail(QL_ERR_UNSUPPORTED, "ceil32(M)*K must be below 2^31 (M=%d K=%d)", M, K);
+    return QL_OK;
+}
+
+struct WsLayout {
+    size_t xq_off, sx_off, total;
+};
+
+WsLayout ws_layout(int M, int K)
+{
+    WsLayout l;
+    l.xq_off = 0;
+    l.sx_off = (act_kernel_bytes(M, K) + 255) & ~(size_t)255;
+    l.total = l.sx_off + (((size_t)M * sizeof(float) + 255) & ~(size_t)255);
+    return l;
+}
+
+int check_out(const void *y, int64_t ldy, int N)
+{
+    if (!y) return fail(QL_ERR_NULL, "y is NULL");
+    if (!aligned(y, 16)) return fail(QL_ERR_ALIGN, "y must be 16-byte aligned");
+    if (ldy < N || ldy % 8) return fail(QL_ERR_ALIGN, "ldy=%lld must be >= N and a multiple of 8", (long long)ldy);
+    return QL_OK;
+}
+
+int run_gemm(GemmArgs &a, hipStream_t st)
+{
+    if (a.M == 0) return QL_OK;
+    int variant = g_variant;
+    if (variant == 0 && a.M <= DECODE_MAX_M) variant = 100;
+    if (variant >= 100) {
+        if (a.M > DECODE_MAX_M)
+            return fail(QL_ERR_UNSUPPORTED, "decode kernels take at most %d tokens (M=%d)", DECODE_MAX_M, a.M);
+        return launch_gemm_decode(a, variant, st);
+    }
+    return launch_gemm_prefill(a, variant, st);
+}
+
+int gemm_common(const int8_t *xq, const float *sx, int M, int K, const void *wq, const float *sw, int bits,
+                int group, const void *bias, int N, void *y, int64_t ldy, void *ws, size_t ws_bytes,
+                hipStream_t st)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_nk(N, K, bits));
+    if (!xq || !sx || !wq || (bits == 8 && !sw)) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!aligned(xq, 256) || !aligned(wq, 256) || !aligned(sx, 16) || (sw && !aligned(sw, 16)) ||
+        (bias && !aligned(bias, 16)))
+        return fail(QL_ERR_ALIGN, "xq/wq need 256-byte, sx/sw/bias 16-byte alignment");
+    QL_TRY(check_out(y, ldy, N));
+    (void)ws;
+    (void)ws_bytes;
+    GemmArgs a = {};
+    a.xq = xq;
+    a.sx = sx;
+    a.wq = wq;
+    a.sw = sw;
+    a.bias = static_cast<const __half *>(bias);
+    a.y = static_cast<__half *>(y);
+    a.ldy = ldy;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.bits = bits;
+    a.group = group;
+    a.ws = ws;
+    a.ws_bytes = ws_bytes;
+    return run_gemm(a, st);
+}
+
+int linear_common(const void *x, int64_t ldx, int M, int K, const void *wq, const float *sw, int bits, int group,
+                  const void *bias, int N, void *y, int64_t ldy, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_nk(N, K, bits));
+    if (M == 0) return QL_OK;
+    if (!x || !ws) return fail(QL_ERR_NULL, "x or ws is NULL");
+    if (!aligned(x, 16) || ldx < K || ldx % 8)
+        return fail(QL_ERR_ALIGN, "x must be 16-byte aligned, ldx >= K and a multiple of 8 (ldx=%lld)", (long long)ldx);
+    if (!aligned(ws, 256)) return fail(QL_ERR_ALIGN, "ws must be 256-byte aligned");
+    const WsLayout l = ws_layout(M, K);
+    if (ws_bytes < l.total)
+        return fail(QL_ERR_WORKSPACE, "workspace too small: %zu < %zu bytes", ws_bytes, l.total);
+    int8_t *xq = static_cast<int8_t *>(ws) + l.xq_off;
+    float *sx = reinterpret_cast<float *>(static_cast<char *>(ws) + l.sx_off);
+    // validate the GEMM's arguments before the first launch so a failing call has no side effects
+    if (!wq || (bits == 8 && !sw)) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!aligned(wq, 256) || (sw && !aligned(sw, 16)) || (bias && !aligned(bias, 16)))
+        return fail(QL_ERR_ALIGN, "wq needs 256-byte, sw/bias 16-byte alignment");
+    QL_TRY(check_out(y, ldy, N));
+    QL_TRY(launch_act_quant(static_cast<const __half *>(x), ldx, M, K, nullptr, xq, sx, st));
+    return gemm_common(xq, sx, M, K, wq, sw, bits, group, bias, N, y, ldy, ws, ws_bytes, st);
+}
+
+}  // namespace
+}  // namespace ql
+
+using namespace ql;
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int ql_version(void) { return 100; }
+
+const char *ql_last_error(void) { return g_err; }
+
+int ql_set_kernel_variant(int variant)
+{
+    if (variant < 0 || (variant > 5 && variant < 100) || variant > 101)
+        return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);
+    g_variant = variant;
+    return QL_OK;
+}
+
+int ql_weight_bytes(int N, int K, int bits, int group, size_t *canonical, size_t *scales, size_t *kernel)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_nk(N, K, bits));
+    if (bits == 8) {
+        if (canonical) *canonical = (size_t)N * K;
+        if (scales) *scales = (size_t)N * sizeof(float);
+        if (kernel) *kernel = w8_kernel_bytes(N, K);
+    } else {
+        if (canonical) *canonical = (size_t)N * K / 2;
+        if (scales) *scales = (size_t)N * (K / group) * sizeof(__half);
+        if (kernel) *kernel = w4_kernel_bytes(N, K, group);
+    }
+    return QL_OK;
+}
+
+int ql_act_kernel_bytes(int M, int K, size_t *bytes)
+{
+    QL_TRY(check_mk(M, K));
+    if (!bytes) return fail(QL_ERR_NULL, "bytes is NULL");
+    *bytes = act_kernel_bytes(M, K);
+    return QL_OK;
+}
+
+int ql_workspace_bytes(int M, int N, int K, int bits, size_t *bytes)
+{
+    if (bits != 8 && bits != 4) return fail(QL_ERR_UNSUPPORTED, "bits must be 8 or 4");
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_nk(N, K, bits));
+    if (!bytes) return fail(QL_ERR_NULL, "bytes is NULL");
+    *bytes = ws_layout(M, K).total;
+    return QL_OK;
+}
+
+int ql_quant_act_per_token(const void *x, int64_t ldx, int M, int K, int8_t *xq_rowmajor, int8_t *xq_kernel,
+                           float *sx, void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    if (M == 0) return QL_OK;
+    if (!x || !sx || (!xq_rowmajor && !xq_kernel)) return fail(QL_ERR_NULL, "x, sx and one of the outputs are required");
+    if (!aligned(x, 16) || ldx < K || ldx % 8)
+        return fail(QL_ERR_ALIGN, "x must be 16-byte aligned, ldx >= K and a multiple of 8 (ldx=%lld)", (long long)ldx);
+    if ((xq_rowmajor && !aligned(xq_rowmajor, 16)) || (xq_kernel && !aligned(xq_kernel, 256)) || !aligned(sx, 4))
+        return fail(QL_ERR_ALIGN, "xq_rowmajor needs 16-byte, xq_kernel 256-byte alignment");
+    return launch_act_quant(static_cast<const __half *>(x), ldx, M, K, xq_rowmajor, xq_kernel, sx,
+                            static_cast<hipStream_t>(stream));
+}
+
+int ql_act_repack(const int8_t *xq_rowmajor, int M, int K, int8_t *xq_kernel, void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    if (M == 0) return QL_OK;
+    if (!xq_rowmajor || !xq_kernel) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!aligned(xq_rowmajor, 16) || !aligned(xq_kernel, 256))
+        return fail(QL_ERR_ALIGN, "xq_rowmajor needs 16-byte, xq_kernel 256-byte alignment");
+    return launch_act_repack(xq_rowmajor, M, K, xq_kernel, static_cast<hipStream_t>(stream));
+}
+
+int ql_quant_weight(const void *w, int N, int K, int bits, int group, void *wq_canonical, void *scales,
+                    void *wq_kernel, void *stream)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_nk(N, K, bits));
+    if (!w) return fail(QL_ERR_NULL, "w is NULL");
+    if (bits == 8 && !scales) return fail(QL_ERR_NULL, "scales is required for int8 weights");
+    if (!wq_canonical && !wq_kernel && !scales) return fail(QL_ERR_NULL, "no output requested");
+    if (!aligned(w, 16) || (wq_canonical && !aligned(wq_canonical, 16)) || (scales && !aligned(scales, 16)) ||
+        (wq_kernel && !aligned(wq_kernel, 256)))
+        return fail(QL_ERR_ALIGN, "w/wq_canonical/scales need 16-byte, wq_kernel 256-byte alignment");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (bits == 8)
+        return launch_weight_quant8(static_cast<const __half *>(w), N, K, static_cast<int8_t *>(wq_canonical),
+                                    static_cast<float *>(scales), static_cast<int8_t *>(wq_kernel), st);
+    return launch_weight_quant4(static_cast<const __half *>(w), N, K, group, static_cast<uint8_t *>(wq_canonical),
+                                static_cast<__half *>(scales), static_cast<uint8_t *>(wq_kernel), st);
+}
+
+int ql_export_canonical(const void *wq_kernel, int N, int K, int bits, int group, void *wq_canonical,
+                        void *scales, void *stream)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_nk(N, K, bits));
+    if (!wq_kernel || (!wq_canonical && !(bits == 4 && scales))) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!aligned(wq_kernel, 256) || (wq_canonical && !aligned(wq_canonical, 16)) || (scales && !aligned(scales, 2)))
+        return fail(QL_ERR_ALIGN, "wq_kernel needs 256-byte, wq_canonical 16-byte alignment");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (bits == 8)
+        return launch_export8(static_cast<const int8_t *>(wq_kernel), N, K, static_cast<int8_t *>(wq_canonical), st);
+    return launch_export4(static_cast<const uint8_t *>(wq_kernel), N, K, group, static_cast<uint8_t *>(wq_canonical),
+                          static_cast<__half *>(scales), st);
+}
+
+int ql_w8a8_linear(const void *x, int64_t ldx, int M, int K, const void *wq_kernel, const float *sw,
+                   const void *bias, int N, void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    return linear_common(x, ldx, M, K, wq_kernel, sw, 8, 0, bias, N, y, ldy, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+int ql_w4a8_linear(const void *x, int64_t ldx, int M, int K, const void *w4_kernel, int group, const void *bias,
+                   int N, void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    return linear_common(x, ldx, M, K, w4_kernel, nullptr, 4, group, bias, N, y, ldy, ws, ws_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
+int ql_w8a8_gemm(const int8_t *xq_kernel, const float *sx, int M, int K, const void *wq_kernel, const float *sw,
+                 const void *bias, int N, void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    return gemm_common(xq_kernel, sx, M, K, wq_kernel, sw, 8, 0, bias, N, y, ldy, ws, ws_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+int ql_w4a8_gemm(const int8_t *xq_kernel, const float *sx, int M, int K, const void *w4_kernel, int group,
+                 const void *bias, int N, void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream)
+{
+    return gemm_common(xq_kernel, sx, M, K, w4_kernel, nullptr, 4, group, bias, N, y, ldy, ws, ws_bytes,
+                       static_cast<hipStream_t>(stream));
+}
+
+static int acc_common(const int8_t *xq, int M, int K, const void *wq, int bits, int group, int N, int32_t *acc,
+                      int32_t *partials, int row0, int nrows, void *ws, size_t ws_bytes, hipStream_t st)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_nk(N, K, bits));
+    if (!xq || !wq || !acc) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!aligned(xq, 256) || !aligned(wq, 256) || !aligned(acc, 16) || (partials && !aligned(partials, 4)))
+        return fail(QL_ERR_ALIGN, "xq/wq need 256-byte, acc 16-byte alignment");
+    if (partials && (row0 < 0 || nrows < 0 || row0 + nrows > M))
+        return fail(QL_ERR_SHAPE, "partials row range [%d, %d) outside [0, %d)", row0, row0 + nrows, M);
+    GemmArgs a = {};
+    a.xq = xq;
+    a.wq = wq;
+    a.acc = acc;
+    a.partials = partials;
+    a.row0 = row0;
+    a.nrows = partials ? nrows : 0;
+    a.M = M;
+    a.N = N;
+    a.K = K;
+    a.bits = bits;
+    a.group = group;
+    a.ws = ws;
+    a.ws_bytes = ws_bytes;
+    return run_gemm(a, st);
+}
+
+int ql_w8a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *wq_kernel, int N, int32_t *acc,
+                         void *ws, size_t ws_bytes, void *stream)
+{
+    return acc_common(xq_kernel, M, K, wq_kernel, 8, 0, N, acc, nullptr, 0, 0, ws, ws_bytes,
+                      static_cast<hipStream_t>(stream));
+}
+
+int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_kernel, int group, int N,
+                         int32_t *acc, int32_t *partials, int row0, int nrows, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    return acc_common(xq_kernel, M, K, w4_kernel, 4, group, N, acc, partials, row0, nrows, ws, ws_bytes,
+                      static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,386 @@
+// Prefill GEMM + dequantization epilogue of the W8A8 / W4A8 linear layer for gfx950
+// (the int8 / W4A8 matrix multiplication and "dequantization logic" of the paper's
+// inference framework, Method section; integer accumulation, Y = XW).
+//
+// Both operands arrive in tile order (32 rows x 32 k per 1024-byte tile, already in the lane order
+// of the 32x32x32 int8 matrix instruction), so:
+//   * global -> LDS is one `buffer_load_dwordx4 ... lds` per tile per wavefront: 1024 contiguous
+//     bytes in, 1024 contiguous LDS bytes out, no registers, no swizzle;
+//   * LDS -> register is one `ds_read_b128` per tile with lane-linear addresses (conflict free).
+// The weight tile is the instruction's first operand and the activation tile its second, so a
+// lane ends up with 4 consecutive output channels of one token per accumulator quad, which makes
+// the fp16 stores 8 bytes wide.
+//
+// Pipeline: STAGES LDS buffers of KBS k-blocks each; loads for stage it+STAGES-1 are issued while
+// stage it is multiplied; one workgroup barrier per stage.  8 wavefronts (two per SIMD) so that one
+// wavefront's barrier / LDS waits are covered by the other's matrix instructions.
+//
+// W4A8: weight tiles hold nibbles; the unpack (shift + mask, giving 16 * code in each byte) sits
+// between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
+// an fp32 accumulator with the group's scale.
+#include "common.h"
+
+namespace ql {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+
+enum { EPI_F16 = 0, EPI_ACC = 1 };
+
+struct PrefillParams {
+    const int8_t *xq;
+    const void *wq;
+    const float *sx;
+    const float *sw;
+    const __half *wscales;   // W4A8: [G][Npad] fp16
+    const __half *bias;
+    __half *y;
+    int64_t ldy;
+    int32_t *acc;
+    int32_t *partials;
+    int row0, nrows;
+    int M, N, K, Npad;
+    int tiles_m, tiles_n;
+    unsigned x_bytes, w_bytes;
+};
+
+#define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+template <int N>
+__device__ inline void wait_vmcnt()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+// Hardware hands consecutive workgroup ids to the 8 XCDs in turn; give every XCD one contiguous
+// range of logical tiles, ordered so that tiles running together share activation and weight
+// strips in that XCD's L2.
+__device__ inline void tile_coords(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int nt = tiles_m * tiles_n;
+    const int xcd = bid % 8, idx = bid / 8;
+    const int per = nt / 8, rem = nt % 8;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
+    constexpr int GROUP = 8;
+    const int per_group = GROUP * tiles_n;
+    const int g = logical / per_group, in_g = logical % per_group;
+    const int first_m = g * GROUP;
+    const int gsize = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
+    tm = first_m + in_g % gsize;
+    tn = in_g / gsize;
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(PrefillParams p)
+{
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int TMB = WAVES_M * WM;                    // activation row-blocks per workgroup tile
+    constexpr int TNB = WAVES_N * WN;                    // weight row-blocks per workgroup tile
+    constexpr int XFR = TMB * KBS;                       // 1024-byte fragments per stage: activations
+    constexpr int WFR = W4 ? TNB * KBS / 2 : TNB * KBS;  //                               weights
+    constexpr int WKB = W4 ? KBS / 2 : KBS;              // weight fragments per row-block per stage
+    constexpr int XOFF = 0, WOFF = XFR * 1024;
+    constexpr int STAGE_BYTES = (XFR + WFR) * 1024;
+    static_assert(XFR % NW == 0 && WFR % NW == 0, "fragments must divide evenly over the wavefronts");
+    constexpr int XL = XFR / NW, WL = WFR / NW;          // loads per wavefront per stage
+    constexpr int LPW = XL + WL;
+    static_assert(!W4 || KBS == 4, "W4A8: one stage is one scale group (128 k)");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+
+    int tm, tn;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+
+    const int KB = p.K / 32;                             // k-blocks
+    const int nstages = KB / KBS;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.w_bytes);
+    const unsigned voff = lane * 16;
+
+    // Fragment f of a stage lives at LDS offset f*1024 and, in global memory, at
+    //   row-block base + (stage * fragments-per-row-block + f % fragments-per-row-block) * 1024.
+    // Wavefront w loads activation fragments [w*XL, (w+1)*XL) and weight fragments [w*WL, (w+1)*WL).
+    auto issue_stage = [&](int s) {
+        const bool live = s < nstages;
+        char *buf = smem + (s % STAGES) * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < XL; ++i) {
+            const int f = wave * XL + i;
+            const int mb = f / KBS, kb = f % KBS;
+            unsigned off = ((unsigned)(tm * TMB + mb) * KB + s * KBS + kb) * 1024u;
+            if (!live) off = 0xFFFFF000u;                // beyond the buffer: the load returns nothing
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(buf + XOFF + f * 1024), 16, voff, off, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WL; ++i) {
+            const int f = wave * WL + i;
+            const int nb = f / WKB, kb = f % WKB;
+            unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + s * WKB + kb) * 1024u;
+            if (!live) off = 0xFFFFF000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + WOFF + f * 1024), 16, voff, off, 0, 0);
+        }
+    };
+
+    v16i acc[WN][WM];
+#pragma unroll
+    for (int i = 0; i < WN; ++i)
+#pragma unroll
+        for (int j = 0; j < WM; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // W4A8 only: fp32 accumulators over groups (EPI_F16) or integer totals (EPI_ACC)
+    float accf[W4 ? WN : 1][W4 ? WM : 1][16];
+    int tot[(W4 && EPI == EPI_ACC) ? WN : 1][(W4 && EPI == EPI_ACC) ? WM : 1][16];
+    if (W4) {
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int j = 0; j < WM; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    accf[i][j][r] = 0.0f;
+                    if (EPI == EPI_ACC) tot[i][j][r] = 0;
+                }
+    }
+
+    // prologue: STAGES-1 stages in flight
+#pragma unroll
+    for (int s = 0; s < STAGES - 1; ++s) issue_stage(s);
+
+    const int n_lane0 = (tn * TNB + wn * WN) * 32 + 4 * (lane >> 5);   // + bi*32 + 8*q + (r%4)
+    const int m_lane0 = (tm * TMB + wm * WM) * 32 + (lane & 31);       // + bj*32
+
+    for (int it = 0; it < nstages; ++it) {
+        wait_vmcnt<(STAGES - 2) * LPW>();        // this wavefront's loads of stage `it` have landed
+        __builtin_amdgcn_s_barrier();            // ... everyone's; and stage it-1 is fully consumed
+        issue_stage(it + STAGES - 1);            // refills the buffer stage it-1 used
+
+        const char *buf = smem + (it % STAGES) * STAGE_BYTES;
+        if (!W4) {
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb) {
+                v4i wf[WN], xf[WM];
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+                    wf[i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb) * 1024 + lane * 16);
+#pragma unroll
+                for (int j = 0; j < WM; ++j)
+                    xf[j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+#pragma unroll
+                    for (int j = 0; j < WM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
+            }
+        } else {
+            // group scales of this stage (= group `it`): 4 consecutive channels per accumulator quad
+            h4 sg[WN][4];
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n_lane0 + i * 32 + 8 * q;     // whole 32-blocks are inside or outside Npad
+                    sg[i][q] = (n < p.Npad) ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)it * p.Npad + n)
+                                            : h4{0, 0, 0, 0};
+                }
+#pragma unroll
+            for (int kp = 0; kp < KBS / 2; ++kp) {
+                v4i wp[WN];
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+                    wp[i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * WKB + kp) * 1024 + lane * 16);
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int kb = 2 * kp + h;
+                    v4i xf[WM];
+#pragma unroll
+                    for (int j = 0; j < WM; ++j)
+                        xf[j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
+#pragma unroll
+                    for (int i = 0; i < WN; ++i) {
+                        const unsigned w0 = (unsigned)wp[i][2 * h], w1 = (unsigned)wp[i][2 * h + 1];
+                        v4i wf;
+                        wf[0] = (int)((w0 << 4) & 0xF0F0F0F0u);
+                        wf[1] = (int)(w0 & 0xF0F0F0F0u);
+                        wf[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
+                        wf[3] = (int)(w1 & 0xF0F0F0F0u);
+#pragma unroll
+                        for (int j = 0; j < WM; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[j], acc[i][j], 0, 0, 0);
+                    }
+                }
+            }
+            // fold the group's integer partial (16x the true value) into the running sums
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int j = 0; j < WM; ++j) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if (EPI == EPI_F16) {
+                            accf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], (float)sg[i][r / 4][r % 4], accf[i][j][r]);
+                        } else {
+                            tot[i][j][r] += acc[i][j][r];
+                            if (p.partials) {
+                                const int m = m_lane0 + j * 32, n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
+                                if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
+                                    p.partials[((size_t)(m - p.row0) * nstages + it) * p.N + n] = acc[i][j][r] >> 4;
+                            }
+                        }
+                        acc[i][j][r] = 0;
+                    }
+                }
+        }
+    }
+    wait_vmcnt<0>();   // drain the dead tail loads before the LDS is released
+
+    // ---------------------------------------------------------------- epilogue
+#pragma unroll
+    for (int j = 0; j < WM; ++j) {
+        const int m = m_lane0 + j * 32;
+        if (m >= p.M) continue;
+        float sxm = 0.0f;
+        if (EPI == EPI_F16) sxm = p.sx[m] * (W4 ? 0.0625f : 1.0f);
+#pragma unroll
+        for (int i = 0; i < WN; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n_lane0 + i * 32 + 8 * q;
+                if (n >= p.N) continue;
+                if (EPI == EPI_ACC) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < p.N)
+                            p.acc[(size_t)m * p.N + n + e] = W4 ? (tot[i][j][4 * q + e] >> 4) : acc[i][j][4 * q + e];
+                    continue;
+                }
+                float v[4];
+                if (n + 3 < p.N) {
+                    float b[4] = {0.f, 0.f, 0.f, 0.f};
+                    if (p.bias) {
+                        const h4 bb = *reinterpret_cast<const h4 *>(p.bias + n);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) b[e] = (float)bb[e];
+                    }
+                    if (W4) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b[e]);
+                    } else {
+                        const float4 s4 = *reinterpret_cast<const float4 *>(p.sw + n);
+                        const float s[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            v[e] = __builtin_fmaf((float)acc[i][j][4 * q + e] * sxm, s[e], b[e]);
+                    }
+                    h4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = (_Float16)v[e];
+                    *reinterpret_cast<h4 *>(p.y + (size_t)m * p.ldy + n) = o;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (n + e >= p.N) break;
+                        const float b = p.bias ? __half2float(p.bias[n + e]) : 0.0f;
+                        float val;
+                        if (W4) val = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b);
+                        else val = __builtin_fmaf((float)acc[i][j][4 * q + e] * sxm, p.sw[n + e], b);
+                        p.y[(size_t)m * p.ldy + n + e] = __float2half_rn(val);
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI>
+int launch_one(const GemmArgs &a, hipStream_t st)
+{
+    constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
+    constexpr int XFR = WAVES_M * WM * KBS;
+    constexpr int WFR = W4 ? WAVES_N * WN * KBS / 2 : WAVES_N * WN * KBS;
+    constexpr int LDS = (XFR + WFR) * 1024 * STAGES;
+    static_assert(LDS <= 160 * 1024, "LDS budget");
+    static_assert((STAGES - 2) * (XFR + WFR) / (WAVES_M * WAVES_N) <= 63, "vmcnt range");
+    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS),
+                         "hipFuncSetAttribute(max dynamic LDS)"));
+        attr_set = true;
+    }
+    PrefillParams p;
+    p.xq = a.xq;
+    p.wq = a.wq;
+    p.sx = a.sx;
+    p.sw = a.sw;
+    p.bias = a.bias;
+    p.y = a.y;
+    p.ldy = a.ldy;
+    p.acc = a.acc;
+    p.partials = a.partials;
+    p.row0 = a.row0;
+    p.nrows = a.nrows;
+    p.M = a.M;
+    p.N = a.N;
+    p.K = a.K;
+    p.Npad = round_up(a.N, TILE_ROWS);
+    p.tiles_m = ceil_div(a.M, TM);
+    p.tiles_n = ceil_div(a.N, TN);
+    p.x_bytes = (unsigned)act_kernel_bytes(a.M, a.K);
+    p.w_bytes = (unsigned)(W4 ? w4_codes_bytes(a.N, a.K) : w8_kernel_bytes(a.N, a.K));
+    p.wscales = W4 ? reinterpret_cast<const __half *>(static_cast<const char *>(a.wq) + w4_scales_offset(a.N, a.K))
+                   : nullptr;
+    const int grid = p.tiles_m * p.tiles_n;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * 64), LDS, st, p);
+    return check_hip(hipGetLastError(), "gemm_prefill launch");
+}
+
+template <bool W4, int EPI>
+int dispatch(const GemmArgs &a, int variant, hipStream_t st)
+{
+    if (W4) {
+        // 256 tokens x 128 channels, 8 wavefronts of 64x64: int32 + fp32 accumulators fit 256 registers
+        return launch_one<4, 2, 2, 2, 4, 3, true, EPI>(a, st);
+    }
+    switch (variant) {
+    case 0:
+    case 1:   // 256x256, 8 wavefronts of 128 tokens x 64 channels, 64 k per stage, 4 stages
+        return launch_one<2, 4, 4, 2, 2, 4, false, EPI>(a, st);
+    case 2:   // 256x256, 8 wavefronts of 64 tokens x 128 channels
+        return launch_one<4, 2, 2, 4, 2, 4, false, EPI>(a, st);
+    case 3:   // 256x256, 4 wavefronts of 128x128
+        return launch_one<2, 2, 4, 4, 2, 4, false, EPI>(a, st);
+    case 4:   // 128x128, 4 wavefronts of 64x64 (two workgroups per CU)
+        return launch_one<2, 2, 2, 2, 2, 4, false, EPI>(a, st);
+    case 5:   // 256x256, 8 wavefronts, 128 k per stage, 2 stages
+        return launch_one<2, 4, 4, 2, 4, 2, false, EPI>(a, st);
+    default:
+        return fail(QL_ERR_UNSUPPORTED, "unknown prefill kernel variant %d", variant);
+    }
+}
+
+}  // namespace
+
+int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st)
+{
+    if (a.M == 0) return QL_OK;
+    const bool w4 = a.bits == 4;
+    const bool dump = a.acc != nullptr;
+    if (w4) return dump ? dispatch<true, EPI_ACC>(a, variant, st) : dispatch<true, EPI_F16>(a, variant, st);
+    return dump ? dispatch<false, EPI_ACC>(a, variant, st) : dispatch<false, EPI_F16>(a, variant, st);
+}
+
+}  // namespace ql

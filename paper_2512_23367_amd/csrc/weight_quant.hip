@@ -1,0 +1,213 @@
+// Offline weight quantization (paper Eq. 1-2; per-output-channel scales for int8, group-wise
+// scales along K for int4 -- Preliminary, granularity paragraph) and the conversion to and from the
+// GEMM's tile order (the "weight layout" step of the paper's inference framework), for gfx950.
+//
+//   int8: s[n] = amax_n / 127 (fp32; 1 if zero);       code = clamp(rne(w / s[n]), +-127)
+//   int4: s[n,g] = fp16(amax_{n,g} / 7) (1 if zero);   code = clamp(rne(w / float(s[n,g])), +-7)
+//         canonical packing: two's-complement nibbles, even k in bits 3:0, odd k in bits 7:4
+// Not on the timed path: one workgroup per output channel, the row is read twice.
+#include "common.h"
+
+namespace ql {
+namespace {
+
+constexpr int CHUNK = 16;
+
+struct alignas(16) Half16 {
+    uint4 lo, hi;
+};
+
+__device__ inline void unpack16(const Half16 &v, unsigned short (&h)[16])
+{
+    const unsigned w[8] = {v.lo.x, v.lo.y, v.lo.z, v.lo.w, v.hi.x, v.hi.y, v.hi.z, v.hi.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        h[2 * i] = (unsigned short)(w[i] & 0xffffu);
+        h[2 * i + 1] = (unsigned short)(w[i] >> 16);
+    }
+}
+
+__device__ inline unsigned amax_bits16(const unsigned short (&h)[16])
+{
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) m = max(m, (unsigned)(h[i] & 0x7fffu));
+    return m;
+}
+
+__device__ inline float hbits_to_float(unsigned short b) { return __half2float(__ushort_as_half(b)); }
+
+__device__ inline int code_div(unsigned short hbits, float scale, float lim)
+{
+    const float t = hbits_to_float(hbits) / scale;   // IEEE fp32 division by the stored scale
+    float r = rintf(t);
+    r = fminf(fmaxf(r, -lim), lim);
+    return (int)r;
+}
+
+__global__ void weight_quant8_kernel(const __half *__restrict__ w, int N, int K,
+                                     int8_t *__restrict__ canon, float *__restrict__ scales,
+                                     int8_t *__restrict__ kl)
+{
+    __shared__ unsigned red[4];
+    const int n = blockIdx.x;
+    const int nchunks = K / CHUNK;
+    if (n >= N) {   // padding rows of the kernel layout
+        if (kl)
+            for (int c = threadIdx.x; c < nchunks; c += blockDim.x)
+                *reinterpret_cast<uint4 *>(kl + tile_offset_i8(n, c * CHUNK, K)) = make_uint4(0, 0, 0, 0);
+        return;
+    }
+    const Half16 *row = reinterpret_cast<const Half16 *>(w + (size_t)n * K);
+    unsigned mx = 0;
+    for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
+        unsigned short h[16];
+        unpack16(row[c], h);
+        mx = max(mx, amax_bits16(h));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    mx = max(max(red[0], red[1]), max(red[2], red[3]));
+
+    float s = hbits_to_float((unsigned short)mx) / 127.0f;
+    if (s == 0.0f) s = 1.0f;
+    if (threadIdx.x == 0 && scales) scales[n] = s;
+
+    for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
+        unsigned short h[16];
+        unpack16(row[c], h);
+        unsigned q[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) q[i / 4] |= (unsigned)(code_div(h[i], s, 127.0f) & 0xff) << (8 * (i % 4));
+        const uint4 o = make_uint4(q[0], q[1], q[2], q[3]);
+        if (canon) *reinterpret_cast<uint4 *>(canon + (size_t)n * K + (size_t)c * CHUNK) = o;
+        if (kl) *reinterpret_cast<uint4 *>(kl + tile_offset_i8(n, c * CHUNK, K)) = o;
+    }
+}
+
+// group == 128: eight consecutive lanes hold one group.
+__global__ void weight_quant4_kernel(const __half *__restrict__ w, int N, int Npad, int K,
+                                     uint8_t *__restrict__ canon, __half *__restrict__ scales,
+                                     uint8_t *__restrict__ kl_codes, __half *__restrict__ kl_scales)
+{
+    const int n = blockIdx.x;
+    const int nchunks = K / CHUNK;
+    const int G = K / 128;
+    for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
+        unsigned short h[16];
+        if (n < N) {
+            unpack16(reinterpret_cast<const Half16 *>(w + (size_t)n * K)[c], h);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) h[i] = 0;
+        }
+        unsigned mx = amax_bits16(h);
+        mx = max(mx, (unsigned)__shfl_xor((int)mx, 1, 64));
+        mx = max(mx, (unsigned)__shfl_xor((int)mx, 2, 64));
+        mx = max(mx, (unsigned)__shfl_xor((int)mx, 4, 64));
+        const float s32 = hbits_to_float((unsigned short)mx) / 7.0f;   // IEEE fp32 division
+        __half s16 = __float2half_rn(s32);
+        if (__half2float(s16) == 0.0f) s16 = __float2half_rn(1.0f);
+        const float s = __half2float(s16);
+        const int g = c / 8;
+        if ((c % 8) == 0) {
+            if (n < N && scales) scales[(size_t)n * G + g] = s16;
+            if (kl_scales) kl_scales[(size_t)g * Npad + n] = s16;
+        }
+        int q[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) q[i] = code_div(h[i], s, 7.0f) & 0xf;
+        if (n < N && canon) {
+            unsigned lo = 0, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                lo |= (unsigned)(q[2 * i] | (q[2 * i + 1] << 4)) << (8 * i);
+                hi |= (unsigned)(q[8 + 2 * i] | (q[8 + 2 * i + 1] << 4)) << (8 * i);
+            }
+            *reinterpret_cast<uint2 *>(canon + (size_t)n * (K / 2) + (size_t)c * 8) = make_uint2(lo, hi);
+        }
+        if (kl_codes) {
+            unsigned w0 = 0, w1 = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                w0 |= (unsigned)q[i] << (4 * w4_nibble_pos(i));
+                w1 |= (unsigned)q[8 + i] << (4 * w4_nibble_pos(i));
+            }
+            *reinterpret_cast<uint2 *>(kl_codes + tile_offset_w4_word(n, c * CHUNK, K)) = make_uint2(w0, w1);
+        }
+    }
+}
+
+__global__ void export8_kernel(const int8_t *__restrict__ kl, int K, int8_t *__restrict__ canon)
+{
+    const int n = blockIdx.x;
+    for (int c = threadIdx.x; c < K / CHUNK; c += blockDim.x)
+        *reinterpret_cast<uint4 *>(canon + (size_t)n * K + (size_t)c * CHUNK) =
+            *reinterpret_cast<const uint4 *>(kl + tile_offset_i8(n, c * CHUNK, K));
+}
+
+__global__ void export4_kernel(const uint8_t *__restrict__ kl_codes, const __half *__restrict__ kl_scales,
+                               int Npad, int K, uint8_t *__restrict__ canon, __half *__restrict__ scales)
+{
+    const int n = blockIdx.x;
+    const int G = K / 128;
+    for (int c = threadIdx.x; c < K / CHUNK; c += blockDim.x) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(kl_codes + tile_offset_w4_word(n, c * CHUNK, K));
+        int q[16];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            q[i] = (v.x >> (4 * w4_nibble_pos(i))) & 0xf;
+            q[8 + i] = (v.y >> (4 * w4_nibble_pos(i))) & 0xf;
+        }
+        unsigned lo = 0, hi = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            lo |= (unsigned)(q[2 * i] | (q[2 * i + 1] << 4)) << (8 * i);
+            hi |= (unsigned)(q[8 + 2 * i] | (q[8 + 2 * i + 1] << 4)) << (8 * i);
+        }
+        if (canon) *reinterpret_cast<uint2 *>(canon + (size_t)n * (K / 2) + (size_t)c * 8) = make_uint2(lo, hi);
+        if (scales && (c % 8) == 0) scales[(size_t)n * G + c / 8] = kl_scales[(size_t)(c / 8) * Npad + n];
+    }
+}
+
+}  // namespace
+
+int launch_weight_quant8(const __half *w, int N, int K, int8_t *canon, float *scales, int8_t *kl,
+                         hipStream_t st)
+{
+    const int rows = kl ? round_up(N, TILE_ROWS) : N;
+    hipLaunchKernelGGL(weight_quant8_kernel, dim3(rows), dim3(256), 0, st, w, N, K, canon, scales, kl);
+    return check_hip(hipGetLastError(), "weight_quant8 launch");
+}
+
+int launch_weight_quant4(const __half *w, int N, int K, int group, uint8_t *canon, __half *scales,
+                         uint8_t *kl, hipStream_t st)
+{
+    (void)group;   // validated by the caller: 128
+    const int Npad = round_up(N, TILE_ROWS);
+    const int rows = kl ? Npad : N;
+    __half *kls = kl ? reinterpret_cast<__half *>(kl + w4_scales_offset(N, K)) : nullptr;
+    hipLaunchKernelGGL(weight_quant4_kernel, dim3(rows), dim3(256), 0, st, w, N, Npad, K, canon, scales,
+                       kl, kls);
+    return check_hip(hipGetLastError(), "weight_quant4 launch");
+}
+
+int launch_export8(const int8_t *kl, int N, int K, int8_t *canon, hipStream_t st)
+{
+    hipLaunchKernelGGL(export8_kernel, dim3(N), dim3(256), 0, st, kl, K, canon);
+    return check_hip(hipGetLastError(), "export8 launch");
+}
+
+int launch_export4(const uint8_t *kl, int N, int K, int group, uint8_t *canon, __half *scales,
+                   hipStream_t st)
+{
+    (void)group;
+    const int Npad = round_up(N, TILE_ROWS);
+    const __half *kls = reinterpret_cast<const __half *>(kl + w4_scales_offset(N, K));
+    hipLaunchKernelGGL(export4_kernel, dim3(N), dim3(256), 0, st, kl, kls, Npad, K, canon, scales);
+    return check_hip(hipGetLastError(), "export4 launch");
+}
+
+}  // namespace ql

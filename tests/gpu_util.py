@@ -1,0 +1,108 @@
+"""Helpers for the GPU parity tests: host arrays in, host arrays out, everything through the C ABI."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2512_23367_amd import binding as ql
+
+DEV = "cuda:0"
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def empty_bytes(n: int) -> torch.Tensor:
+    return torch.empty(max(int(n), 1), dtype=torch.uint8, device=DEV)
+
+
+def gpu_quant_act(x16: np.ndarray, ldx: int | None = None):
+    """Returns (xq int8 [M,K] row-major, sx float32 [M], xq_kernel device tensor)."""
+    M, K = x16.shape
+    if ldx is None:
+        xd = dev(x16)
+    else:
+        buf = torch.zeros((M, ldx), dtype=torch.float16, device=DEV)
+        buf[:, :K] = dev(x16)
+        xd = buf[:, :K]
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    xk = empty_bytes(ql.ql_act_kernel_bytes(M, K))
+    ql.ql_quant_act_per_token(xd, xq, xk, sx)
+    torch.cuda.synchronize()
+    return xq.cpu().numpy(), sx.cpu().numpy(), xk
+
+
+def gpu_quant_weight(w16: np.ndarray, bits: int, group: int):
+    """Returns dict(canon, scales, kernel (device), N, K) with canon/scales as host arrays."""
+    N, K = w16.shape
+    cb, sb, kb = ql.ql_weight_bytes(N, K, bits, group)
+    canon = empty_bytes(cb)
+    scales = empty_bytes(sb)
+    kern = empty_bytes(kb)
+    ql.ql_quant_weight(dev(w16), bits, group, canon, scales, kern)
+    torch.cuda.synchronize()
+    if bits == 8:
+        c = canon.cpu().numpy().view(np.int8).reshape(N, K)
+        s = scales.cpu().numpy().view(np.float32).reshape(N)
+    else:
+        c = canon.cpu().numpy().reshape(N, K // 2)
+        s = scales.cpu().numpy().view(np.float16).reshape(N, K // group)
+    return dict(canon=c, scales=s, scales_dev=scales, kernel=kern, N=N, K=K, bits=bits, group=group)
+
+
+def gpu_export(wk, N, K, bits, group):
+    cb, sb, _ = ql.ql_weight_bytes(N, K, bits, group)
+    canon = empty_bytes(cb)
+    scales = empty_bytes(sb)
+    ql.ql_export_canonical(wk, N, K, bits, group, canon, scales if bits == 4 else None)
+    torch.cuda.synchronize()
+    if bits == 8:
+        return canon.cpu().numpy().view(np.int8).reshape(N, K), None
+    return canon.cpu().numpy().reshape(N, K // 2), scales.cpu().numpy().view(np.float16).reshape(N, K // group)
+
+
+def repack_act(xq: np.ndarray) -> torch.Tensor:
+    M, K = xq.shape
+    xk = empty_bytes(ql.ql_act_kernel_bytes(M, K))
+    ql.ql_act_repack(dev(xq), xk)
+    return xk
+
+
+def gpu_acc(xq: np.ndarray, wq, want_partials=False):
+    """Raw integer accumulators of the GEMM main loop for host codes xq and a gpu_quant_weight dict."""
+    M, K = xq.shape
+    N = wq["N"]
+    xk = repack_act(xq)
+    acc = torch.full((M, N), -12345, dtype=torch.int32, device=DEV)
+    part = None
+    if wq["bits"] == 8:
+        ql.ql_w8a8_gemm_acc_i32(xk, M, K, wq["kernel"], N, acc)
+    else:
+        G = K // wq["group"]
+        part = torch.full((M, G, N), -12345, dtype=torch.int32, device=DEV) if want_partials else None
+        ql.ql_w4a8_gemm_acc_i32(xk, M, K, wq["kernel"], wq["group"], N, acc, part, 0, M if want_partials else 0)
+    torch.cuda.synchronize()
+    return acc.cpu().numpy(), (part.cpu().numpy() if part is not None else None)
+
+
+def gpu_linear(x16: np.ndarray, wq, bias16=None, ldy=None) -> np.ndarray:
+    M, K = x16.shape
+    N = wq["N"]
+    ld = ldy or ((N + 7) // 8 * 8)
+    ybuf = torch.full((M, ld), float("nan"), dtype=torch.float16, device=DEV)
+    y = ybuf[:, :N]
+    ws = empty_bytes(ql.ql_workspace_bytes(M, N, K, wq["bits"]))
+    b = dev(bias16) if bias16 is not None else None
+    if wq["bits"] == 8:
+        ql.ql_w8a8_linear(dev(x16), wq["kernel"], wq["scales_dev"].view(torch.float32), b, N, y, ws)
+    else:
+        ql.ql_w4a8_linear(dev(x16), wq["kernel"], wq["group"], b, N, y, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def norm_err(y: np.ndarray, ref64: np.ndarray) -> float:
+    """max|y - ref| / max|ref| (the tolerance the parity bar is stated in)."""
+    return float(np.abs(y.astype(np.float64) - ref64).max() / max(np.abs(ref64).max(), 1e-30))

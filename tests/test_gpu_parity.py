@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: quantized codes, scales and int32 accumulators bit-exact; fp16 outputs within 1e-3 of the
+oracle's fp64 result, as max-abs error normalised by the largest reference magnitude.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2512_23367_amd import binding as ql
+from paper_2512_23367_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_util
+    return gpu_util
+
+
+@pytest.fixture(autouse=True)
+def _auto_variant():
+    yield
+    ql.ql_set_kernel_variant(0)
+
+
+# ------------------------------------------------------------------ quantizers
+@pytest.mark.parametrize("M,K,ldx", [(64, 512, None), (33, 1536, None), (5, 11008, None), (3, 64, None),
+                                     (7, 4096, 4104), (1, 4096, None), (2, 6144, None), (4, 40960, None)])
+def test_act_quant_bit_exact(G, M, K, ldx):
+    x = synth.activations(M, K, 0, "single")
+    x[M // 2, :] *= np.float16(0.01) if M > 1 else np.float16(1)
+    xq_o, sx_o = oracle.quant_act_per_token(x)
+    xq_g, sx_g, xk = G.gpu_quant_act(x, ldx)
+    assert (xq_g == xq_o).all()
+    assert (sx_g.view(np.uint32) == sx_o.view(np.uint32)).all()
+    # the kernel-layout copy holds the same codes: it must equal the repack of the oracle's codes on valid rows
+    a = xk.cpu().numpy().view(np.int8)
+    b = G.repack_act(xq_o).cpu().numpy().view(np.int8)
+    rows_valid = _kernel_layout_mask(M, K)
+    assert (a[rows_valid] == b[rows_valid]).all()
+
+
+def _kernel_layout_mask(M, K):
+    """Boolean mask over the kernel-layout bytes that belong to rows < M (tile order: 32 rows x 32 k per 1 KiB,
+    lane = row%32 + 32*((k%32)//16), 16 bytes per lane)."""
+    Mp = (M + 31) // 32 * 32
+    idx = np.arange(Mp * K)
+    tile, within = idx // 1024, idx % 1024
+    lane = within // 16
+    row = (tile // (K // 32)) * 32 + lane % 32
+    return row < M
+
+
+def test_act_quant_zero_rows_and_ties(G):
+    x = np.zeros((4, 64), dtype=np.float16)
+    x[1, :7] = [127.0, 63.5, -62.5, 0.5, -1.5, 2.5, 0.0]       # inv = 1: every .5 is a tie
+    x[2, :4] = [1.0, -0.5, 0.25, 2.0]
+    xq_o, sx_o = oracle.quant_act_per_token(x)
+    xq_g, sx_g, _ = G.gpu_quant_act(x)
+    assert xq_g[1, :7].tolist() == [127, 64, -62, 0, -2, 2, 0]
+    assert (xq_g == xq_o).all() and (sx_g == sx_o).all()
+    assert sx_g[0] == 1 and sx_g[3] == 1 and (xq_g[0] == 0).all()
+
+
+@pytest.mark.parametrize("N,K", [(512, 512), (100, 1536), (33, 4096)])
+def test_weight_quant_int8_bit_exact_and_export(G, N, K):
+    w = synth.weights(N, K, 0, "single")
+    w[1] = 0
+    wq_o, sw_o = oracle.quant_weight_int8(w)
+    g = G.gpu_quant_weight(w, 8, 0)
+    assert (g["canon"] == wq_o).all()
+    assert (g["scales"].view(np.uint32) == sw_o.view(np.uint32)).all()
+    back, _ = G.gpu_export(g["kernel"], N, K, 8, 0)
+    assert (back == wq_o).all()
+
+
+@pytest.mark.parametrize("N,K", [(512, 512), (100, 1536), (33, 4096)])
+def test_weight_quant_int4_bit_exact_and_export(G, N, K):
+    w = synth.weights(N, K, 0, "single")
+    w[1, :128] = 0
+    w[2, 128:256] *= np.float16(1e-4)
+    packed_o, _, s_o = oracle.quant_weight_int4(w, 128)
+    g = G.gpu_quant_weight(w, 4, 128)
+    assert (g["canon"] == packed_o).all()
+    assert (g["scales"].view(np.uint16) == s_o.view(np.uint16)).all()
+    back, sback = G.gpu_export(g["kernel"], N, K, 4, 128)
+    assert (back == packed_o).all() and (sback.view(np.uint16) == s_o.view(np.uint16)).all()
+
+
+# --------------------------------------------------------------- accumulators
+PREFILL_VARIANTS = [1, 2, 3, 4, 5]
+SHAPES_ACC = [(64, 512, 512), (100, 192, 200), (300, 1024, 520), (257, 256, 33)]
+
+
+@pytest.mark.parametrize("variant", PREFILL_VARIANTS)
+@pytest.mark.parametrize("M,K,N", SHAPES_ACC)
+def test_w8a8_accumulators_bit_exact_prefill(G, variant, M, K, N):
+    if variant == 5 and K % 128:
+        pytest.skip("variant 5 stages 128 k at a time")
+    rng = np.random.default_rng(M + K + N)
+    xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    w = synth.weights(N, K, 0, "single")
+    g = G.gpu_quant_weight(w, 8, 0)
+    ql.ql_set_kernel_variant(variant)
+    acc, _ = G.gpu_acc(xq, g)
+    assert (acc == oracle.igemm(xq, g["canon"])).all()
+
+
+@pytest.mark.parametrize("M", [1, 8, 16, 17, 32])
+@pytest.mark.parametrize("K,N", [(512, 512), (4096, 200), (11008, 48), (192, 33)])
+def test_w8a8_accumulators_bit_exact_decode(G, M, K, N):
+    rng = np.random.default_rng(M + K + N)
+    xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    g = G.gpu_quant_weight(synth.weights(N, K, 0, "single"), 8, 0)
+    acc, _ = G.gpu_acc(xq, g)
+    assert (acc == oracle.igemm(xq, g["canon"])).all()
+
+
+def test_w8a8_accumulator_extremes(G):
+    K = 11008
+    xq = np.full((2, K), 127, dtype=np.int8)
+    xq[1] = -127
+    w = np.ones((40, K), dtype=np.float16)
+    w[1::2] = -1
+    g = G.gpu_quant_weight(w, 8, 0)
+    assert (np.abs(g["canon"]) == 127).all()
+    acc, _ = G.gpu_acc(xq, g)
+    assert (acc == oracle.igemm(xq, g["canon"])).all() and abs(int(acc[0, 0])) == 177548032
+    ql.ql_set_kernel_variant(1)
+    acc, _ = G.gpu_acc(xq, g)
+    assert (acc == oracle.igemm(xq, g["canon"])).all()
+
+
+@pytest.mark.parametrize("M,K,N", [(64, 512, 512), (100, 256, 200), (300, 1024, 264), (1, 512, 512), (8, 4096, 200),
+                                   (17, 1024, 48), (32, 11008, 64)])
+def test_w4a8_accumulators_and_partials_bit_exact(G, M, K, N):
+    rng = np.random.default_rng(M + K + N)
+    xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    g = G.gpu_quant_weight(synth.weights(N, K, 0, "single"), 4, 128)
+    q = oracle.unpack_int4(g["canon"])
+    _, total, part = oracle.igemm_grouped(xq, q, g["scales"], 128, want_partials=True)
+    acc, gpart = G.gpu_acc(xq, g, want_partials=True)
+    assert (acc == total).all()
+    assert (gpart == part).all()
+
+
+# ------------------------------------------------------------------ fp16 layer
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N,bias", [(64, 512, 512, False), (100, 256, 200, True), (300, 1024, 520, True),
+                                        (1, 4096, 512, False), (8, 1536, 200, True), (32, 11008, 64, True),
+                                        (17, 512, 33, False)])
+def test_linear_fp16_within_tolerance(G, bits, M, K, N, bias):
+    x = synth.activations(M, K, 0, "single")
+    w = synth.weights(N, K, 0, "single")
+    b = synth.bias(N, 0, "single") if bias else None
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
+    if bits == 8:
+        ref = oracle.linear_w8a8(x, g["canon"], g["scales"], b)
+    else:
+        ref = oracle.linear_w4a8(x, g["canon"], g["scales"], 128, b)
+    y = G.gpu_linear(x, g, b)
+    assert np.isfinite(y).all()
+    assert G.norm_err(y, ref["y64"]) <= TOL
+    # headroom: against the un-rounded reference the error is about half an fp16 ulp of the largest value
+    assert G.norm_err(y, ref["y64"]) <= 6e-4
+
+
+def test_config0_end_to_end(G):
+    sh = synth.workload(0)[0]
+    x, w, _ = synth.tensors(sh)
+    wq_o, sw_o = oracle.quant_weight_int8(w)
+    ref = oracle.linear_w8a8(x, wq_o, sw_o)
+    g = G.gpu_quant_weight(w, 8, 0)
+    assert (g["canon"] == wq_o).all() and (g["scales"] == sw_o).all()
+    y = G.gpu_linear(x, g)
+    assert G.norm_err(y, ref["y64"]) <= TOL
+    for v in PREFILL_VARIANTS:
+        ql.ql_set_kernel_variant(v)
+        assert G.norm_err(G.gpu_linear(x, g), ref["y64"]) <= TOL
+
+
+def test_padded_output_is_untouched_and_runs_are_deterministic(G):
+    x = synth.activations(70, 256, 0, "single")
+    g = G.gpu_quant_weight(synth.weights(100, 256, 0, "single"), 8, 0)
+    y1 = G.gpu_linear(x, g, ldy=112)
+    y2 = G.gpu_linear(x, g, ldy=112)
+    assert (y1.view(np.uint16) == y2.view(np.uint16)).all()
+
+
+def test_m_zero_is_a_noop(G):
+    import torch
+    g = G.gpu_quant_weight(synth.weights(64, 128, 0, "single"), 8, 0)
+    x = torch.empty((0, 128), dtype=torch.float16, device="cuda:0")
+    y = torch.empty((0, 64), dtype=torch.float16, device="cuda:0")
+    ql.ql_w8a8_linear(x, g["kernel"], g["scales_dev"].view(torch.float32), None, 64, y, None)
+
+
+def test_errors_are_reported_not_launched(G):
+    import torch
+    g = G.gpu_quant_weight(synth.weights(64, 128, 0, "single"), 8, 0)
+    x = G.dev(synth.activations(4, 128, 0, "single"))
+    y = torch.empty((4, 64), dtype=torch.float16, device="cuda:0")
+    with pytest.raises(ql.QlError) as e:
+        ql.ql_w8a8_linear(x, g["kernel"], g["scales_dev"].view(torch.float32), None, 64, y, G.empty_bytes(16))
+    assert e.value.status == 5
+    with pytest.raises(ql.QlError) as e:
+        ql.ql_w8a8_linear(x[:, :100], g["kernel"], g["scales_dev"].view(torch.float32), None, 64, y, G.empty_bytes(4096))
+    assert e.value.status == 2
