@@ -355,6 +355,7 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         // 256 tokens x 128 channels, 8 wavefronts of 64x64: int32 + fp32 accumulators fit 256 registers
         return launch_one<4, 2, 2, 2, 4, 3, true, EPI>(a, st);
     }
+    if (variant == 5 && a.K % 128) variant = 1;   // 128-k stages need K % 128 == 0
     switch (variant) {
     case 0:
     case 1:   // 256x256, 8 wavefronts of 128 tokens x 64 channels, 64 k per stage, 4 stages
