@@ -1,9 +1,10 @@
 // Per-token dynamic int8 activation quantization (paper Eq. 1-2 with n = 8; one scale per token
 // over its whole feature dimension, Preliminary section) for gfx950.
 //
-// One workgroup per token.  The row is read once: each lane keeps its 16-element chunks in
-// registers, the row maximum is reduced across the wavefronts, then the codes are produced from
-// the registers and written both row-major and/or in the GEMM's tile order.
+// One workgroup per 8 tokens.  The rows are read once: each lane keeps its 16-element chunks in
+// registers, the row maxima are reduced across lanes and wavefronts, then the codes are produced
+// from the registers and written row-major and/or in the GEMM's tile order, whole 128-byte lines
+// at a time.
 //
 // Arithmetic (every step a single correctly rounded fp32 operation):
 //   amax = max_k |x|            sx = amax / 127          inv = 127 / amax
@@ -63,52 +64,60 @@ __device__ inline uint4 quant_chunk(const Half16 &v, float inv)
     return q;
 }
 
-// Reduces `m` over the workgroup (blockDim.x a multiple of 64, at most 1024).
-__device__ inline unsigned block_max(unsigned m, unsigned *lds)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1)
-        m = max(m, (unsigned)__shfl_xor((int)m, off, 64));
-    const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    if ((threadIdx.x & 63) == 0) lds[wave] = m;
-    __syncthreads();
-    unsigned r = 0;
-    for (int i = 0; i < nwaves; ++i) r = max(r, lds[i]);
-    return r;
-}
+// One workgroup quantizes 8 consecutive tokens.  A wavefront covers 8 tokens x 8 chunks per step
+// (lane = token % 8 + 8 * chunk), so that in the GEMM's tile order the 8 lanes of one chunk write
+// one whole 128-byte line (8 token slots x 16 bytes) and in the row-major copy each token gets
+// 128 contiguous bytes per step.  The NW wavefronts split K; the row maxima meet in LDS.
+// NIT: steps per wavefront kept in registers (NW * NIT * 128 >= K); NIT == 0: the row is read twice.
+constexpr int ROWS_PER_BLOCK = 8;
+constexpr int MAX_WAVES = 8;
 
-// NIT: chunks per lane kept in registers (blockDim.x * NIT * 16 >= K); NIT == 0: re-read the row.
 template <int NIT>
-__global__ void act_quant_kernel(const __half *__restrict__ x, int64_t ldx, int K,
-                                 int8_t *__restrict__ xq_rm, int8_t *__restrict__ xq_kl,
-                                 float *__restrict__ sx)
+__global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half *__restrict__ x, int64_t ldx,
+                                                                    int M, int K, int per_wave,
+                                                                    int8_t *__restrict__ xq_rm,
+                                                                    int8_t *__restrict__ xq_kl,
+                                                                    float *__restrict__ sx)
 {
-    __shared__ unsigned red[16];
-    const int m = blockIdx.x;
-    const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)m * ldx);
+    __shared__ unsigned red[ROWS_PER_BLOCK][MAX_WAVES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int r = lane & 7, cl = lane >> 3;
+    const int m = blockIdx.x * ROWS_PER_BLOCK + r;
+    const bool valid = m < M;
     const int nchunks = K / CHUNK;
+    const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)(valid ? m : 0) * ldx);
+    const int s0 = wave * per_wave;
 
     Half16 v[NIT > 0 ? NIT : 1];
     unsigned mx = 0;
     if (NIT > 0) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int c = threadIdx.x + i * blockDim.x;
-            if (c < nchunks) {
+            const int c = (s0 + i) * 8 + cl;
+            if (i < per_wave && c < nchunks && valid) {
                 v[i] = row[c];
                 mx = abs_max_bits(v[i], mx);
             }
         }
     } else {
-        for (int c = threadIdx.x; c < nchunks; c += blockDim.x) mx = abs_max_bits(row[c], mx);
+        for (int i = 0; i < per_wave; ++i) {
+            const int c = (s0 + i) * 8 + cl;
+            if (c < nchunks && valid) mx = abs_max_bits(row[c], mx);
+        }
     }
-    mx = block_max(mx, red);
+    mx = max(mx, (unsigned)__shfl_xor((int)mx, 8, 64));
+    mx = max(mx, (unsigned)__shfl_xor((int)mx, 16, 64));
+    mx = max(mx, (unsigned)__shfl_xor((int)mx, 32, 64));
+    if (cl == 0) red[r][wave] = mx;
+    __syncthreads();
+    mx = 0;
+    for (int w = 0; w < nwaves; ++w) mx = max(mx, red[r][w]);
 
     const float amax = half_bits_to_float(mx);
     const bool zero = (mx == 0);
     const float scale = zero ? 1.0f : amax / 127.0f;    // IEEE fp32 division
     const float inv = zero ? 0.0f : 127.0f / amax;      // IEEE fp32 division
-    if (threadIdx.x == 0) sx[m] = scale;
+    if (wave == 0 && cl == 0 && valid) sx[m] = scale;
 
     auto emit = [&](int c, const Half16 &h) {
         const uint4 q = quant_chunk(h, inv);
@@ -118,11 +127,14 @@ __global__ void act_quant_kernel(const __half *__restrict__ x, int64_t ldx, int 
     if (NIT > 0) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int c = threadIdx.x + i * blockDim.x;
-            if (c < nchunks) emit(c, v[i]);
+            const int c = (s0 + i) * 8 + cl;
+            if (i < per_wave && c < nchunks && valid) emit(c, v[i]);
         }
     } else {
-        for (int c = threadIdx.x; c < nchunks; c += blockDim.x) emit(c, row[c]);
+        for (int i = 0; i < per_wave; ++i) {
+            const int c = (s0 + i) * 8 + cl;
+            if (c < nchunks && valid) emit(c, row[c]);
+        }
     }
 }
 
@@ -145,21 +157,19 @@ int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, 
                      float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
-    const int nchunks = K / CHUNK;
-    int threads = round_up(nchunks < 64 ? 64 : nchunks, 64);
-    if (threads > 256) threads = 256;
-    const int nit = ceil_div(nchunks, threads);
-    dim3 grid(M), block(threads);
-    if (nit <= 1)
-        hipLaunchKernelGGL(act_quant_kernel<1>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
-    else if (nit <= 2)
-        hipLaunchKernelGGL(act_quant_kernel<2>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
-    else if (nit <= 4)
-        hipLaunchKernelGGL(act_quant_kernel<4>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
-    else if (nit <= 8)
-        hipLaunchKernelGGL(act_quant_kernel<8>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
-    else
-        hipLaunchKernelGGL(act_quant_kernel<0>, grid, block, 0, st, x, ldx, K, xq_rm, xq_kl, sx);
+    const int steps = ceil_div(K / CHUNK, 8);            // 128 k per wavefront per step
+    const int nw = steps < MAX_WAVES ? steps : MAX_WAVES;
+    const int per_wave = ceil_div(steps, nw);
+    dim3 grid(ceil_div(M, ROWS_PER_BLOCK)), block(nw * 64);
+#define QL_LAUNCH_AQ(NIT) \
+    hipLaunchKernelGGL(act_quant_kernel<NIT>, grid, block, 0, st, x, ldx, M, K, per_wave, xq_rm, xq_kl, sx)
+    if (per_wave <= 1) QL_LAUNCH_AQ(1);
+    else if (per_wave <= 2) QL_LAUNCH_AQ(2);
+    else if (per_wave <= 4) QL_LAUNCH_AQ(4);
+    else if (per_wave <= 8) QL_LAUNCH_AQ(8);
+    else if (per_wave <= 12) QL_LAUNCH_AQ(12);
+    else QL_LAUNCH_AQ(0);
+#undef QL_LAUNCH_AQ
     return check_hip(hipGetLastError(), "act_quant launch");
 }
 

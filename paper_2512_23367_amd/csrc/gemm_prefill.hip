@@ -8,8 +8,8 @@
 //     bytes in, 1024 contiguous LDS bytes out, no registers, no swizzle;
 //   * LDS -> register is one `ds_read_b128` per tile with lane-linear addresses (conflict free).
 // The weight tile is the instruction's first operand and the activation tile its second, so a
-// lane ends up with 4 consecutive output channels of one token per accumulator quad, which makes
-// the fp16 stores 8 bytes wide.
+// lane ends up with 4 consecutive output channels of one token per accumulator quad; the epilogue
+// dequantizes in registers, transposes fp16 blocks through LDS and stores 16 bytes per lane.
 //
 // Pipeline: STAGES LDS buffers of KBS k-blocks each; loads for stage it+STAGES-1 are issued while
 // stage it is multiplied; one workgroup barrier per stage.  8 wavefronts (two per SIMD) so that one
@@ -247,60 +247,116 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(Pre
     wait_vmcnt<0>();   // drain the dead tail loads before the LDS is released
 
     // ---------------------------------------------------------------- epilogue
+    if (EPI == EPI_ACC) {   // test hook: raw integer accumulators, element by element
 #pragma unroll
-    for (int j = 0; j < WM; ++j) {
-        const int m = m_lane0 + j * 32;
-        if (m >= p.M) continue;
-        float sxm = 0.0f;
-        if (EPI == EPI_F16) sxm = p.sx[m] * (W4 ? 0.0625f : 1.0f);
+        for (int j = 0; j < WM; ++j) {
+            const int m = m_lane0 + j * 32;
+            if (m >= p.M) continue;
 #pragma unroll
-        for (int i = 0; i < WN; ++i) {
+            for (int i = 0; i < WN; ++i)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n_lane0 + i * 32 + 8 * q;
-                if (n >= p.N) continue;
-                if (EPI == EPI_ACC) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (n + e < p.N)
-                            p.acc[(size_t)m * p.N + n + e] = W4 ? (tot[i][j][4 * q + e] >> 4) : acc[i][j][4 * q + e];
-                    continue;
+                for (int r = 0; r < 16; ++r) {
+                    const int n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
+                    if (n < p.N) p.acc[(size_t)m * p.N + n] = W4 ? (tot[i][j][r] >> 4) : acc[i][j][r];
                 }
-                float v[4];
-                if (n + 3 < p.N) {
-                    float b[4] = {0.f, 0.f, 0.f, 0.f};
-                    if (p.bias) {
-                        const h4 bb = *reinterpret_cast<const h4 *>(p.bias + n);
+        }
+        return;
+    }
+
+    // A lane holds 4 consecutive channels of ONE token per accumulator quad; storing that directly
+    // would scatter 8-byte pieces over 32 rows per instruction.  Instead each wavefront dequantizes
+    // to fp16, transposes a 32-token block through its own LDS patch and writes 16 bytes per lane,
+    // whole 128/256-byte row segments at a time.
+    constexpr int ROW_BYTES = WN * 32 * 2 + 16;        // +16: 16 lanes of one column hit distinct banks
+    constexpr int LPR = WN * 4;                        // lanes (16 B each) per staged row
+    constexpr int RPI = 64 / LPR;                      // rows per read-back instruction
+    static_assert(NW * 32 * ROW_BYTES <= STAGES * STAGE_BYTES, "staging patch fits the pipeline buffers");
+    __syncthreads();                                   // every wavefront is done with the stage buffers
+    char *stg = smem + wave * (32 * ROW_BYTES);
+
+    // per-channel scales and bias of the 4 channels of accumulator quad (i, q)
+    auto load_scales = [&](int i, int q, float (&sw4)[4], float (&b4)[4]) {
+        const int n = n_lane0 + i * 32 + 8 * q;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) b[e] = (float)bb[e];
-                    }
-                    if (W4) {
+        for (int e = 0; e < 4; ++e) sw4[e] = 0.0f, b4[e] = 0.0f;
+        if (n + 3 < p.N) {
+            if (!W4) {
+                const float4 t = *reinterpret_cast<const float4 *>(p.sw + n);
+                sw4[0] = t.x, sw4[1] = t.y, sw4[2] = t.z, sw4[3] = t.w;
+            }
+            if (p.bias) {
+                const h4 bb = *reinterpret_cast<const h4 *>(p.bias + n);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b[e]);
-                    } else {
-                        const float4 s4 = *reinterpret_cast<const float4 *>(p.sw + n);
-                        const float s[4] = {s4.x, s4.y, s4.z, s4.w};
+                for (int e = 0; e < 4; ++e) b4[e] = (float)bb[e];
+            }
+        } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            v[e] = __builtin_fmaf((float)acc[i][j][4 * q + e] * sxm, s[e], b[e]);
-                    }
-                    h4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (_Float16)v[e];
-                    *reinterpret_cast<h4 *>(p.y + (size_t)m * p.ldy + n) = o;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (n + e >= p.N) break;
-                        const float b = p.bias ? __half2float(p.bias[n + e]) : 0.0f;
-                        float val;
-                        if (W4) val = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b);
-                        else val = __builtin_fmaf((float)acc[i][j][4 * q + e] * sxm, p.sw[n + e], b);
-                        p.y[(size_t)m * p.ldy + n + e] = __float2half_rn(val);
-                    }
+            for (int e = 0; e < 4; ++e) {
+                if (n + e < p.N) {
+                    if (!W4) sw4[e] = p.sw[n + e];
+                    if (p.bias) b4[e] = __half2float(p.bias[n + e]);
                 }
             }
         }
+    };
+    constexpr bool PRELOAD = WN <= 2;                  // enough registers to keep all scales resident
+    float swv[PRELOAD ? WN : 1][4][4], bv[PRELOAD ? WN : 1][4][4];
+    if (PRELOAD) {
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) load_scales(i, q, swv[i][q], bv[i][q]);
+    }
+
+    const int n_wave0 = (tn * TNB + wn * WN) * 32;
+    const int m_wave0 = (tm * TMB + wm * WM) * 32;
+#pragma unroll
+    for (int j = 0; j < WM; ++j) {
+        const int m = m_lane0 + j * 32;
+        const float sxm = (m < p.M) ? p.sx[m] * (W4 ? 0.0625f : 1.0f) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float sw4[4], b4[4];
+                if (PRELOAD) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sw4[e] = swv[i][q][e], b4[e] = bv[i][q][e];
+                } else {
+                    load_scales(i, q, sw4, b4);
+                }
+                h4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float v;
+                    if (W4) v = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b4[e]);
+                    else v = __builtin_fmaf((float)acc[i][j][4 * q + e] * sxm, sw4[e], b4[e]);
+                    o[e] = (_Float16)v;
+                }
+                *reinterpret_cast<h4 *>(stg + (lane & 31) * ROW_BYTES + (i * 32 + 8 * q + 4 * (lane >> 5)) * 2) = o;
+            }
+        // same wavefront, LDS operations complete in order: only the compiler has to be kept from
+        // moving the differently-typed reads above the writes (and the next block's writes above them)
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int t = 0; t < 32 / RPI; ++t) {
+            const int row = t * RPI + lane / LPR, c = lane % LPR;
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * ROW_BYTES + c * 16);
+            const int mm = m_wave0 + j * 32 + row, nn = n_wave0 + c * 8;
+            if (mm < p.M && nn < p.N) {
+                __half *dst = p.y + (size_t)mm * p.ldy + nn;
+                if (nn + 7 < p.N) {
+                    *reinterpret_cast<uint4 *>(dst) = v;
+                } else {
+                    const unsigned w[4] = {v.x, v.y, v.z, v.w};
+                    for (int e = 0; e < 8 && nn + e < p.N; ++e)
+                        dst[e] = __ushort_as_half((unsigned short)(w[e / 2] >> (16 * (e % 2))));
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
