@@ -3,9 +3,9 @@
 // per-channel / per-group scales), but the time goes into streaming the weights from HBM once, so:
 //   * one workgroup owns 16 output channels and the whole K; its 8 wavefronts split K and add their
 //     exact integer (W8A8) or fp32 (W4A8) partial sums through LDS -- no atomics, no second pass;
-//   * weight fragments go global -> registers with 16-byte (int8) or 8-byte (int4) loads per lane,
-//     several in flight per wavefront, straight into the 16x16x64 int8 matrix instruction; nothing is
-//     reused, so nothing is staged in LDS;
+//   * weight fragments go global -> registers with 16-byte loads per lane, a ring of them in flight
+//     per wavefront, straight into the 16x16x64 int8 matrix instruction (int4: after a shift/mask
+//     unpack); nothing is reused, so nothing is staged in LDS;
 //   * the (at most 32) quantized tokens are re-read from L2 in the same tile order.
 #include "common.h"
 
@@ -34,137 +34,182 @@ struct DecodeParams {
     int M, N, K, Npad;
 };
 
-template <bool W4, int MH, int EPI>
+// C: groups of 16 output channels per workgroup (they share every token fragment that is loaded).
+template <bool W4, int MH, int C, int EPI>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 {
-    __shared__ int red[WAVES][MH][4][64];
+    __shared__ int red[WAVES][C][MH][4][64];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rg = blockIdx.x;                    // group of 16 output channels
+    const int rg0 = blockIdx.x * C;               // first group of 16 output channels
     const int r = lane & 15, ch = lane >> 4;      // operand row and 16-k chunk of the 16x16x64 instruction
     const int KB = p.K / 32;
+    const int ngroups = p.Npad / 16;
 
-    // token operand: rows 0..15 (and 16..31) of row-block 0; 64 k = two consecutive 32-k tiles
+    // token operand: rows 0..15 (and 16..31) of row-block 0; 64 k = two consecutive 32-k tiles.
+    // Rows >= M hold nothing: their lanes load nothing, which keeps the L2 traffic at M/16 of the weights'.
     const char *xb = reinterpret_cast<const char *>(p.xq) + (ch / 2) * 1024 + (r + 32 * (ch % 2)) * 16;
-    const int wl = (rg % 2) * 16 + r + 32 * (ch % 2);   // lane slot inside the 32-row weight tile
+    bool xlive[MH];
+#pragma unroll
+    for (int h = 0; h < MH; ++h) xlive[h] = r + 16 * h < p.M;
+    const int wl = r + 32 * (ch % 2);             // lane slot inside the 32-row weight tile, + 16 for odd groups
 
-    v4i acc[MH];
-    float accf[MH][4];
-    int tot[MH][4];
+    v4i acc[C][MH];
+    float accf[C][MH][4];
+    int tot[C][MH][4];
 #pragma unroll
-    for (int h = 0; h < MH; ++h) {
-        acc[h] = v4i{0, 0, 0, 0};
+    for (int j = 0; j < C; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            accf[h][e] = 0.0f;
-            tot[h][e] = 0;
+        for (int h = 0; h < MH; ++h) {
+            acc[j][h] = v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                accf[j][h][e] = 0.0f;
+                tot[j][h][e] = 0;
+            }
         }
+
+    // byte offset of channel group rg0+j inside the weight blob, for this lane
+    size_t wgo[C];
+    bool glive[C];
+#pragma unroll
+    for (int j = 0; j < C; ++j) {
+        const int rg = rg0 + j;
+        glive[j] = rg < ngroups;
+        const int g2 = glive[j] ? rg : 0;
+        if (!W4) wgo[j] = (size_t)(g2 / 2) * KB * 1024 + (ch / 2) * 1024 + ((g2 % 2) * 16 + wl) * 16;
+        else wgo[j] = (size_t)(g2 / 2) * (p.K / 64) * 1024 + (ch / 2) * 1024 + ((g2 % 2) * 16 + wl) * 16;
     }
 
+    // Both loops keep a ring of U weight fragments (1 KiB each per wavefront) in flight: slot u is
+    // consumed, then immediately refilled with the fragment U steps ahead.
     if (!W4) {
         const int nchunks = p.K / 64;
         const int per = (nchunks + WAVES - 1) / WAVES;
         const int c0 = wave * per, c1 = (c0 + per < nchunks) ? c0 + per : nchunks;
-        const char *wb = p.wq + (size_t)(rg / 2) * KB * 1024 + (ch / 2) * 1024 + wl * 16;
-        constexpr int U = 8;
-        for (int c = c0; c < c1; c += U) {
-            v4i wv[U], xv[MH][U];
+        constexpr int U = 8 / C;
+        v4i wv[U][C], xv[U][MH];
+        auto fetch = [&](int u, int c) {
+            if (c < c1) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (c + u < c1) {
-                    wv[u] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(wb + (size_t)(c + u) * 2048));
+                for (int j = 0; j < C; ++j)
+                    wv[u][j] = glive[j] ? __builtin_nontemporal_load(
+                                              reinterpret_cast<const v4i *>(p.wq + wgo[j] + (size_t)c * 2048))
+                                        : v4i{0, 0, 0, 0};
 #pragma unroll
-                    for (int h = 0; h < MH; ++h)
-                        xv[h][u] = *reinterpret_cast<const v4i *>(xb + (size_t)(c + u) * 2048 + h * 256);
-                }
+                for (int h = 0; h < MH; ++h)
+                    xv[u][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb + (size_t)c * 2048 + h * 256)
+                                        : v4i{0, 0, 0, 0};
             }
+        };
+#pragma unroll
+        for (int u = 0; u < U; ++u) fetch(u, c0 + u);
+        for (int c = c0; c < c1; c += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (c + u < c1) {
 #pragma unroll
-                    for (int h = 0; h < MH; ++h)
-                        acc[h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[u], xv[h][u], acc[h], 0, 0, 0);
+                    for (int j = 0; j < C; ++j)
+#pragma unroll
+                        for (int h = 0; h < MH; ++h)
+                            acc[j][h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[u][j], xv[u][h], acc[j][h], 0, 0, 0);
                 }
+                fetch(u, c + U + u);
             }
         }
     } else {
+        // One 16-byte load per lane covers one scale group (128 k): words 0,1 feed the first matrix
+        // instruction (k-blocks 4g, 4g+2 over the four lane chunks), words 2,3 the second (4g+1, 4g+3).
         const int G = p.K / 128;
         const int per = (G + WAVES - 1) / WAVES;
         const int g0 = wave * per, g1 = (g0 + per < G) ? g0 + per : G;
-        const char *wb = p.wq + (size_t)(rg / 2) * (p.K / 64) * 1024 + wl * 16 + (ch / 2) * 8;
-        const __half *sgp = p.wscales + rg * 16 + 4 * ch;
-        constexpr int U = 4;                      // groups per batch = 8 fragments in flight
-        for (int g = g0; g < g1; g += U) {
-            v2i wv[U][2];
-            v4i xv[MH][U][2];
-            h4 sg[U];
+        const char *xb4 = reinterpret_cast<const char *>(p.xq) + (2 * (ch / 2)) * 1024 + (r + 32 * (ch % 2)) * 16;
+        constexpr int U = C >= 4 ? 1 : 4 / C;     // each slot also holds two token fragments per half
+        v4i wv[U][C], xv[U][2][MH];
+        h4 sg[U][C];
+        auto fetch = [&](int u, int g) {
+            if (g < g1) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (g + u < g1) {
-                    sg[u] = *reinterpret_cast<const h4 *>(sgp + (size_t)(g + u) * p.Npad);
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const size_t c = 2 * (size_t)(g + u) + t;
-                        wv[u][t] = __builtin_nontemporal_load(reinterpret_cast<const v2i *>(wb + c * 1024));
-#pragma unroll
-                        for (int h = 0; h < MH; ++h)
-                            xv[h][u][t] = *reinterpret_cast<const v4i *>(xb + c * 2048 + h * 256);
-                    }
+                for (int j = 0; j < C; ++j) {
+                    wv[u][j] = glive[j] ? __builtin_nontemporal_load(
+                                              reinterpret_cast<const v4i *>(p.wq + wgo[j] + (size_t)g * 2048))
+                                        : v4i{0, 0, 0, 0};
+                    sg[u][j] = glive[j] ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)g * p.Npad +
+                                                                        (rg0 + j) * 16 + 4 * ch)
+                                        : h4{0, 0, 0, 0};
                 }
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int h = 0; h < MH; ++h)
+                        xv[u][t][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb4 + ((size_t)4 * g + t) * 1024 + h * 256)
+                                               : v4i{0, 0, 0, 0};
             }
+        };
+#pragma unroll
+        for (int u = 0; u < U; ++u) fetch(u, g0 + u);
+        for (int g = g0; g < g1; g += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (g + u < g1) {
 #pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        const unsigned w0 = (unsigned)wv[u][t][0], w1 = (unsigned)wv[u][t][1];
-                        v4i wf;
-                        wf[0] = (int)((w0 << 4) & 0xF0F0F0F0u);
-                        wf[1] = (int)(w0 & 0xF0F0F0F0u);
-                        wf[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
-                        wf[3] = (int)(w1 & 0xF0F0F0F0u);
+                    for (int t = 0; t < 2; ++t)
 #pragma unroll
-                        for (int h = 0; h < MH; ++h)
-                            acc[h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xv[h][u][t], acc[h], 0, 0, 0);
-                    }
+                        for (int j = 0; j < C; ++j) {
+                            const unsigned w0 = (unsigned)wv[u][j][2 * t], w1 = (unsigned)wv[u][j][2 * t + 1];
+                            v4i wf;
+                            wf[0] = (int)((w0 << 4) & 0xF0F0F0F0u);
+                            wf[1] = (int)(w0 & 0xF0F0F0F0u);
+                            wf[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
+                            wf[3] = (int)(w1 & 0xF0F0F0F0u);
 #pragma unroll
-                    for (int h = 0; h < MH; ++h) {
+                            for (int h = 0; h < MH; ++h)
+                                acc[j][h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xv[u][t][h], acc[j][h], 0, 0, 0);
+                        }
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            if (EPI == EPI_F16) {
-                                accf[h][e] = __builtin_fmaf((float)acc[h][e], (float)sg[u][e], accf[h][e]);
-                            } else {
-                                tot[h][e] += acc[h][e];
-                                if (p.partials) {
-                                    const int m = r + 16 * h, n = rg * 16 + 4 * ch + e;
-                                    if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
-                                        p.partials[((size_t)(m - p.row0) * G + (g + u)) * p.N + n] = acc[h][e] >> 4;
+                    for (int j = 0; j < C; ++j)
+#pragma unroll
+                        for (int h = 0; h < MH; ++h) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                if (EPI == EPI_F16) {
+                                    accf[j][h][e] = __builtin_fmaf((float)acc[j][h][e], (float)sg[u][j][e], accf[j][h][e]);
+                                } else {
+                                    tot[j][h][e] += acc[j][h][e];
+                                    if (p.partials) {
+                                        const int m = r + 16 * h, n = (rg0 + j) * 16 + 4 * ch + e;
+                                        if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
+                                            p.partials[((size_t)(m - p.row0) * G + (g + u)) * p.N + n] = acc[j][h][e] >> 4;
+                                    }
                                 }
                             }
+                            acc[j][h] = v4i{0, 0, 0, 0};
                         }
-                        acc[h] = v4i{0, 0, 0, 0};
-                    }
                 }
+                fetch(u, g + U + u);
             }
         }
     }
 
     // add the 8 wavefronts' partial sums (fixed order: the result does not depend on timing)
 #pragma unroll
-    for (int h = 0; h < MH; ++h)
+    for (int j = 0; j < C; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            int v;
-            if (!W4) v = acc[h][e];
-            else if (EPI == EPI_F16) v = __float_as_int(accf[h][e]);
-            else v = tot[h][e];
-            red[wave][h][e][lane] = v;
-        }
+        for (int h = 0; h < MH; ++h)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int v;
+                if (!W4) v = acc[j][h][e];
+                else if (EPI == EPI_F16) v = __float_as_int(accf[j][h][e]);
+                else v = tot[j][h][e];
+                red[wave][j][h][e][lane] = v;
+            }
     __syncthreads();
-    if (wave != 0) return;
-
-    const int n0 = rg * 16 + 4 * ch;
+    // wavefront w finishes channel group w (C <= WAVES)
+    if (wave >= C) return;
+    const int j = wave;
+    const int n0 = (rg0 + j) * 16 + 4 * ch;
 #pragma unroll
     for (int h = 0; h < MH; ++h) {
         const int m = r + 16 * h;
@@ -174,8 +219,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         for (int w = 0; w < WAVES; ++w)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (W4 && EPI == EPI_F16) sf[e] += __int_as_float(red[w][h][e][lane]);
-                else si[e] += red[w][h][e][lane];
+                if (W4 && EPI == EPI_F16) sf[e] += __int_as_float(red[w][j][h][e][lane]);
+                else si[e] += red[w][j][h][e][lane];
             }
         if (m >= p.M || n0 >= p.N) continue;
         if (EPI == EPI_ACC) {
@@ -197,7 +242,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     }
 }
 
-template <bool W4, int MH, int EPI>
+template <bool W4, int MH, int C, int EPI>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     DecodeParams p;
@@ -217,26 +262,40 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     p.K = a.K;
     p.Npad = round_up(a.N, TILE_ROWS);
     p.wscales = W4 ? reinterpret_cast<const __half *>(p.wq + w4_scales_offset(a.N, a.K)) : nullptr;
-    const int grid = p.Npad / 16;
-    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, EPI>), dim3(grid), dim3(WAVES * 64), 0, st, p);
+    const int grid = ceil_div(p.Npad / 16, C);
+    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI>), dim3(grid), dim3(WAVES * 64), 0, st, p);
     return check_hip(hipGetLastError(), "gemm_decode launch");
 }
 
+// The token fragments are re-read from L2 by every workgroup; their traffic relative to the weight
+// stream is (tokens rounded up to 16) / (16 * C).  More channel groups per workgroup cut it, at the
+// price of fewer workgroups, so C grows with M and shrinks again when N is too small to fill 256 CUs.
 template <bool W4, int EPI>
-int by_m(const GemmArgs &a, hipStream_t st)
+int by_m(const GemmArgs &a, int variant, hipStream_t st)
 {
-    return a.M <= 16 ? launch_one<W4, 1, EPI>(a, st) : launch_one<W4, 2, EPI>(a, st);
+    int c = a.M <= 4 ? 1 : (a.M <= 16 ? 2 : 4);
+    while (c > 1 && ceil_div(round_up(a.N, TILE_ROWS) / 16, c) < 512) c /= 2;
+    if (variant == 101) c = 1;
+    if (variant == 102) c = 2;
+    if (variant == 104) c = 4;
+    if (a.M <= 16) {
+        if (c == 1) return launch_one<W4, 1, 1, EPI>(a, st);
+        if (c == 2) return launch_one<W4, 1, 2, EPI>(a, st);
+        return launch_one<W4, 1, 4, EPI>(a, st);
+    }
+    if (c == 1) return launch_one<W4, 2, 1, EPI>(a, st);
+    if (c == 2) return launch_one<W4, 2, 2, EPI>(a, st);
+    return launch_one<W4, 2, 4, EPI>(a, st);
 }
 
 }  // namespace
 
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st)
 {
-    (void)variant;
     if (a.M == 0) return QL_OK;
     const bool dump = a.acc != nullptr;
-    if (a.bits == 4) return dump ? by_m<true, EPI_ACC>(a, st) : by_m<true, EPI_F16>(a, st);
-    return dump ? by_m<false, EPI_ACC>(a, st) : by_m<false, EPI_F16>(a, st);
+    if (a.bits == 4) return dump ? by_m<true, EPI_ACC>(a, variant, st) : by_m<true, EPI_F16>(a, variant, st);
+    return dump ? by_m<false, EPI_ACC>(a, variant, st) : by_m<false, EPI_F16>(a, variant, st);
 }
 
 }  // namespace ql

@@ -162,28 +162,62 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(Pre
     const int n_lane0 = (tn * TNB + wn * WN) * 32 + 4 * (lane >> 5);   // + bi*32 + 8*q + (r%4)
     const int m_lane0 = (tm * TMB + wm * WM) * 32 + (lane & 31);       // + bj*32
 
-    for (int it = 0; it < nstages; ++it) {
+    if (!W4) {
+        // Rotated pipeline.  Fragments of the next k-block are read from LDS while the matrix
+        // instructions of the current one run; the stage hand-over (wait for the next stage's loads,
+        // barrier, refill of the buffer just freed, first fragment read of the next stage) sits in
+        // front of the LAST k-block's matrix instructions, so they cover its latency.
+        v4i wf[2][WN], xf[2][WM];
+        auto read_frags = [&](int slot, const char *buf, int kb) {
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+                wf[slot][i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb) * 1024 + lane * 16);
+#pragma unroll
+            for (int j = 0; j < WM; ++j)
+                xf[slot][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
+        };
+        auto mma = [&](int slot) {
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int j = 0; j < WM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[slot][i], xf[slot][j], acc[i][j], 0, 0, 0);
+        };
+        static_assert(KBS % 2 == 0, "fragment slots alternate over an even number of k-blocks");
+        wait_vmcnt<(STAGES - 2) * LPW>();        // stage 0 has landed (this wavefront's part)
+        __builtin_amdgcn_s_barrier();            // ... everyone's
+        issue_stage(STAGES - 1);
+        read_frags(0, smem, 0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): enter the loop with nothing outstanding
+        for (int it = 0; it < nstages; ++it) {
+            const char *buf = smem + (it % STAGES) * STAGE_BYTES;
+#pragma unroll
+            for (int kb = 0; kb < KBS - 1; ++kb) {
+                read_frags((kb + 1) & 1, buf, kb + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(kb & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // stage `it` is fully in registers
+            wait_vmcnt<(STAGES - 2) * LPW>();                       // stage it+1 has landed (own part)
+            __builtin_amdgcn_s_barrier();                           // ... everyone's; buffer of stage `it` is free
+            issue_stage(it + STAGES);
+            read_frags(0, smem + ((it + 1) % STAGES) * STAGE_BYTES, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma((KBS - 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            // the reads above finished long ago; saying so lets the compiler start the next iteration's
+            // matrix instructions without a conservative wait at the loop header
+            __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+        }
+    }
+    for (int it = 0; W4 && it < nstages; ++it) {
         wait_vmcnt<(STAGES - 2) * LPW>();        // this wavefront's loads of stage `it` have landed
         __builtin_amdgcn_s_barrier();            // ... everyone's; and stage it-1 is fully consumed
         issue_stage(it + STAGES - 1);            // refills the buffer stage it-1 used
 
         const char *buf = smem + (it % STAGES) * STAGE_BYTES;
         if (!W4) {
-#pragma unroll
-            for (int kb = 0; kb < KBS; ++kb) {
-                v4i wf[WN], xf[WM];
-#pragma unroll
-                for (int i = 0; i < WN; ++i)
-                    wf[i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb) * 1024 + lane * 16);
-#pragma unroll
-                for (int j = 0; j < WM; ++j)
-                    xf[j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
-#pragma unroll
-                for (int i = 0; i < WN; ++i)
-#pragma unroll
-                    for (int j = 0; j < WM; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
-            }
         } else {
             // group scales of this stage (= group `it`): 4 consecutive channels per accumulator quad
             h4 sg[WN][4];
@@ -404,6 +438,7 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     return check_hip(hipGetLastError(), "gemm_prefill launch");
 }
 
+// variant 0 = automatic choice; 1..5 pick one tile configuration (tests and tuning)
 template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
 {
@@ -411,9 +446,15 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         // 256 tokens x 128 channels, 8 wavefronts of 64x64: int32 + fp32 accumulators fit 256 registers
         return launch_one<4, 2, 2, 2, 4, 3, true, EPI>(a, st);
     }
+    if (variant == 0) {
+        // 256x256 tiles run the matrix pipes best, but a grid that fills only part of the last round of
+        // 256 CUs wastes more than the smaller tile's extra L2 traffic costs
+        const long t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
+        const long rounds = (t256 + 255) / 256;
+        variant = (t256 * 10 < rounds * 256 * 8) ? 4 : 5;
+    }
     if (variant == 5 && a.K % 128) variant = 1;   // 128-k stages need K % 128 == 0
     switch (variant) {
-    case 0:
     case 1:   // 256x256, 8 wavefronts of 128 tokens x 64 channels, 64 k per stage, 4 stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI>(a, st);
     case 2:   // 256x256, 8 wavefronts of 64 tokens x 128 channels
@@ -424,6 +465,10 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 2, 2, 2, 2, 4, false, EPI>(a, st);
     case 5:   // 256x256, 8 wavefronts, 128 k per stage, 2 stages
         return launch_one<2, 4, 4, 2, 4, 2, false, EPI>(a, st);
+    case 6:   // 256x256, 8 wavefronts, 64 k per stage, 5 stages (all 160 KB of LDS)
+        return launch_one<2, 4, 4, 2, 2, 5, false, EPI>(a, st);
+    case 7:   // 256x256, 8 wavefronts of 64 tokens x 128 channels, 128 k per stage, 2 stages
+        return launch_one<4, 2, 2, 4, 4, 2, false, EPI>(a, st);
     default:
         return fail(QL_ERR_UNSUPPORTED, "unknown prefill kernel variant %d", variant);
     }
