@@ -107,6 +107,19 @@ def event_time_ms(torch, fn, reps, per_launch):
     return a.elapsed_time(b) / reps
 
 
+def profiled_traffic(cfg):
+    """HBM bytes per GEMM launch (average over the workload's linears) from the committed rocprofv3
+    FETCH_SIZE + WRITE_SIZE summary of this workload, copy-kernel calibrated; None if not profiled."""
+    path = os.path.join(ROOT, "profiles", f"prefill_gemm_config{cfg}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(shapes, synth):
     """The oracle as it stands, timed on the host cores on the same workload (all rows)."""
     import oracle
@@ -139,6 +152,9 @@ def main():
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape table of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--only-step", action="store_true", help="only the timed steps (for profiling)")
+    ap.add_argument("--copy-only", action="store_true",
+                    help="run a plain 1 GiB device-to-device copy 5 times and exit (calibrates the profiler's "
+                         "FETCH_SIZE / WRITE_SIZE counters against a known size)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: every box of this build has one MI355X and the path uses no "
@@ -152,6 +168,14 @@ def main():
     if not torch.cuda.is_available():
         log("no GPU visible")
         sys.exit(1)
+    if args.copy_only:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_per_launch": src.numel() * 4, "launches": 5}), flush=True)
+        return
     ql.lib()
     ql.ql_set_kernel_variant(args.variant)
     cfg = int(args.workload.replace("config", ""))
@@ -192,7 +216,7 @@ def main():
         print(json.dumps(out), flush=True)
         return
 
-    # ---- roofline of the dominant kernel (the prefill GEMM): HIP events around each GEMM launch
+    # ---- roofline of the dominant kernel (the prefill GEMM), timed with HIP events on the launch stream
     for l in layers:
         l.quant()
     reps = max(20, min(args.steps, 100))
@@ -208,7 +232,7 @@ def main():
     achieved = total_ops / (sum(gemm_ms) * 1e-3) / 1e12
     out["roofline"] = {
         "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-        "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": None,
+        "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": profiled_traffic(cfg),
         "kernel": "gemm_prefill_kernel (int8 MFMA GEMM + fused dequant epilogue), one launch per linear",
         "launch_us": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, gemm_ms)},
         "launch_us_event_pair_each": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, gemm_ms_b2b)},
