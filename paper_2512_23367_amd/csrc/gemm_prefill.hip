@@ -77,8 +77,8 @@ __device__ inline void tile_coords(int bid, int tiles_m, int tiles_n, int &tm, i
     tn = in_g / gsize;
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(PrefillParams p)
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC>
+__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kernel(PrefillParams p)
 {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int TMB = WAVES_M * WM;                    // activation row-blocks per workgroup tile
@@ -211,24 +211,48 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(Pre
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
         }
     }
-    for (int it = 0; W4 && it < nstages; ++it) {
-        wait_vmcnt<(STAGES - 2) * LPW>();        // this wavefront's loads of stage `it` have landed
-        __builtin_amdgcn_s_barrier();            // ... everyone's; and stage it-1 is fully consumed
-        issue_stage(it + STAGES - 1);            // refills the buffer stage it-1 used
-
-        const char *buf = smem + (it % STAGES) * STAGE_BYTES;
-        if (!W4) {
-        } else {
-            // group scales of this stage (= group `it`): 4 consecutive channels per accumulator quad
-            h4 sg[WN][4];
+    if (W4) {
+        // Per stage (= one scale group of 128 k): 4*WN*WM matrix instructions, and the fold of the group's
+        // int32 partial into the fp32 sums (accf += float(acc) * scale: 2 vector-ALU ops per element, about
+        // as many cycles as the stage's matrix instructions).  The fold of stage it-1 is done block by block
+        // at the start of stage it, each block right before the first matrix instruction that overwrites it
+        // (C = 0), so the vector ALU works on block b+1 while the matrix pipe runs block b.
+        h4 sg[WN][4];                                // scales of the stage whose partial sits in acc
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sg[i][q] = h4{0, 0, 0, 0};
+        auto load_sg = [&](int g) {
 #pragma unroll
             for (int i = 0; i < WN; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int n = n_lane0 + i * 32 + 8 * q;     // whole 32-blocks are inside or outside Npad
-                    sg[i][q] = (n < p.Npad) ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)it * p.Npad + n)
+                    sg[i][q] = (n < p.Npad) ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)g * p.Npad + n)
                                             : h4{0, 0, 0, 0};
                 }
+        };
+        auto fold_block = [&](int i, int j, int g) {   // group g's partial of block (i, j); g < 0: nothing yet
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                if (EPI == EPI_F16) {
+                    accf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], (float)sg[i][r / 4][r % 4], accf[i][j][r]);
+                } else {
+                    tot[i][j][r] += acc[i][j][r];
+                    if (p.partials && g >= 0) {
+                        const int m = m_lane0 + j * 32, n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
+                        if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
+                            p.partials[((size_t)(m - p.row0) * nstages + g) * p.N + n] = acc[i][j][r] >> 4;
+                    }
+                }
+            }
+        };
+        const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        for (int it = 0; it < nstages; ++it) {
+            wait_vmcnt<(STAGES - 2) * LPW>();        // this wavefront's loads of stage `it` have landed
+            __builtin_amdgcn_s_barrier();            // ... everyone's; and stage it-1 is fully consumed
+            issue_stage(it + STAGES - 1);            // refills the buffer stage it-1 used
+            const char *buf = smem + (it % STAGES) * STAGE_BYTES;
 #pragma unroll
             for (int kp = 0; kp < KBS / 2; ++kp) {
                 v4i wp[WN];
@@ -251,32 +275,23 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(Pre
                         wf[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
                         wf[3] = (int)(w1 & 0xF0F0F0F0u);
 #pragma unroll
-                        for (int j = 0; j < WM; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[j], acc[i][j], 0, 0, 0);
-                    }
-                }
-            }
-            // fold the group's integer partial (16x the true value) into the running sums
-#pragma unroll
-            for (int i = 0; i < WN; ++i)
-#pragma unroll
-                for (int j = 0; j < WM; ++j) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        if (EPI == EPI_F16) {
-                            accf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], (float)sg[i][r / 4][r % 4], accf[i][j][r]);
-                        } else {
-                            tot[i][j][r] += acc[i][j][r];
-                            if (p.partials) {
-                                const int m = m_lane0 + j * 32, n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
-                                if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
-                                    p.partials[((size_t)(m - p.row0) * nstages + it) * p.N + n] = acc[i][j][r] >> 4;
+                        for (int j = 0; j < WM; ++j) {
+                            if (kb == 0) {
+                                fold_block(i, j, it - 1);
+                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[j], zero16, 0, 0, 0);
+                            } else {
+                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[j], acc[i][j], 0, 0, 0);
                             }
                         }
-                        acc[i][j][r] = 0;
                     }
                 }
+                if (kp == 0) load_sg(it);            // the previous scales were consumed by the folds above
+            }
         }
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int j = 0; j < WM; ++j) fold_block(i, j, nstages - 1);
     }
     wait_vmcnt<0>();   // drain the dead tail loads before the LDS is released
 
@@ -394,7 +409,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_prefill_kernel(Pre
     }
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI>
+// OCC: wavefronts per SIMD the register allocation must leave room for (workgroups per CU x waves / 4)
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
@@ -403,7 +419,7 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     constexpr int LDS = (XFR + WFR) * 1024 * STAGES;
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert((STAGES - 2) * (XFR + WFR) / (WAVES_M * WAVES_N) <= 63, "vmcnt range");
-    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI>;
+    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC>;
     static bool attr_set = false;
     if (!attr_set) {
         QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -451,9 +467,15 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         // 256 CUs wastes more than the smaller tile's extra L2 traffic costs
         const long t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
         const long rounds = (t256 + 255) / 256;
-        variant = (t256 * 10 < rounds * 256 * 8) ? 4 : 5;
+        variant = 5;
+        if (t256 * 10 < rounds * 256 * 8) {
+            // 128x128 tiles: three workgroups per CU when there are enough tiles to need them, eight
+            // wavefronts per tile when every tile gets a CU of its own
+            const long t128 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 128);
+            variant = t128 > 512 ? 11 : (t128 <= 256 ? 13 : 4);
+        }
     }
-    if (variant == 5 && a.K % 128) variant = 1;   // 128-k stages need K % 128 == 0
+    if ((variant == 5 || variant == 12) && a.K % 128) variant = variant == 5 ? 1 : 4;   // 128-k stages need K % 128 == 0
     switch (variant) {
     case 1:   // 256x256, 8 wavefronts of 128 tokens x 64 channels, 64 k per stage, 4 stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI>(a, st);
@@ -469,6 +491,20 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 4, 4, 2, 2, 5, false, EPI>(a, st);
     case 7:   // 256x256, 8 wavefronts of 64 tokens x 128 channels, 128 k per stage, 2 stages
         return launch_one<4, 2, 2, 4, 4, 2, false, EPI>(a, st);
+    case 11:  // 128x128, 4 wavefronts of 64x64, 3 stages of 64 k: three workgroups per CU
+        return launch_one<2, 2, 2, 2, 2, 3, false, EPI, 3>(a, st);
+    case 12:  // 128x128, 4 wavefronts of 64x64, 2 stages of 128 k: two workgroups per CU
+        return launch_one<2, 2, 2, 2, 4, 2, false, EPI, 2>(a, st);
+    case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU)
+        return launch_one<4, 2, 1, 2, 2, 4, false, EPI>(a, st);
+    case 14:  // 128x128, 8 wavefronts of 64 tokens x 32 channels
+        return launch_one<2, 4, 2, 1, 2, 4, false, EPI>(a, st);
+    case 10:  // 256x256, 4 wavefronts of 128x128, 128 k per stage, 2 stages
+        return launch_one<2, 2, 4, 4, 4, 2, false, EPI>(a, st);
+    case 8:   // 256 tokens x 128 channels, 4 wavefronts of 128x64, two workgroups per CU (independent barriers)
+        return launch_one<2, 2, 4, 2, 2, 3, false, EPI>(a, st);
+    case 9:   // 128 tokens x 256 channels, 4 wavefronts of 64x128, two workgroups per CU
+        return launch_one<2, 2, 2, 4, 2, 3, false, EPI>(a, st);
     default:
         return fail(QL_ERR_UNSUPPORTED, "unknown prefill kernel variant %d", variant);
     }
