@@ -40,10 +40,10 @@
  * + 32 * ((k % 32) / 16), 16 consecutive k per lane); tiles are ordered
  * row-block-major, then k-block.  Rows are padded to a multiple of 32.  int4
  * tiles hold two k-blocks per 1024 bytes with the nibbles pre-ordered for a
- * shift/mask unpack, followed in the same blob by the group scales transposed to
- * [K/128][ceil32(N)].  The layout is opaque to callers: build it with
- * ql_quant_weight / ql_quant_act_per_token / ql_act_repack and read it back with
- * ql_export_canonical.
+ * shift/mask unpack, followed in the same blob by two copies of the group scales
+ * ([K/128][ceil32(N)] for the prefill kernels, [ceil32(N)/16][K/128][16] for the
+ * decode kernels).  The layout is opaque to callers: build it with ql_quant_weight /
+ * ql_quant_act_per_token / ql_act_repack and read it back with ql_export_canonical.
  */
 #ifndef QLINEAR_H
 #define QLINEAR_H

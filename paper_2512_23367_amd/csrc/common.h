@@ -61,9 +61,17 @@ inline size_t act_kernel_bytes(int M, int K) { return (size_t)round_up(M, TILE_R
 inline size_t w8_kernel_bytes(int N, int K) { return (size_t)round_up(N, TILE_ROWS) * K; }
 inline size_t w4_codes_bytes(int N, int K) { return (size_t)round_up(N, TILE_ROWS) * K / 2; }
 inline size_t w4_scales_offset(int N, int K) { return (w4_codes_bytes(N, K) + 255) & ~(size_t)255; }
+// The int4 blob holds the group scales twice: [K/group][ceil32(N)] (a prefill tile's 128 channels of one
+// group are contiguous) and, for the decode kernels, [ceil32(N)/16][K/group][16] (everything one
+// workgroup's 16 channels need is contiguous).
+inline size_t w4_scales_bytes(int N, int K, int group)
+{
+    return (((size_t)(K / group) * round_up(N, TILE_ROWS) * sizeof(__half)) + 255) & ~(size_t)255;
+}
+inline size_t w4_scales_dec_offset(int N, int K, int group) { return w4_scales_offset(N, K) + w4_scales_bytes(N, K, group); }
 inline size_t w4_kernel_bytes(int N, int K, int group)
 {
-    return w4_scales_offset(N, K) + (size_t)(K / group) * round_up(N, TILE_ROWS) * sizeof(__half);
+    return w4_scales_offset(N, K) + 2 * w4_scales_bytes(N, K, group);
 }
 
 // ---- launchers implemented in the .hip files ----------------------------------------------------

@@ -1,7 +1,7 @@
 // Decode-shaped GEMM (at most 32 tokens) + dequantization epilogue of the W8A8 / W4A8 linear layer
 // for gfx950.  Same arithmetic as the prefill kernel (integer accumulation, Y = XW, per-token and
 // per-channel / per-group scales), but the time goes into streaming the weights from HBM once, so:
-//   * one workgroup owns 16 output channels and the whole K; its 8 wavefronts split K and add their
+//   * one workgroup owns 16 output channels and the whole K; its 8 (or 16) wavefronts split K and add their
 //     exact integer (W8A8) or fp32 (W4A8) partial sums through LDS -- no atomics, no second pass;
 //   * weight fragments go global -> registers with 16-byte loads per lane, a ring of them in flight
 //     per wavefront, straight into the 16x16x64 int8 matrix instruction (int4: after a shift/mask
@@ -17,7 +17,6 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 
 enum { EPI_F16 = 0, EPI_ACC = 1 };
-constexpr int WAVES = 8;
 
 struct DecodeParams {
     const int8_t *xq;
@@ -35,10 +34,18 @@ struct DecodeParams {
 };
 
 // C: groups of 16 output channels per workgroup (they share every token fragment that is loaded).
-template <bool W4, int MH, int C, int EPI>
+// XL: the (few) quantized tokens are staged once per workgroup in LDS, [k-tile half][token] with one extra
+// all-zero token row that the lanes of absent tokens read; the ring then holds weights only.
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 {
     __shared__ int red[WAVES][C][MH][4][64];
+    extern __shared__ __attribute__((aligned(16))) char dyn_lds[];
+    // W4A8: the group scales of this workgroup's C*16 channels, [C][K/128][16] fp16, then
+    // XL: the staged tokens, (M + 1) * K bytes
+    char *ss = dyn_lds;
+    char *xs = dyn_lds + (W4 ? (size_t)C * (p.K / 128) * 32 : 0);
+    static_assert(!XL || MH == 1, "LDS-staged tokens: at most 16 tokens");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -82,6 +89,25 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         else wgo[j] = (size_t)(g2 / 2) * (p.K / 64) * 1024 + (ch / 2) * 1024 + ((g2 % 2) * 16 + wl) * 16;
     }
 
+    // XL: copy tokens 0..M-1 from the tile order into xs[(k-tile * 2 + half) * (M + 1) + token] and clear row M
+    const int xrows = p.M + 1;
+    const int xrow = (r < p.M) ? r : p.M;
+    // Every wavefront stages only the k-range it multiplies (tile-halves th0 .. th1-1), so no workgroup
+    // barrier is needed: a wavefront's LDS operations complete in order.
+    auto stage_tokens = [&](int th0, int th1) {
+        const int pieces = (th1 - th0) * xrows;
+        for (int i = lane; i < pieces; i += 64) {
+            const int th = th0 + i / xrows, row = i % xrows;
+            v4i v = v4i{0, 0, 0, 0};
+            if (row < p.M)
+                v = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(p.xq) + (size_t)(th / 2) * 1024 +
+                                                   (row + 32 * (th % 2)) * 16);
+            *reinterpret_cast<v4i *>(xs + ((size_t)th * xrows + row) * 16) = v;
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+    };
+
     // Both loops keep a ring of U weight fragments (1 KiB each per wavefront) in flight: slot u is
     // consumed, then immediately refilled with the fragment U steps ahead.
     if (!W4) {
@@ -89,7 +115,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const int per = (nchunks + WAVES - 1) / WAVES;
         const int c0 = wave * per, c1 = (c0 + per < nchunks) ? c0 + per : nchunks;
         constexpr int U = 8 / C;
-        v4i wv[U][C], xv[U][MH];
+        v4i wv[U][C], xv[XL ? 1 : U][MH];
         auto fetch = [&](int u, int c) {
             if (c < c1) {
 #pragma unroll
@@ -97,23 +123,27 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                     wv[u][j] = glive[j] ? __builtin_nontemporal_load(
                                               reinterpret_cast<const v4i *>(p.wq + wgo[j] + (size_t)c * 2048))
                                         : v4i{0, 0, 0, 0};
+                if (!XL) {
 #pragma unroll
-                for (int h = 0; h < MH; ++h)
-                    xv[u][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb + (size_t)c * 2048 + h * 256)
-                                        : v4i{0, 0, 0, 0};
+                    for (int h = 0; h < MH; ++h)
+                        xv[u][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb + (size_t)c * 2048 + h * 256)
+                                            : v4i{0, 0, 0, 0};
+                }
             }
         };
 #pragma unroll
         for (int u = 0; u < U; ++u) fetch(u, c0 + u);
+        if (XL && c0 < c1) stage_tokens(4 * c0, 4 * c1);
         for (int c = c0; c < c1; c += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (c + u < c1) {
+                    if (XL) xv[0][0] = *reinterpret_cast<const v4i *>(xs + ((size_t)(4 * (c + u) + ch) * xrows + xrow) * 16);
 #pragma unroll
                     for (int j = 0; j < C; ++j)
 #pragma unroll
                         for (int h = 0; h < MH; ++h)
-                            acc[j][h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[u][j], xv[u][h], acc[j][h], 0, 0, 0);
+                            acc[j][h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wv[u][j], xv[XL ? 0 : u][h], acc[j][h], 0, 0, 0);
                 }
                 fetch(u, c + U + u);
             }
@@ -125,9 +155,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const int per = (G + WAVES - 1) / WAVES;
         const int g0 = wave * per, g1 = (g0 + per < G) ? g0 + per : G;
         const char *xb4 = reinterpret_cast<const char *>(p.xq) + (2 * (ch / 2)) * 1024 + (r + 32 * (ch % 2)) * 16;
-        constexpr int U = C >= 4 ? 1 : 4 / C;     // each slot also holds two token fragments per half
-        v4i wv[U][C], xv[U][2][MH];
-        h4 sg[U][C];
+                // a short ring keeps the register count low: more resident workgroups hide a workgroup's serial
+        // load -> unpack -> multiply -> fold -> reduce chain better than a deeper ring does
+        constexpr int U = C >= 4 ? 1 : 4 / C;   // without XL a slot also holds token fragments
+        v4i wv[U][C], xv[XL ? 1 : U][2][MH];
         auto fetch = [&](int u, int g) {
             if (g < g1) {
 #pragma unroll
@@ -135,24 +166,46 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                     wv[u][j] = glive[j] ? __builtin_nontemporal_load(
                                               reinterpret_cast<const v4i *>(p.wq + wgo[j] + (size_t)g * 2048))
                                         : v4i{0, 0, 0, 0};
-                    sg[u][j] = glive[j] ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)g * p.Npad +
-                                                                        (rg0 + j) * 16 + 4 * ch)
-                                        : h4{0, 0, 0, 0};
+
                 }
+                if (!XL) {
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
+                    for (int t = 0; t < 2; ++t)
 #pragma unroll
-                    for (int h = 0; h < MH; ++h)
-                        xv[u][t][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb4 + ((size_t)4 * g + t) * 1024 + h * 256)
-                                               : v4i{0, 0, 0, 0};
+                        for (int h = 0; h < MH; ++h)
+                            xv[u][t][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb4 + ((size_t)4 * g + t) * 1024 + h * 256)
+                                                   : v4i{0, 0, 0, 0};
+                }
             }
         };
 #pragma unroll
         for (int u = 0; u < U; ++u) fetch(u, g0 + u);
+        if (g0 < g1) {
+            // scales of this wavefront's groups g0..g1-1 for the C channel groups: (g1-g0)*32 contiguous
+            // bytes each in the blob's decode-ordered copy [channel group][K/128][16]
+            const int n16 = (g1 - g0) * 2;             // 16-byte pieces per channel group
+            for (int i = lane; i < C * n16; i += 64) {
+                const int j = i / n16, o = i % n16;
+                v4i v = v4i{0, 0, 0, 0};
+                if (rg0 + j < ngroups)
+                    v = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(p.wscales) +
+                                                       ((size_t)(rg0 + j) * G + g0) * 32 + (size_t)o * 16);
+                *reinterpret_cast<v4i *>(ss + ((size_t)j * G + g0) * 32 + (size_t)o * 16) = v;
+            }
+            if (XL) stage_tokens(8 * g0, 8 * g1);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+        }
         for (int g = g0; g < g1; g += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (g + u < g1) {
+                    if (XL) {
+#pragma unroll
+                        for (int t = 0; t < 2; ++t)   // k-tile 4g + 2(ch/2) + t, half ch%2
+                            xv[0][t][0] = *reinterpret_cast<const v4i *>(
+                                xs + ((size_t)((4 * (g + u) + 2 * (ch / 2) + t) * 2 + (ch % 2)) * xrows + xrow) * 16);
+                    }
 #pragma unroll
                     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -165,8 +218,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                             wf[3] = (int)(w1 & 0xF0F0F0F0u);
 #pragma unroll
                             for (int h = 0; h < MH; ++h)
-                                acc[j][h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xv[u][t][h], acc[j][h], 0, 0, 0);
+                                acc[j][h] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf, xv[XL ? 0 : u][t][h], acc[j][h], 0, 0, 0);
                         }
+                    h4 sgv[C];
+#pragma unroll
+                    for (int j = 0; j < C; ++j)
+                        sgv[j] = *reinterpret_cast<const h4 *>(ss + ((size_t)(j * G + g + u) * 16 + 4 * ch) * 2);
 #pragma unroll
                     for (int j = 0; j < C; ++j)
 #pragma unroll
@@ -174,7 +231,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 #pragma unroll
                             for (int e = 0; e < 4; ++e) {
                                 if (EPI == EPI_F16) {
-                                    accf[j][h][e] = __builtin_fmaf((float)acc[j][h][e], (float)sg[u][j][e], accf[j][h][e]);
+                                    accf[j][h][e] = __builtin_fmaf((float)acc[j][h][e], (float)sgv[j][e], accf[j][h][e]);
                                 } else {
                                     tot[j][h][e] += acc[j][h][e];
                                     if (p.partials) {
@@ -242,7 +299,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     }
 }
 
-template <bool W4, int MH, int C, int EPI>
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     DecodeParams p;
@@ -261,9 +318,20 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     p.N = a.N;
     p.K = a.K;
     p.Npad = round_up(a.N, TILE_ROWS);
-    p.wscales = W4 ? reinterpret_cast<const __half *>(p.wq + w4_scales_offset(a.N, a.K)) : nullptr;
+    p.wscales = W4 ? reinterpret_cast<const __half *>(p.wq + w4_scales_dec_offset(a.N, a.K, a.group)) : nullptr;
     const int grid = ceil_div(p.Npad / 16, C);
-    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI>), dim3(grid), dim3(WAVES * 64), 0, st, p);
+    const size_t xs_bytes = (XL ? (size_t)(a.M + 1) * a.K : 0) + (W4 ? (size_t)C * (a.K / 128) * 32 : 0);
+    if (XL || W4) {   // static reduction buffer + staged tokens/scales can exceed the default 64 KB limit
+        static bool attr_set = false;
+        if (!attr_set) {
+            QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(
+                                                     gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 40960 + 32768),
+                             "hipFuncSetAttribute(max dynamic LDS)"));
+            attr_set = true;
+        }
+    }
+    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL>), dim3(grid), dim3(WAVES * 64), xs_bytes, st, p);
     return check_hip(hipGetLastError(), "gemm_decode launch");
 }
 
@@ -273,19 +341,35 @@ int launch_one(const GemmArgs &a, hipStream_t st)
 template <bool W4, int EPI>
 int by_m(const GemmArgs &a, int variant, hipStream_t st)
 {
-    int c = a.M <= 4 ? 1 : (a.M <= 16 ? 2 : 4);
-    while (c > 1 && ceil_div(round_up(a.N, TILE_ROWS) / 16, c) < 512) c /= 2;
-    if (variant == 101) c = 1;
-    if (variant == 102) c = 2;
-    if (variant == 104) c = 4;
-    if (a.M <= 16) {
-        if (c == 1) return launch_one<W4, 1, 1, EPI>(a, st);
-        if (c == 2) return launch_one<W4, 1, 2, EPI>(a, st);
-        return launch_one<W4, 1, 4, EPI>(a, st);
+    int c = a.M <= 16 ? 2 : 4;
+    const int min_blocks = a.M <= 16 ? 320 : 512;
+    while (c > 1 && ceil_div(round_up(a.N, TILE_ROWS) / 16, c) < min_blocks) c /= 2;
+    if (W4) {   // the staged scales (C * K/128 * 32 bytes of LDS) must stay small
+        while (c > 1 && (size_t)c * (a.K / 128) * 32 > 16384) c /= 2;
     }
-    if (c == 1) return launch_one<W4, 2, 1, EPI>(a, st);
-    if (c == 2) return launch_one<W4, 2, 2, EPI>(a, st);
-    return launch_one<W4, 2, 4, EPI>(a, st);
+    if (variant == 101 || variant == 111) c = 1;
+    if (variant == 102 && (!W4 || (size_t)2 * (a.K / 128) * 32 <= 16384)) c = 2;
+    if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
+    // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
+    const bool wide = c == 1 && (ceil_div(round_up(a.N, TILE_ROWS) / 16, c) <= 256 || variant == 111) && variant != 101;
+    // few tokens: stage them in LDS (ring slots then hold weights only, more bytes in flight per register)
+    const bool xl = (size_t)(a.M + 1) * a.K <= 24576 && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
+    if (xl) {
+        if (wide) return launch_one<W4, 1, 1, EPI, 16, true>(a, st);
+        if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true>(a, st);
+        if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true>(a, st);
+        return launch_one<W4, 1, 4, EPI, 8, true>(a, st);
+    }
+    if (a.M <= 16) {
+        if (wide) return launch_one<W4, 1, 1, EPI, 16>(a, st);
+        if (c == 1) return launch_one<W4, 1, 1, EPI, 8>(a, st);
+        if (c == 2) return launch_one<W4, 1, 2, EPI, 8>(a, st);
+        return launch_one<W4, 1, 4, EPI, 8>(a, st);
+    }
+    if (wide) return launch_one<W4, 2, 1, EPI, 16>(a, st);
+    if (c == 1) return launch_one<W4, 2, 1, EPI, 8>(a, st);
+    if (c == 2) return launch_one<W4, 2, 2, EPI, 8>(a, st);
+    return launch_one<W4, 2, 4, EPI, 8>(a, st);
 }
 
 }  // namespace

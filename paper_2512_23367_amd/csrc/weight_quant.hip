@@ -90,7 +90,8 @@ __global__ void weight_quant8_kernel(const __half *__restrict__ w, int N, int K,
 // group == 128: eight consecutive lanes hold one group.
 __global__ void weight_quant4_kernel(const __half *__restrict__ w, int N, int Npad, int K,
                                      uint8_t *__restrict__ canon, __half *__restrict__ scales,
-                                     uint8_t *__restrict__ kl_codes, __half *__restrict__ kl_scales)
+                                     uint8_t *__restrict__ kl_codes, __half *__restrict__ kl_scales,
+                                     __half *__restrict__ kl_scales_dec)
 {
     const int n = blockIdx.x;
     const int nchunks = K / CHUNK;
@@ -115,6 +116,7 @@ __global__ void weight_quant4_kernel(const __half *__restrict__ w, int N, int Np
         if ((c % 8) == 0) {
             if (n < N && scales) scales[(size_t)n * G + g] = s16;
             if (kl_scales) kl_scales[(size_t)g * Npad + n] = s16;
+            if (kl_scales_dec) kl_scales_dec[((size_t)(n / 16) * G + g) * 16 + n % 16] = s16;
         }
         int q[16];
 #pragma unroll
@@ -185,12 +187,12 @@ int launch_weight_quant8(const __half *w, int N, int K, int8_t *canon, float *sc
 int launch_weight_quant4(const __half *w, int N, int K, int group, uint8_t *canon, __half *scales,
                          uint8_t *kl, hipStream_t st)
 {
-    (void)group;   // validated by the caller: 128
     const int Npad = round_up(N, TILE_ROWS);
     const int rows = kl ? Npad : N;
     __half *kls = kl ? reinterpret_cast<__half *>(kl + w4_scales_offset(N, K)) : nullptr;
+    __half *klsd = kl ? reinterpret_cast<__half *>(kl + w4_scales_dec_offset(N, K, group)) : nullptr;
     hipLaunchKernelGGL(weight_quant4_kernel, dim3(rows), dim3(256), 0, st, w, N, Npad, K, canon, scales,
-                       kl, kls);
+                       kl, kls, klsd);
     return check_hip(hipGetLastError(), "weight_quant4 launch");
 }
 

@@ -32,7 +32,7 @@ def test_version_and_sizes():
     assert (canon, scales, kern) == (100 * 256, 400, 128 * 256)
     canon, scales, kern = binding.ql_weight_bytes(100, 256, 4, 128)
     assert canon == 100 * 128 and scales == 100 * 2 * 2
-    assert kern == 128 * 128 + 2 * 128 * 2           # padded codes (256-aligned) + [K/128][ceil32(N)] fp16
+    assert kern == 128 * 128 + 2 * 512               # padded codes + two 256-aligned copies of the fp16 group scales
     assert binding.ql_act_kernel_bytes(33, 128) == 64 * 128
     assert binding.ql_workspace_bytes(33, 100, 128, 8) >= 64 * 128 + 33 * 4
 
