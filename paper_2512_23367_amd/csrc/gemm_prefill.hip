@@ -11,9 +11,12 @@
 // lane ends up with 4 consecutive output channels of one token per accumulator quad; the epilogue
 // dequantizes in registers, transposes fp16 blocks through LDS and stores 16 bytes per lane.
 //
-// Pipeline: STAGES LDS buffers of KBS k-blocks each; loads for stage it+STAGES-1 are issued while
-// stage it is multiplied; one workgroup barrier per stage.  8 wavefronts (two per SIMD) so that one
-// wavefront's barrier / LDS waits are covered by the other's matrix instructions.
+// Pipeline: STAGES LDS buffers of KBS k-blocks each, loads issued STAGES-1 stages ahead.  The default
+// main loop is a ping-pong: the 8 wavefronts form two groups (one wavefront of each per SIMD) that run
+// one phase apart, so that on every SIMD one wavefront issues matrix instructions while the other reads
+// fragments from LDS, issues global loads and (int4) does the vector-ALU work; every phase ends with the
+// workgroup barrier.  Other variants (4 wavefronts, smaller tiles, a rotated single-phase loop) serve
+// shapes with few tiles and the tests.
 //
 // W4A8: weight tiles hold nibbles; the unpack (shift + mask, giving 16 * code in each byte) sits
 // between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
@@ -77,7 +80,7 @@ __device__ inline void tile_coords(int bid, int tiles_m, int tiles_n, int &tm, i
     tn = in_g / gsize;
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC, bool PP>
 __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kernel(PrefillParams p)
 {
     constexpr int NW = WAVES_M * WAVES_N;
@@ -94,6 +97,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     static_assert(!W4 || KBS == 4, "W4A8: one stage is one scale group (128 k)");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    // behind the stage buffers: the tile's token scales, channel scales and bias as fp32, fetched once at
+    // the start so that the epilogue reads them from LDS instead of waiting for global memory
+    float *side_sx = reinterpret_cast<float *>(smem + STAGES * STAGE_BYTES);
+    float *side_sw = side_sx + TMB * 32;
+    float *side_b = side_sw + TNB * 32;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -101,6 +109,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
 
     int tm, tn;
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+
+    if (EPI == EPI_F16) {
+        for (int t = threadIdx.x; t < TMB * 32; t += NW * 64) {
+            const int m = tm * TMB * 32 + t;
+            side_sx[t] = (m < p.M) ? p.sx[m] : 0.0f;
+        }
+        for (int t = threadIdx.x; t < TNB * 32; t += NW * 64) {
+            const int n = tn * TNB * 32 + t;
+            side_sw[t] = (!W4 && n < p.N) ? p.sw[n] : 0.0f;
+            side_b[t] = (p.bias && n < p.N) ? __half2float(p.bias[n]) : 0.0f;
+        }
+    }   // made visible by the barriers of the main loop / the one in front of the epilogue
 
     const int KB = p.K / 32;                             // k-blocks
     const int nstages = KB / KBS;
@@ -162,7 +182,51 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     const int n_lane0 = (tn * TNB + wn * WN) * 32 + 4 * (lane >> 5);   // + bi*32 + 8*q + (r%4)
     const int m_lane0 = (tm * TMB + wm * WM) * 32 + (lane & 31);       // + bj*32
 
-    if (!W4) {
+    if constexpr (!W4 && PP) {
+        // Ping-pong.  The 8 wavefronts form two groups, one wavefront of each per SIMD (w and w + 4).  A
+        // wavefront alternates between a memory phase (read the 2*(WN+WM) fragments of one 64-k stage from
+        // LDS, issue its share of the global->LDS loads STAGES-1 stages ahead, wait for its loads of the
+        // next stage) and a compute phase (the stage's 2*WN*WM matrix instructions); every phase ends with
+        // the workgroup barrier.  Group 1 runs one phase behind group 0, so on every SIMD one wavefront
+        // computes while the other fetches, and a stage buffer is refilled only after both groups (one
+        // phase apart) have read it.
+        static_assert(KBS == 2 && NW == 8, "ping-pong: 64-k stages, 8 wavefronts");
+        const bool late = wave >= NW / 2;
+        v4i wf[KBS][WN], xf[KBS][WM];
+        wait_vmcnt<(STAGES - 2) * LPW>();        // stage 0 has landed (this wavefront's part)
+        __builtin_amdgcn_s_barrier();            // ... everyone's
+        if (late) __builtin_amdgcn_s_barrier();  // phase shift
+        for (int it = 0; it < nstages; ++it) {
+            // ---- memory phase
+            const char *buf = smem + (it % STAGES) * STAGE_BYTES;
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb) {
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+                    wf[kb][i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb) * 1024 + lane * 16);
+#pragma unroll
+                for (int j = 0; j < WM; ++j)
+                    xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
+            }
+            issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
+            wait_vmcnt<(STAGES - 2) * LPW>();    // own loads of stage it+1 have landed
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragments are in registers, the buffer may be reused
+            __builtin_amdgcn_s_barrier();
+            // ---- compute phase
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb)
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+#pragma unroll
+                    for (int j = 0; j < WM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kb][i], xf[kb][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+        }
+        if (!late) __builtin_amdgcn_s_barrier();
+    }
+    if (!W4 && !PP) {
         // Rotated pipeline.  Fragments of the next k-block are read from LDS while the matrix
         // instructions of the current one run; the stage hand-over (wait for the next stage's loads,
         // barrier, refill of the buffer just freed, first fragment read of the next stage) sits in
@@ -211,7 +275,92 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
             __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
         }
     }
-    if (W4) {
+    if constexpr (W4 && PP) {
+        // Ping-pong for int4 weights (same two phase-shifted groups as above; a stage is one scale group of
+        // 128 k).  Memory phase: read the stage's fragments (nibbles stay packed), fold the PREVIOUS group's
+        // int32 partial into the fp32 sums (accf += float(acc) * scale -- as many vector-ALU cycles as the
+        // stage has matrix cycles, now running under the other group's matrix phase), issue loads, wait.
+        // Compute phase: shift/mask unpack + matrix instructions, the first of each block with C = 0.
+        static_assert(KBS == 4 && NW == 8, "ping-pong: one 128-k group per stage, 8 wavefronts");
+        const bool late = wave >= NW / 2;
+        v4i wp[KBS / 2][WN], xf[KBS][WM];
+        h4 sg[WN][4];
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) sg[i][q] = h4{0, 0, 0, 0};
+        auto fold_all = [&](int g) {                 // group g's partial (g < 0: nothing yet, acc = 0)
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int j = 0; j < WM; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        if (EPI == EPI_F16) {
+                            accf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], (float)sg[i][r / 4][r % 4], accf[i][j][r]);
+                        } else {
+                            tot[i][j][r] += acc[i][j][r];
+                            if (p.partials && g >= 0) {
+                                const int m = m_lane0 + j * 32, n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
+                                if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
+                                    p.partials[((size_t)(m - p.row0) * nstages + g) * p.N + n] = acc[i][j][r] >> 4;
+                            }
+                        }
+                    }
+        };
+        const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        wait_vmcnt<(STAGES - 2) * LPW>();        // stage 0 has landed (this wavefront's part)
+        __builtin_amdgcn_s_barrier();            // ... everyone's
+        if (late) __builtin_amdgcn_s_barrier();  // phase shift
+        for (int it = 0; it < nstages; ++it) {
+            // ---- memory phase
+            const char *buf = smem + (it % STAGES) * STAGE_BYTES;
+#pragma unroll
+            for (int kp = 0; kp < KBS / 2; ++kp)
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+                    wp[kp][i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * WKB + kp) * 1024 + lane * 16);
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb)
+#pragma unroll
+                for (int j = 0; j < WM; ++j)
+                    xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
+            issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
+            fold_all(it - 1);                    // uses the scales loaded one stage ago
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = n_lane0 + i * 32 + 8 * q;     // whole 32-blocks are inside or outside Npad
+                    sg[i][q] = (n < p.Npad) ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)it * p.Npad + n)
+                                            : h4{0, 0, 0, 0};
+                }
+            wait_vmcnt<(STAGES - 2) * LPW + WN * 4>();   // own loads of stage it+1 (the scale loads are younger)
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragments are in registers, the buffer may be reused
+            __builtin_amdgcn_s_barrier();
+            // ---- compute phase
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kb = 0; kb < KBS; ++kb)
+#pragma unroll
+                for (int i = 0; i < WN; ++i) {
+                    const unsigned w0 = (unsigned)wp[kb / 2][i][2 * (kb % 2)], w1 = (unsigned)wp[kb / 2][i][2 * (kb % 2) + 1];
+                    v4i wf;
+                    wf[0] = (int)((w0 << 4) & 0xF0F0F0F0u);
+                    wf[1] = (int)(w0 & 0xF0F0F0F0u);
+                    wf[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
+                    wf[3] = (int)(w1 & 0xF0F0F0F0u);
+#pragma unroll
+                    for (int j = 0; j < WM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[kb][j], kb == 0 ? zero16 : acc[i][j], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_barrier();
+        }
+        if (!late) __builtin_amdgcn_s_barrier();
+        fold_all(nstages - 1);
+    }
+    if constexpr (W4 && !PP) {
         // Per stage (= one scale group of 128 k): 4*WN*WM matrix instructions, and the fold of the group's
         // int32 partial into the fp32 sums (accf += float(acc) * scale: 2 vector-ALU ops per element, about
         // as many cycles as the stage's matrix instructions).  The fold of stage it-1 is done block by block
@@ -323,57 +472,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     __syncthreads();                                   // every wavefront is done with the stage buffers
     char *stg = smem + wave * (32 * ROW_BYTES);
 
-    // per-channel scales and bias of the 4 channels of accumulator quad (i, q)
-    auto load_scales = [&](int i, int q, float (&sw4)[4], float (&b4)[4]) {
-        const int n = n_lane0 + i * 32 + 8 * q;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) sw4[e] = 0.0f, b4[e] = 0.0f;
-        if (n + 3 < p.N) {
-            if (!W4) {
-                const float4 t = *reinterpret_cast<const float4 *>(p.sw + n);
-                sw4[0] = t.x, sw4[1] = t.y, sw4[2] = t.z, sw4[3] = t.w;
-            }
-            if (p.bias) {
-                const h4 bb = *reinterpret_cast<const h4 *>(p.bias + n);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) b4[e] = (float)bb[e];
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (n + e < p.N) {
-                    if (!W4) sw4[e] = p.sw[n + e];
-                    if (p.bias) b4[e] = __half2float(p.bias[n + e]);
-                }
-            }
-        }
-    };
-    constexpr bool PRELOAD = WN <= 2;                  // enough registers to keep all scales resident
-    float swv[PRELOAD ? WN : 1][4][4], bv[PRELOAD ? WN : 1][4][4];
-    if (PRELOAD) {
-#pragma unroll
-        for (int i = 0; i < WN; ++i)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) load_scales(i, q, swv[i][q], bv[i][q]);
-    }
-
     const int n_wave0 = (tn * TNB + wn * WN) * 32;
     const int m_wave0 = (tm * TMB + wm * WM) * 32;
 #pragma unroll
     for (int j = 0; j < WM; ++j) {
-        const int m = m_lane0 + j * 32;
-        const float sxm = (m < p.M) ? p.sx[m] * (W4 ? 0.0625f : 1.0f) : 0.0f;
+        const float sxm = side_sx[(wm * WM + j) * 32 + (lane & 31)] * (W4 ? 0.0625f : 1.0f);
 #pragma unroll
         for (int i = 0; i < WN; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                float sw4[4], b4[4];
-                if (PRELOAD) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) sw4[e] = swv[i][q][e], b4[e] = bv[i][q][e];
-                } else {
-                    load_scales(i, q, sw4, b4);
-                }
+                const int nl = (wn * WN + i) * 32 + 8 * q + 4 * (lane >> 5);   // channel inside the tile
+                const float4 swq = *reinterpret_cast<const float4 *>(side_sw + nl);
+                const float4 bq = *reinterpret_cast<const float4 *>(side_b + nl);
+                const float sw4[4] = {swq.x, swq.y, swq.z, swq.w}, b4[4] = {bq.x, bq.y, bq.z, bq.w};
                 h4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -410,16 +521,16 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
 }
 
 // OCC: wavefronts per SIMD the register allocation must leave room for (workgroups per CU x waves / 4)
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
     constexpr int XFR = WAVES_M * WM * KBS;
     constexpr int WFR = W4 ? WAVES_N * WN * KBS / 2 : WAVES_N * WN * KBS;
-    constexpr int LDS = (XFR + WFR) * 1024 * STAGES;
+    constexpr int LDS = (XFR + WFR) * 1024 * STAGES + (TM + 2 * TN) * 4;   // stages + epilogue side area
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert((STAGES - 2) * (XFR + WFR) / (WAVES_M * WAVES_N) <= 63, "vmcnt range");
-    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC>;
+    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP>;
     static bool attr_set = false;
     if (!attr_set) {
         QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -459,15 +570,18 @@ template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
 {
     if (W4) {
-        // 256 tokens x 128 channels, 8 wavefronts of 64x64: int32 + fp32 accumulators fit 256 registers
-        return launch_one<4, 2, 2, 2, 4, 3, true, EPI>(a, st);
+        if (variant == 1)   // 256 tokens x 128 channels, 8 wavefronts of 64x64, 3 stages, no ping-pong
+            return launch_one<4, 2, 2, 2, 4, 3, true, EPI>(a, st);
+        // 128 tokens x 256 channels (equal bytes of both operands per stage), 8 wavefronts of 64x64 in two
+        // ping-pong groups, 4 stages of one 128-k scale group each
+        return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
     }
     if (variant == 0) {
         // 256x256 tiles run the matrix pipes best, but a grid that fills only part of the last round of
         // 256 CUs wastes more than the smaller tile's extra L2 traffic costs
         const long t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
         const long rounds = (t256 + 255) / 256;
-        variant = 5;
+        variant = 6;
         if (t256 * 10 < rounds * 256 * 8) {
             // 128x128 tiles: three workgroups per CU when there are enough tiles to need them, eight
             // wavefronts per tile when every tile gets a CU of its own
@@ -487,14 +601,14 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 2, 2, 2, 2, 4, false, EPI>(a, st);
     case 5:   // 256x256, 8 wavefronts, 128 k per stage, 2 stages
         return launch_one<2, 4, 4, 2, 4, 2, false, EPI>(a, st);
-    case 6:   // 256x256, 8 wavefronts, 64 k per stage, 5 stages (all 160 KB of LDS)
-        return launch_one<2, 4, 4, 2, 2, 5, false, EPI>(a, st);
     case 7:   // 256x256, 8 wavefronts of 64 tokens x 128 channels, 128 k per stage, 2 stages
         return launch_one<4, 2, 2, 4, 4, 2, false, EPI>(a, st);
     case 11:  // 128x128, 4 wavefronts of 64x64, 3 stages of 64 k: three workgroups per CU
         return launch_one<2, 2, 2, 2, 2, 3, false, EPI, 3>(a, st);
     case 12:  // 128x128, 4 wavefronts of 64x64, 2 stages of 128 k: two workgroups per CU
         return launch_one<2, 2, 2, 2, 4, 2, false, EPI, 2>(a, st);
+    case 6:   // 256x256, 8 wavefronts in two ping-pong groups (one computes while the other fetches), 64-k stages
+        return launch_one<2, 4, 4, 2, 2, 4, false, EPI, 1, true>(a, st);
     case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU)
         return launch_one<4, 2, 1, 2, 2, 4, false, EPI>(a, st);
     case 14:  // 128x128, 8 wavefronts of 64 tokens x 32 channels
