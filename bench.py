@@ -115,6 +115,30 @@ def best_time_ms(torch, fn, reps, per_launch=False, warm=30, rounds=5):
     return min(event_time_ms(torch, fn, reps, per_launch) for _ in range(rounds))
 
 
+def graph_time_ms(torch, fn, reps, warm=10, rounds=5):
+    """Average GPU time of fn(i) with `reps` launches captured into one HIP graph and replayed: for kernels
+    of a few microseconds the Python/ctypes/hipLaunchKernel path (~7 us per call) would otherwise be what is
+    measured.  Best of `rounds` replays, each bracketed by HIP events on the replay stream."""
+    for i in range(warm):
+        fn(i)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for i in range(reps):
+            fn(i)
+    g.replay()
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(rounds):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        best = min(best, a.elapsed_time(b) / reps)
+    return best
+
+
 def profiled_traffic(cfg):
     """HBM bytes per GEMM launch (average over the workload's linears) from the committed rocprofv3
     FETCH_SIZE + WRITE_SIZE summary of this workload, copy-kernel calibrated; None if not profiled."""
@@ -155,7 +179,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config1", help="config1 (default), config2, config3")
+    ap.add_argument("--workload", default="config1",
+                    help="config1 (default), config2, config3, config4 (long prefill), decode8, decode4 "
+                         "(the 7B-class decode GEMMs of config 4, int8 / int4 weights)")
+    ap.add_argument("--decode-m", type=int, default=1, help="tokens of the decode workloads: 1, 8 or 32")
     ap.add_argument("--variant", type=int, default=0, help="kernel variant (0 = automatic)")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape table of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
@@ -186,14 +213,26 @@ def main():
         return
     ql.lib()
     ql.ql_set_kernel_variant(args.variant)
-    cfg = int(args.workload.replace("config", ""))
-    shapes = [s for s in synth.workload(cfg) if s.M > 32]
+    decode = args.workload.startswith("decode")
+    if decode:
+        bits = int(args.workload.replace("decode", ""))
+        cfg = 4
+        shapes = [s for s in synth.workload(4) if s.M == args.decode_m and s.bits == bits]
+    else:
+        cfg = int(args.workload.replace("config", ""))
+        shapes = [s for s in synth.workload(cfg) if s.M > 32]
     descr = {1: "config1: W8A8 linears of a 1B-class decoder layer, prefill M=2048, d=1536 (qkv, o, gate_up, down)",
              2: "config2: W8A8 linears (+bias) of a 7B-class decoder layer, prefill M=4096, d=4096",
              3: "config3: W4A8 (group 128) linears of a 7B-class decoder layer, prefill M=4096, d=4096",
              4: "config4: long-reasoning prefill of the down projection, M=16384, W8A8"}[cfg]
+    if decode:
+        descr = (f"config4 decode: {'W8A8' if bits == 8 else 'W4A8 (group 128)'} linears of a 7B-class decoder "
+                 f"layer, M={args.decode_m} (qkv, o, gate_up, down), weights rotated over >768 MB of copies")
 
-    layers = [Layer(s, torch, ql, synth) for s in shapes]
+    def copies_for(s):   # decode: enough copies that the weight stream cannot come from the Infinity Cache
+        return -(-3 * MALL_BYTES // (s.N * s.K // (1 if s.bits == 8 else 2))) if decode else 1
+
+    layers = [Layer(s, torch, ql, synth, copies_for(s)) for s in shapes]
     total_ops = sum(s.ops for s in shapes)
 
     def step(i=0):
@@ -203,19 +242,37 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    graph = None
+    if decode:
+        # a decode step is 8 launches of 4-16 us: replay them from a HIP graph so that the GPU, not the
+        # launch path, is timed (the warm-up above ran every kernel once outside the capture)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for i in range(args.steps):
+                step(i)
+        graph.replay()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
+    if graph is not None:
+        graph.replay()
+    else:
+        for i in range(args.steps):
+            step(i)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     value = total_ops / (dt / args.steps) / 1e12
-    log(f"[step] {descr}: {ms_per_step:.4f} ms/step, {value:.1f} TOPS whole layer (quant + GEMM + epilogue)")
+    unit = "TOPS"
+    if decode:   # memory-bound: report the algorithmic bytes of the GEMMs per second
+        value = sum(l.gemm_bytes() for l in layers) / (dt / args.steps) / 1e9
+        unit = "GB/s"
+    log(f"[step] {descr}: {ms_per_step:.4f} ms/step, {value:.1f} {unit} whole layer (quant + GEMM + epilogue)")
 
     out = {
-        "metric": METRIC, "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "metric": METRIC, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "launch": "hip graph replay" if decode else "stream launches",
         "config": {"workload": descr, "layers": [s.name for s in shapes],
                    "weights": "int8 per-channel" if shapes[0].bits == 8 else "int4 group-128",
                    "activations": "int8 per-token dynamic", "output": "fp16"},
@@ -232,14 +289,22 @@ def main():
     for l in layers:
         # one event pair around `reps` back-to-back launches: per-launch pairs add ~2-7 us of event
         # overhead to kernels this short and would not agree with the profiler's kernel durations
-        gemm_ms.append(best_time_ms(torch, l.gemm, reps))
+        timer = graph_time_ms if decode else best_time_ms
+        gemm_ms.append(timer(torch, l.gemm, reps))
         gemm_ms_b2b.append(best_time_ms(torch, l.gemm, reps, per_launch=True, warm=0, rounds=1))
-        quant_ms.append(best_time_ms(torch, lambda i, l=l: l.quant(), reps))
+        quant_ms.append(timer(torch, lambda i, l=l: l.quant(), reps))
     achieved = total_ops / (sum(gemm_ms) * 1e-3) / 1e12
+    roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+            "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": profiled_traffic(cfg),
+            "kernel": "gemm_prefill_kernel (int8 MFMA GEMM + fused dequant epilogue), one launch per linear"}
+    if decode:
+        achieved = sum(l.gemm_bytes() for l in layers) / (sum(gemm_ms) * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                "kernel": "gemm_decode_kernel (weight-streaming int8 MFMA GEMM + fused epilogue), one launch per linear",
+                "per_layer_gbs": {l.sh.layer: round(l.gemm_bytes() / (t * 1e-3) / 1e9, 1) for l, t in zip(layers, gemm_ms)}}
     out["roofline"] = {
-        "bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-        "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": profiled_traffic(cfg),
-        "kernel": "gemm_prefill_kernel (int8 MFMA GEMM + fused dequant epilogue), one launch per linear",
+        **roof,
         "launch_us": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, gemm_ms)},
         "launch_us_event_pair_each": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, gemm_ms_b2b)},
         "per_layer_tops": {l.sh.layer: round(l.sh.ops / (t * 1e-3) / 1e12, 1) for l, t in zip(layers, gemm_ms)},
@@ -249,7 +314,7 @@ def main():
     log("[roofline]", json.dumps(out["roofline"]))
 
     # ---- detail: GEMM-only throughput of the other configurations (parity-test cases, not the headline)
-    if not args.no_detail:
+    if not args.no_detail and not decode:
         detail = []
         del layers
         torch.cuda.empty_cache()
@@ -271,8 +336,9 @@ def main():
                         l.kernels, l.scales, l.sw = base.kernels, base.scales, base.sw
                     l.quant()
                     r = 20 if not decode else max(50, 2 * copies)
-                    t_bb = best_time_ms(torch, l.gemm, r)
-                    t_lin = best_time_ms(torch, l.linear, r, warm=3, rounds=2)
+                    timer = graph_time_ms if decode else best_time_ms
+                    t_bb = timer(torch, l.gemm, r)
+                    t_lin = timer(torch, l.linear, r, warm=3, rounds=2)
                     row = {"shape": sh.name, "gemm_us": round(t_bb * 1e3, 2), "linear_us": round(t_lin * 1e3, 2)}
                     if not decode:
                         row["tops"] = round(sh.ops / (t_bb * 1e-3) / 1e12, 1)

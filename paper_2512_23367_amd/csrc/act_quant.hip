@@ -1,7 +1,7 @@
 // Per-token dynamic int8 activation quantization (paper Eq. 1-2 with n = 8; one scale per token
 // over its whole feature dimension, Preliminary section) for gfx950.
 //
-// One workgroup per 8 tokens.  The rows are read once: each lane keeps its 16-element chunks in
+// One workgroup per 8 tokens (per token when there are at most 4).  The rows are read once: each lane keeps its 16-element chunks in
 // registers, the row maxima are reduced across lanes and wavefronts, then the codes are produced
 // from the registers and written row-major and/or in the GEMM's tile order, whole 128-byte lines
 // at a time.
@@ -64,25 +64,28 @@ __device__ inline uint4 quant_chunk(const Half16 &v, float inv)
     return q;
 }
 
-// One workgroup quantizes 8 consecutive tokens.  A wavefront covers 8 tokens x 8 chunks per step
-// (lane = token % 8 + 8 * chunk), so that in the GEMM's tile order the 8 lanes of one chunk write
-// one whole 128-byte line (8 token slots x 16 bytes) and in the row-major copy each token gets
-// 128 contiguous bytes per step.  The NW wavefronts split K; the row maxima meet in LDS.
-// NIT: steps per wavefront kept in registers (NW * NIT * 128 >= K); NIT == 0: the row is read twice.
-constexpr int ROWS_PER_BLOCK = 8;
+// One workgroup quantizes RPB consecutive tokens.  RPB = 8 (prefill): a wavefront covers 8 tokens x 8
+// chunks per step (lane = token % 8 + 8 * chunk), so that in the GEMM's tile order the 8 lanes of one
+// chunk write one whole 128-byte line (8 token slots x 16 bytes) and in the row-major copy each token
+// gets 128 contiguous bytes per step.  RPB = 1 (a handful of decode tokens): all 64 lanes of a wavefront
+// work on the same token, 64 chunks per step, so that a single token is not left to 8 lanes.
+// The NW wavefronts split K; the row maxima meet in LDS.
+// NIT: steps per wavefront kept in registers; NIT == 0: the row is read twice.
+constexpr int MAX_RPB = 8;
 constexpr int MAX_WAVES = 8;
 
-template <int NIT>
+template <int NIT, int RPB>
 __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half *__restrict__ x, int64_t ldx,
                                                                     int M, int K, int per_wave,
                                                                     int8_t *__restrict__ xq_rm,
                                                                     int8_t *__restrict__ xq_kl,
                                                                     float *__restrict__ sx)
 {
-    __shared__ unsigned red[ROWS_PER_BLOCK][MAX_WAVES];
+    __shared__ unsigned red[MAX_RPB][MAX_WAVES];
+    constexpr int CPS = 64 / RPB;                       // chunks per wavefront per step
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
-    const int r = lane & 7, cl = lane >> 3;
-    const int m = blockIdx.x * ROWS_PER_BLOCK + r;
+    const int r = lane % RPB, cl = lane / RPB;
+    const int m = blockIdx.x * RPB + r;
     const bool valid = m < M;
     const int nchunks = K / CHUNK;
     const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)(valid ? m : 0) * ldx);
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     if (NIT > 0) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int c = (s0 + i) * 8 + cl;
+            const int c = (s0 + i) * CPS + cl;
             if (i < per_wave && c < nchunks && valid) {
                 v[i] = row[c];
                 mx = abs_max_bits(v[i], mx);
@@ -101,13 +104,12 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
         }
     } else {
         for (int i = 0; i < per_wave; ++i) {
-            const int c = (s0 + i) * 8 + cl;
+            const int c = (s0 + i) * CPS + cl;
             if (c < nchunks && valid) mx = abs_max_bits(row[c], mx);
         }
     }
-    mx = max(mx, (unsigned)__shfl_xor((int)mx, 8, 64));
-    mx = max(mx, (unsigned)__shfl_xor((int)mx, 16, 64));
-    mx = max(mx, (unsigned)__shfl_xor((int)mx, 32, 64));
+#pragma unroll
+    for (int off = 32; off >= RPB; off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
     if (cl == 0) red[r][wave] = mx;
     __syncthreads();
     mx = 0;
@@ -127,12 +129,12 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     if (NIT > 0) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const int c = (s0 + i) * 8 + cl;
+            const int c = (s0 + i) * CPS + cl;
             if (i < per_wave && c < nchunks && valid) emit(c, v[i]);
         }
     } else {
         for (int i = 0; i < per_wave; ++i) {
-            const int c = (s0 + i) * 8 + cl;
+            const int c = (s0 + i) * CPS + cl;
             if (c < nchunks && valid) emit(c, row[c]);
         }
     }
@@ -153,16 +155,16 @@ __global__ void act_repack_kernel(const int8_t *__restrict__ xq_rm, int M, int K
 
 }  // namespace
 
-int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, int8_t *xq_kl,
-                     float *sx, hipStream_t st)
+template <int RPB>
+static void launch_aq(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, int8_t *xq_kl, float *sx,
+                      hipStream_t st)
 {
-    if (M == 0) return QL_OK;
-    const int steps = ceil_div(K / CHUNK, 8);            // 128 k per wavefront per step
+    const int steps = ceil_div(K / CHUNK, 64 / RPB);
     const int nw = steps < MAX_WAVES ? steps : MAX_WAVES;
     const int per_wave = ceil_div(steps, nw);
-    dim3 grid(ceil_div(M, ROWS_PER_BLOCK)), block(nw * 64);
+    dim3 grid(ceil_div(M, RPB)), block(nw * 64);
 #define QL_LAUNCH_AQ(NIT) \
-    hipLaunchKernelGGL(act_quant_kernel<NIT>, grid, block, 0, st, x, ldx, M, K, per_wave, xq_rm, xq_kl, sx)
+    hipLaunchKernelGGL((act_quant_kernel<NIT, RPB>), grid, block, 0, st, x, ldx, M, K, per_wave, xq_rm, xq_kl, sx)
     if (per_wave <= 1) QL_LAUNCH_AQ(1);
     else if (per_wave <= 2) QL_LAUNCH_AQ(2);
     else if (per_wave <= 4) QL_LAUNCH_AQ(4);
@@ -170,6 +172,14 @@ int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, 
     else if (per_wave <= 12) QL_LAUNCH_AQ(12);
     else QL_LAUNCH_AQ(0);
 #undef QL_LAUNCH_AQ
+}
+
+int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, int8_t *xq_kl,
+                     float *sx, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    if (M <= 4) launch_aq<1>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
+    else launch_aq<8>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant launch");
 }
 

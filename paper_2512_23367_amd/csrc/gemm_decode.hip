@@ -77,6 +77,26 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
             }
         }
 
+    // The finishing wavefronts (w < C handles channel group w) fetch their scales and bias now, so that the
+    // epilogue does not end with a dependent trip to memory.
+    float e_sx[MH], e_sw[4], e_b[4];
+#pragma unroll
+    for (int h = 0; h < MH; ++h) e_sx[h] = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) e_sw[e] = 0.0f, e_b[e] = 0.0f;
+    if (EPI == EPI_F16 && wave < C) {
+        const int n0 = (rg0 + wave) * 16 + 4 * ch;
+#pragma unroll
+        for (int h = 0; h < MH; ++h)
+            if (r + 16 * h < p.M) e_sx[h] = p.sx[r + 16 * h] * (W4 ? 0.0625f : 1.0f);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (n0 + e < p.N) {
+                if (!W4) e_sw[e] = p.sw[n0 + e];
+                if (p.bias) e_b[e] = __half2float(p.bias[n0 + e]);
+            }
+    }
+
     // byte offset of channel group rg0+j inside the weight blob, for this lane
     size_t wgo[C];
     bool glive[C];
@@ -286,14 +306,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                 if (n0 + e < p.N) p.acc[(size_t)m * p.N + n0 + e] = W4 ? (si[e] >> 4) : si[e];
             continue;
         }
-        const float sxm = p.sx[m] * (W4 ? 0.0625f : 1.0f);
+        const float sxm = e_sx[h];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (n0 + e >= p.N) break;
-            const float b = p.bias ? __half2float(p.bias[n0 + e]) : 0.0f;
             float v;
-            if (W4) v = __builtin_fmaf(sf[e], sxm, b);
-            else v = __builtin_fmaf((float)si[e] * sxm, p.sw[n0 + e], b);
+            if (W4) v = __builtin_fmaf(sf[e], sxm, e_b[e]);
+            else v = __builtin_fmaf((float)si[e] * sxm, e_sw[e], e_b[e]);
             p.y[(size_t)m * p.ldy + n0 + e] = __float2half_rn(v);
         }
     }
