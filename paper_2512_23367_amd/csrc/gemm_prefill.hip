@@ -93,7 +93,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     constexpr int STAGE_BYTES = (XFR + WFR) * 1024;
     static_assert(XFR % NW == 0 && WFR % NW == 0, "fragments must divide evenly over the wavefronts");
     constexpr int XL = XFR / NW, WL = WFR / NW;          // loads per wavefront per stage
-    constexpr int LPW = XL + WL;
+    constexpr bool SCALE_DMA = W4 && PP;                 // group scales travel with the stage, through LDS
+    constexpr int LPW = XL + WL + (SCALE_DMA ? 1 : 0);
     static_assert(!W4 || KBS == 4, "W4A8: one stage is one scale group (128 k)");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -102,6 +103,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     float *side_sx = reinterpret_cast<float *>(smem + STAGES * STAGE_BYTES);
     float *side_sw = side_sx + TMB * 32;
     float *side_b = side_sw + TNB * 32;
+    // int4 ping-pong: per stage and wavefront a 256-byte slot with the fp16 group scales of its WN*32 channels
+    char *scale_slots = reinterpret_cast<char *>(side_b + TNB * 32);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -126,6 +129,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     const int nstages = KB / KBS;
     const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, p.x_bytes);
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.w_bytes);
+    const __amdgpu_buffer_rsrc_t sr = make_rsrc(p.wscales, W4 ? (unsigned)(p.K / 128) * p.Npad * 2u : 0u);
     const unsigned voff = lane * 16;
 
     // Fragment f of a stage lives at LDS offset f*1024 and, in global memory, at
@@ -149,6 +153,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
             unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + s * WKB + kb) * 1024u;
             if (!live) off = 0xFFFFF000u;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + WOFF + f * 1024), 16, voff, off, 0, 0);
+        }
+        if (SCALE_DMA) {   // stage s = scale group s: 4 bytes per lane, the first WN*16 lanes carry the wavefront's channels
+            unsigned off = ((unsigned)s * p.Npad + (tn * TNB + wn * WN) * 32) * 2u;
+            if (!live) off = 0xFFFFF000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(sr, LDS_PTR(scale_slots + ((s % STAGES) * NW + wave) * 256), 4,
+                                                     lane * 4, off, 0, 0);
         }
     };
 
@@ -315,6 +325,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
         for (int it = 0; it < nstages; ++it) {
             // ---- memory phase
             const char *buf = smem + (it % STAGES) * STAGE_BYTES;
+            if (it > 0) {   // scales of the group whose partial sits in acc (their slot is refilled below)
+                const char *slot = scale_slots + (((it - 1) % STAGES) * NW + wave) * 256;
+#pragma unroll
+                for (int i = 0; i < WN; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        sg[i][q] = *reinterpret_cast<const h4 *>(slot + (i * 32 + 8 * q + 4 * (lane >> 5)) * 2);
+            }
 #pragma unroll
             for (int kp = 0; kp < KBS / 2; ++kp)
 #pragma unroll
@@ -326,16 +344,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
                 for (int j = 0; j < WM; ++j)
                     xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
             issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
-            fold_all(it - 1);                    // uses the scales loaded one stage ago
-#pragma unroll
-            for (int i = 0; i < WN; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n_lane0 + i * 32 + 8 * q;     // whole 32-blocks are inside or outside Npad
-                    sg[i][q] = (n < p.Npad) ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)it * p.Npad + n)
-                                            : h4{0, 0, 0, 0};
-                }
-            wait_vmcnt<(STAGES - 2) * LPW + WN * 4>();   // own loads of stage it+1 (the scale loads are younger)
+            fold_all(it - 1);
+            wait_vmcnt<(STAGES - 2) * LPW>();    // own loads of stage it+1 have landed
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragments are in registers, the buffer may be reused
             __builtin_amdgcn_s_barrier();
             // ---- compute phase
@@ -358,6 +368,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
             __builtin_amdgcn_s_barrier();
         }
         if (!late) __builtin_amdgcn_s_barrier();
+        {
+            const char *slot = scale_slots + (((nstages - 1) % STAGES) * NW + wave) * 256;
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    sg[i][q] = *reinterpret_cast<const h4 *>(slot + (i * 32 + 8 * q + 4 * (lane >> 5)) * 2);
+        }
         fold_all(nstages - 1);
     }
     if constexpr (W4 && !PP) {
@@ -527,9 +545,10 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
     constexpr int XFR = WAVES_M * WM * KBS;
     constexpr int WFR = W4 ? WAVES_N * WN * KBS / 2 : WAVES_N * WN * KBS;
-    constexpr int LDS = (XFR + WFR) * 1024 * STAGES + (TM + 2 * TN) * 4;   // stages + epilogue side area
+    constexpr int LDS = (XFR + WFR) * 1024 * STAGES + (TM + 2 * TN) * 4 +   // stages + epilogue side area
+                        ((W4 && PP) ? STAGES * WAVES_M * WAVES_N * 256 : 0);  // + int4 group-scale slots
     static_assert(LDS <= 160 * 1024, "LDS budget");
-    static_assert((STAGES - 2) * (XFR + WFR) / (WAVES_M * WAVES_N) <= 63, "vmcnt range");
+    static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N) + 1) <= 63, "vmcnt range");
     auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP>;
     static bool attr_set = false;
     if (!attr_set) {
