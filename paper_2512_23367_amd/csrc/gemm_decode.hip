@@ -360,17 +360,25 @@ int launch_one(const GemmArgs &a, hipStream_t st)
 template <bool W4, int EPI>
 int by_m(const GemmArgs &a, int variant, hipStream_t st)
 {
-    int c = a.M <= 16 ? 2 : 4;
-    const int min_blocks = a.M <= 16 ? 320 : 512;
-    while (c > 1 && ceil_div(round_up(a.N, TILE_ROWS) / 16, c) < min_blocks) c /= 2;
+    const int groups = round_up(a.N, TILE_ROWS) / 16;
+    int c;
+    if (a.M <= 16) {
+        c = 2;
+        while (c > 1 && ceil_div(groups, c) < 320) c /= 2;
+    } else {
+        // 17..32 tokens: token fragments are 2/C of the bytes a wavefront pulls through its CU's L1, so
+        // three channel groups per workgroup as soon as that still leaves one workgroup per CU
+        c = groups >= 768 ? 3 : groups >= 512 ? 2 : 1;
+    }
     if (W4) {   // the staged scales (C * K/128 * 32 bytes of LDS) must stay small
-        while (c > 1 && (size_t)c * (a.K / 128) * 32 > 16384) c /= 2;
+        while (c > 1 && (size_t)c * (a.K / 128) * 32 > 16384) --c;
     }
     if (variant == 101 || variant == 111) c = 1;
     if (variant == 102 && (!W4 || (size_t)2 * (a.K / 128) * 32 <= 16384)) c = 2;
+    if (variant == 103 && a.M > 16 && (!W4 || (size_t)3 * (a.K / 128) * 32 <= 16384)) c = 3;
     if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
     // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
-    const bool wide = c == 1 && (ceil_div(round_up(a.N, TILE_ROWS) / 16, c) <= 256 || variant == 111) && variant != 101;
+    const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101;
     // few tokens: stage them in LDS (ring slots then hold weights only, more bytes in flight per register)
     const bool xl = (size_t)(a.M + 1) * a.K <= 24576 && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
     if (xl) {
@@ -388,6 +396,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     if (wide) return launch_one<W4, 2, 1, EPI, 16>(a, st);
     if (c == 1) return launch_one<W4, 2, 1, EPI, 8>(a, st);
     if (c == 2) return launch_one<W4, 2, 2, EPI, 8>(a, st);
+    if (c == 3) return launch_one<W4, 2, 3, EPI, 8>(a, st);
     return launch_one<W4, 2, 4, EPI, 8>(a, st);
 }
 

@@ -120,6 +120,32 @@ def test_w8a8_accumulators_bit_exact_decode(G, M, K, N):
     assert (acc == oracle.igemm(xq, g["canon"])).all()
 
 
+DECODE_VARIANTS = [101, 102, 103, 104, 111, 121]   # 1/2/3/4 channel groups per workgroup, 16 wavefronts, tokens from L2
+
+
+@pytest.mark.parametrize("variant", DECODE_VARIANTS)
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N", [(1, 1024, 200), (8, 4096, 136), (17, 512, 72), (32, 1536, 200)])
+def test_decode_variants_bit_exact_and_within_tolerance(G, variant, bits, M, K, N):
+    rng = np.random.default_rng(M + K + N + bits)
+    xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    w = synth.weights(N, K, 0, "single")
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
+    ql.ql_set_kernel_variant(variant)
+    if bits == 8:
+        acc, _ = G.gpu_acc(xq, g)
+        assert (acc == oracle.igemm(xq, g["canon"])).all()
+    else:
+        _, total, part = oracle.igemm_grouped(xq, oracle.unpack_int4(g["canon"]), g["scales"], 128, want_partials=True)
+        acc, gpart = G.gpu_acc(xq, g, want_partials=True)
+        assert (acc == total).all() and (gpart == part).all()
+    x = synth.activations(M, K, 0, "single")
+    b = synth.bias(N, 0, "single")
+    ref = (oracle.linear_w8a8(x, g["canon"], g["scales"], b) if bits == 8
+           else oracle.linear_w4a8(x, g["canon"], g["scales"], 128, b))
+    assert G.norm_err(G.gpu_linear(x, g, b), ref["y64"]) <= TOL
+
+
 def test_w8a8_accumulator_extremes(G):
     K = 11008
     xq = np.full((2, K), 127, dtype=np.int8)
