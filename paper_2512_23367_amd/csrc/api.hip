@@ -165,7 +165,7 @@ const char *ql_last_error(void) { return g_err; }
 
 int ql_set_kernel_variant(int variant)
 {
-    if (variant < 0 || (variant > 14 && variant < 100) || (variant > 104 && variant != 111 && variant != 121))
+    if (variant < 0 || (variant > 19 && variant < 100) || (variant > 104 && variant != 111 && variant != 121))
         return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);
     g_variant = variant;
     return QL_OK;

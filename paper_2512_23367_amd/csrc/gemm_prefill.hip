@@ -15,13 +15,15 @@
 // main loop is a ping-pong: the 8 wavefronts form two groups (one wavefront of each per SIMD) that run
 // one phase apart, so that on every SIMD one wavefront issues matrix instructions while the other reads
 // fragments from LDS, issues global loads and (int4) does the vector-ALU work; every phase ends with the
-// workgroup barrier.  Other variants (4 wavefronts, smaller tiles, a rotated single-phase loop) serve
-// shapes with few tiles and the tests.
+// workgroup barrier.  Other variants (256x192 tiles, 128x128 tiles with 4 wavefronts or with the two groups
+// splitting the k-blocks of every stage, a rotated single-phase loop) serve shapes whose 256x256 tile count
+// fills the 256 CUs badly, and the tests; the automatic choice compares rounds x tile area / measured rate.
 //
 // W4A8: weight tiles hold nibbles; the unpack (shift + mask, giving 16 * code in each byte) sits
 // between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
 // an fp32 accumulator with the group's scale.
 #include "common.h"
+#include <type_traits>
 
 namespace ql {
 namespace {
@@ -80,10 +82,14 @@ __device__ inline void tile_coords(int bid, int tiles_m, int tiles_n, int &tm, i
     tn = in_g / gsize;
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC, bool PP>
-__global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kernel(PrefillParams p)
+// WK = 2: the k-blocks of every stage are split between two sets of WAVES_M x WAVES_N wavefronts (the two
+// ping-pong groups) that work on the same output tile and add their accumulators through LDS at the end;
+// gives 64x64 accumulators per wavefront on a 128x128 tile, for shapes with too few tiles for larger ones.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC, bool PP, int WK>
+__global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_kernel(PrefillParams p)
 {
-    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int NW = WAVES_M * WAVES_N * WK;
+    static_assert(WK == 1 || (WK == 2 && PP && !W4 && WM % 2 == 0), "k-split: int8 ping-pong kernels only");
     constexpr int TMB = WAVES_M * WM;                    // activation row-blocks per workgroup tile
     constexpr int TNB = WAVES_N * WN;                    // weight row-blocks per workgroup tile
     constexpr int XFR = TMB * KBS;                       // 1024-byte fragments per stage: activations
@@ -91,10 +97,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     constexpr int WKB = W4 ? KBS / 2 : KBS;              // weight fragments per row-block per stage
     constexpr int XOFF = 0, WOFF = XFR * 1024;
     constexpr int STAGE_BYTES = (XFR + WFR) * 1024;
-    static_assert(XFR % NW == 0 && WFR % NW == 0, "fragments must divide evenly over the wavefronts");
-    constexpr int XL = XFR / NW, WL = WFR / NW;          // loads per wavefront per stage
+    // Fragment f of a stage is loaded by wavefront f % NW.  When the count does not divide evenly the first
+    // FR % NW wavefronts issue one load more per stage than the others (LPW_HI / LPW_LO loads).
+    constexpr int FR = XFR + WFR;
     constexpr bool SCALE_DMA = W4 && PP;                 // group scales travel with the stage, through LDS
-    constexpr int LPW = XL + WL + (SCALE_DMA ? 1 : 0);
+    constexpr int LPW_HI = (FR + NW - 1) / NW + (SCALE_DMA ? 1 : 0);
+    constexpr int LPW_LO = FR / NW + (SCALE_DMA ? 1 : 0);
+    constexpr int NHI = FR % NW;                         // wavefronts 0 .. NHI-1 issue LPW_HI loads
     static_assert(!W4 || KBS == 4, "W4A8: one stage is one scale group (128 k)");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const int wm = wave % WAVES_M, wn = (wave / WAVES_M) % WAVES_N, wk = wave / (WAVES_M * WAVES_N);
 
     int tm, tn;
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -132,34 +141,43 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     const __amdgpu_buffer_rsrc_t sr = make_rsrc(p.wscales, W4 ? (unsigned)(p.K / 128) * p.Npad * 2u : 0u);
     const unsigned voff = lane * 16;
 
-    // Fragment f of a stage lives at LDS offset f*1024 and, in global memory, at
+    // Fragment f of a stage lives at LDS offset f*1024 (activation fragments first) and, in global memory, at
     //   row-block base + (stage * fragments-per-row-block + f % fragments-per-row-block) * 1024.
-    // Wavefront w loads activation fragments [w*XL, (w+1)*XL) and weight fragments [w*WL, (w+1)*WL).
     auto issue_stage = [&](int s) {
         const bool live = s < nstages;
         char *buf = smem + (s % STAGES) * STAGE_BYTES;
+        auto load_fragment = [&](int i) {                // i-th load of this wavefront: fragment i*NW + wave
+            const int f = i * NW + wave;
+            // (when the activation fragments fill whole rounds the operand is known at compile time)
+            const bool is_x = (XFR % NW == 0) ? (i < XFR / NW) : (f < XFR);
+            if (is_x) {
+                const int mb = f / KBS, kb = f % KBS;
+                unsigned off = ((unsigned)(tm * TMB + mb) * KB + s * KBS + kb) * 1024u;
+                if (!live) off = 0xFFFFF000u;            // beyond the buffer: the load returns nothing
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(buf + f * 1024), 16, voff, off, 0, 0);
+            } else {
+                const int g = f - XFR;
+                const int nb = g / WKB, kb = g % WKB;
+                unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + s * WKB + kb) * 1024u;
+                if (!live) off = 0xFFFFF000u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + f * 1024), 16, voff, off, 0, 0);
+            }
+        };
 #pragma unroll
-        for (int i = 0; i < XL; ++i) {
-            const int f = wave * XL + i;
-            const int mb = f / KBS, kb = f % KBS;
-            unsigned off = ((unsigned)(tm * TMB + mb) * KB + s * KBS + kb) * 1024u;
-            if (!live) off = 0xFFFFF000u;                // beyond the buffer: the load returns nothing
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(buf + XOFF + f * 1024), 16, voff, off, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < WL; ++i) {
-            const int f = wave * WL + i;
-            const int nb = f / WKB, kb = f % WKB;
-            unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + s * WKB + kb) * 1024u;
-            if (!live) off = 0xFFFFF000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + WOFF + f * 1024), 16, voff, off, 0, 0);
-        }
+        for (int i = 0; i < FR / NW; ++i) load_fragment(i);
+        if (NHI != 0 && wave < NHI) load_fragment(FR / NW);
         if (SCALE_DMA) {   // stage s = scale group s: 4 bytes per lane, the first WN*16 lanes carry the wavefront's channels
             unsigned off = ((unsigned)s * p.Npad + (tn * TNB + wn * WN) * 32) * 2u;
             if (!live) off = 0xFFFFF000u;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(sr, LDS_PTR(scale_slots + ((s % STAGES) * NW + wave) * 256), 4,
                                                      lane * 4, off, 0, 0);
         }
+    };
+
+    // wait until all but this wavefront's loads of the newest STAGES-2 stages have landed
+    auto wait_stage = [&]() {
+        if (NHI == 0 || wave < NHI) wait_vmcnt<(STAGES - 2) * LPW_HI>();
+        else wait_vmcnt<(STAGES - 2) * LPW_LO>();
     };
 
     v16i acc[WN][WM];
@@ -200,32 +218,33 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
         // the workgroup barrier.  Group 1 runs one phase behind group 0, so on every SIMD one wavefront
         // computes while the other fetches, and a stage buffer is refilled only after both groups (one
         // phase apart) have read it.
-        static_assert(KBS == 2 && NW == 8, "ping-pong: 64-k stages, 8 wavefronts");
+        static_assert(KBS == 2 * WK && NW % 8 == 0, "ping-pong: 64 k per wavefront and stage, two groups with equally many wavefronts on every SIMD");
         const bool late = wave >= NW / 2;
-        v4i wf[KBS][WN], xf[KBS][WM];
-        wait_vmcnt<(STAGES - 2) * LPW>();        // stage 0 has landed (this wavefront's part)
+        const int kb0 = (WK == 2) ? 2 * wk : 0;   // first of this wavefront's two k-blocks in a stage
+        v4i wf[2][WN], xf[2][WM];
+        wait_stage();        // stage 0 has landed (this wavefront's part)
         __builtin_amdgcn_s_barrier();            // ... everyone's
         if (late) __builtin_amdgcn_s_barrier();  // phase shift
         for (int it = 0; it < nstages; ++it) {
             // ---- memory phase
             const char *buf = smem + (it % STAGES) * STAGE_BYTES;
 #pragma unroll
-            for (int kb = 0; kb < KBS; ++kb) {
+            for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
                 for (int i = 0; i < WN; ++i)
-                    wf[kb][i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb) * 1024 + lane * 16);
+                    wf[kb][i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb0 + kb) * 1024 + lane * 16);
 #pragma unroll
                 for (int j = 0; j < WM; ++j)
-                    xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
+                    xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb0 + kb) * 1024 + lane * 16);
             }
             issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
-            wait_vmcnt<(STAGES - 2) * LPW>();    // own loads of stage it+1 have landed
+            wait_stage();    // own loads of stage it+1 have landed
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragments are in registers, the buffer may be reused
             __builtin_amdgcn_s_barrier();
             // ---- compute phase
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kb = 0; kb < KBS; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int i = 0; i < WN; ++i)
 #pragma unroll
@@ -258,7 +277,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[slot][i], xf[slot][j], acc[i][j], 0, 0, 0);
         };
         static_assert(KBS % 2 == 0, "fragment slots alternate over an even number of k-blocks");
-        wait_vmcnt<(STAGES - 2) * LPW>();        // stage 0 has landed (this wavefront's part)
+        wait_stage();        // stage 0 has landed (this wavefront's part)
         __builtin_amdgcn_s_barrier();            // ... everyone's
         issue_stage(STAGES - 1);
         read_frags(0, smem, 0);
@@ -273,7 +292,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
                 __builtin_amdgcn_sched_barrier(0);
             }
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // stage `it` is fully in registers
-            wait_vmcnt<(STAGES - 2) * LPW>();                       // stage it+1 has landed (own part)
+            wait_stage();                       // stage it+1 has landed (own part)
             __builtin_amdgcn_s_barrier();                           // ... everyone's; buffer of stage `it` is free
             issue_stage(it + STAGES);
             read_frags(0, smem + ((it + 1) % STAGES) * STAGE_BYTES, 0);
@@ -319,7 +338,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
                     }
         };
         const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        wait_vmcnt<(STAGES - 2) * LPW>();        // stage 0 has landed (this wavefront's part)
+        wait_stage();        // stage 0 has landed (this wavefront's part)
         __builtin_amdgcn_s_barrier();            // ... everyone's
         if (late) __builtin_amdgcn_s_barrier();  // phase shift
         for (int it = 0; it < nstages; ++it) {
@@ -345,7 +364,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
                     xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
             issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
             fold_all(it - 1);
-            wait_vmcnt<(STAGES - 2) * LPW>();    // own loads of stage it+1 have landed
+            wait_stage();    // own loads of stage it+1 have landed
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragments are in registers, the buffer may be reused
             __builtin_amdgcn_s_barrier();
             // ---- compute phase
@@ -416,7 +435,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
         };
         const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         for (int it = 0; it < nstages; ++it) {
-            wait_vmcnt<(STAGES - 2) * LPW>();        // this wavefront's loads of stage `it` have landed
+            wait_stage();        // this wavefront's loads of stage `it` have landed
             __builtin_amdgcn_s_barrier();            // ... everyone's; and stage it-1 is fully consumed
             issue_stage(it + STAGES - 1);            // refills the buffer stage it-1 used
             const char *buf = smem + (it % STAGES) * STAGE_BYTES;
@@ -462,12 +481,53 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     }
     wait_vmcnt<0>();   // drain the dead tail loads before the LDS is released
 
+    // k-split: wavefronts w and w + NW/2 hold partial sums of the same 64x64 patch.  Each keeps one half of
+    // the token blocks (wk = 0: the first WM/2, wk = 1: the rest), hands the other half over through LDS
+    // and adds what it receives: exact integer sums, so the order does not matter.
+    constexpr int HB = WM / 2;
+    if constexpr (WK == 2) {
+        __syncthreads();                                   // every wavefront is done with the stage buffers
+        static_assert(NW * WN * HB * 4096 <= STAGES * STAGE_BYTES, "exchange area fits the pipeline buffers");
+        char *mine = smem + (size_t)wave * (WN * HB * 4096);
+        const char *theirs = smem + (size_t)((wave + NW / 2) % NW) * (WN * HB * 4096);
+        auto give = [&](auto half) {                       // write the blocks of the half this wavefront does not keep
+            constexpr int j0 = decltype(half)::value * HB;
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int jj = 0; jj < HB; ++jj)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<v4i *>(mine + ((i * HB + jj) * 4 + q) * 1024 + lane * 16) =
+                            v4i{acc[i][j0 + jj][4 * q], acc[i][j0 + jj][4 * q + 1], acc[i][j0 + jj][4 * q + 2],
+                                acc[i][j0 + jj][4 * q + 3]};
+        };
+        auto take = [&](auto half) {
+            constexpr int j0 = decltype(half)::value * HB;
+#pragma unroll
+            for (int i = 0; i < WN; ++i)
+#pragma unroll
+                for (int jj = 0; jj < HB; ++jj)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const v4i v = *reinterpret_cast<const v4i *>(theirs + ((i * HB + jj) * 4 + q) * 1024 + lane * 16);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j0 + jj][4 * q + e] += v[e];
+                    }
+        };
+        if (wk == 0) give(std::integral_constant<int, 1>{}); else give(std::integral_constant<int, 0>{});
+        __syncthreads();
+        if (wk == 0) take(std::integral_constant<int, 0>{}); else take(std::integral_constant<int, 1>{});
+        // (the barrier in front of the fp16 epilogue keeps its staging patches from overwriting unread sums)
+    }
+    auto my_block = [&](int j) { return WK == 1 || j / (HB > 0 ? HB : 1) == wk; };   // token blocks this wavefront finishes
+
     // ---------------------------------------------------------------- epilogue
     if (EPI == EPI_ACC) {   // test hook: raw integer accumulators, element by element
 #pragma unroll
         for (int j = 0; j < WM; ++j) {
             const int m = m_lane0 + j * 32;
-            if (m >= p.M) continue;
+            if (m >= p.M || !my_block(j)) continue;
 #pragma unroll
             for (int i = 0; i < WN; ++i)
 #pragma unroll
@@ -494,6 +554,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
     const int m_wave0 = (tm * TMB + wm * WM) * 32;
 #pragma unroll
     for (int j = 0; j < WM; ++j) {
+        if (!my_block(j)) continue;                        // wave-uniform
         const float sxm = side_sx[(wm * WM + j) * 32 + (lane & 31)] * (W4 ? 0.0625f : 1.0f);
 #pragma unroll
         for (int i = 0; i < WN; ++i)
@@ -518,11 +579,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
         asm volatile("" ::: "memory");
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int t = 0; t < 32 / RPI; ++t) {
+        for (int t = 0; t < (32 + RPI - 1) / RPI; ++t) {
             const int row = t * RPI + lane / LPR, c = lane % LPR;
-            const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * ROW_BYTES + c * 16);
+            const bool mine = (64 % LPR == 0 && 32 % RPI == 0) || (lane < RPI * LPR && row < 32);
+            const uint4 v = *reinterpret_cast<const uint4 *>(stg + (mine ? row : 0) * ROW_BYTES + c * 16);
             const int mm = m_wave0 + j * 32 + row, nn = n_wave0 + c * 8;
-            if (mm < p.M && nn < p.N) {
+            if (mine && mm < p.M && nn < p.N) {
                 __half *dst = p.y + (size_t)mm * p.ldy + nn;
                 if (nn + 7 < p.N) {
                     *reinterpret_cast<uint4 *>(dst) = v;
@@ -539,17 +601,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64, OCC) void gemm_prefill_kerne
 }
 
 // OCC: wavefronts per SIMD the register allocation must leave room for (workgroups per CU x waves / 4)
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false,
+          int WK = 1>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
     constexpr int XFR = WAVES_M * WM * KBS;
     constexpr int WFR = W4 ? WAVES_N * WN * KBS / 2 : WAVES_N * WN * KBS;
     constexpr int LDS = (XFR + WFR) * 1024 * STAGES + (TM + 2 * TN) * 4 +   // stages + epilogue side area
-                        ((W4 && PP) ? STAGES * WAVES_M * WAVES_N * 256 : 0);  // + int4 group-scale slots
+                        ((W4 && PP) ? STAGES * WAVES_M * WAVES_N * WK * 256 : 0);  // + int4 group-scale slots
     static_assert(LDS <= 160 * 1024, "LDS budget");
-    static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N) + 1) <= 63, "vmcnt range");
-    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP>;
+    static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N * WK) + 1) <= 63, "vmcnt range");
+    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP, WK>;
     static bool attr_set = false;
     if (!attr_set) {
         QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -580,7 +643,7 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     p.wscales = W4 ? reinterpret_cast<const __half *>(static_cast<const char *>(a.wq) + w4_scales_offset(a.N, a.K))
                    : nullptr;
     const int grid = p.tiles_m * p.tiles_n;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * 64), LDS, st, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * WK * 64), LDS, st, p);
     return check_hip(hipGetLastError(), "gemm_prefill launch");
 }
 
@@ -596,19 +659,27 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
     }
     if (variant == 0) {
-        // 256x256 tiles run the matrix pipes best, but a grid that fills only part of the last round of
-        // 256 CUs wastes more than the smaller tile's extra L2 traffic costs
-        const long t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
-        const long rounds = (t256 + 255) / 256;
+        // Relative time of a tile shape = rounds over the 256 CUs x tile area / rate of a busy CU (measured:
+        // the big ping-pong tiles sustain ~10.2 TOPS per CU, three resident 128x128 workgroups ~9.2 together,
+        // a lone 128x128 workgroup 8.7, or 10 with the k-split ping-pong once K is long enough to amortise its
+        // exchange).  256x256 wins ties: fewer rounds, fewer pipeline fills and epilogues.
+        auto rounds = [](long tiles, long slots) { return (tiles + slots - 1) / slots; };
+        const long m256 = ceil_div(a.M, 256), m128 = ceil_div(a.M, 128);
+        const long t256 = m256 * ceil_div(a.N, 256), t192 = m256 * ceil_div(a.N, 192), t128 = m128 * ceil_div(a.N, 128);
+        double best = rounds(t256, 256) * (256.0 * 256.0) / 10.2;
         variant = 6;
-        if (t256 * 10 < rounds * 256 * 8) {
-            // 128x128 tiles: three workgroups per CU when there are enough tiles to need them, eight
-            // wavefronts per tile when every tile gets a CU of its own
-            const long t128 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 128);
-            variant = t128 > 512 ? 11 : (t128 <= 256 ? 13 : 4);
-        }
+        const double c192 = rounds(t192, 256) * (256.0 * 192.0) / 10.2;
+        if (c192 < best * 0.97) best = c192, variant = 15;
+        int v128;
+        double c128;
+        if (t128 > 512) v128 = 11, c128 = rounds(t128, 768) * 3 * (128.0 * 128.0) / 9.2;
+        else if (t128 > 256) v128 = 4, c128 = 2 * (128.0 * 128.0) / 9.0;
+        else if (a.K % 128 == 0 && a.K >= 3072) v128 = 19, c128 = (128.0 * 128.0) / 10.0;
+        else v128 = 13, c128 = (128.0 * 128.0) / 8.7;
+        if (c128 < best * 0.97) variant = v128;
     }
-    if ((variant == 5 || variant == 12) && a.K % 128) variant = variant == 5 ? 1 : 4;   // 128-k stages need K % 128 == 0
+    if ((variant == 5 || variant == 12) && a.K % 128) variant = variant == 5 ? 1 : 4;
+    if (variant == 19 && a.K % 128) variant = 13;   // 128-k stages need K % 128 == 0
     switch (variant) {
     case 1:   // 256x256, 8 wavefronts of 128 tokens x 64 channels, 64 k per stage, 4 stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI>(a, st);
@@ -628,6 +699,16 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 2, 2, 2, 4, 2, false, EPI, 2>(a, st);
     case 6:   // 256x256, 8 wavefronts in two ping-pong groups (one computes while the other fetches), 64-k stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI, 1, true>(a, st);
+    case 15:  // 256 tokens x 192 channels, 8 wavefronts of 64x96 in two ping-pong groups
+        return launch_one<4, 2, 2, 3, 2, 4, false, EPI, 1, true>(a, st);
+    case 19:  // 128x128, two ping-pong groups of 4 wavefronts (64x64 each) that split the k-blocks of every 128-k stage
+        return launch_one<2, 2, 2, 2, 4, 3, false, EPI, 1, true, 2>(a, st);
+    case 18:  // 256x256, 16 wavefronts of 64x64 in two ping-pong groups (two wavefronts of each group per SIMD)
+        return launch_one<4, 4, 2, 2, 2, 4, false, EPI, 1, true>(a, st);
+    case 16:  // 256 tokens x 128 channels, 8 wavefronts of 64x64, ping-pong, 3 stages: two workgroups per CU
+        return launch_one<4, 2, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
+    case 17:  // 128 tokens x 256 channels, same
+        return launch_one<2, 4, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
     case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU)
         return launch_one<4, 2, 1, 2, 2, 4, false, EPI>(a, st);
     case 14:  // 128x128, 8 wavefronts of 64 tokens x 32 channels
