@@ -10,59 +10,10 @@
 //   amax = max_k |x|            sx = amax / 127          inv = 127 / amax
 //   code = clamp(rne(x * inv), -127, 127)                (all-zero token: sx = 1, codes 0)
 #include "common.h"
+#include "quant_math.h"
 
 namespace ql {
 namespace {
-
-constexpr int CHUNK = 16;               // elements per lane per step: 32 B in, 16 B out
-
-struct alignas(16) Half16 {
-    uint4 lo, hi;                       // 16 fp16 values
-};
-
-__device__ inline unsigned abs_max_bits(const Half16 &v, unsigned m)
-{
-    // |h| as an integer is monotonic in |value| for finite fp16, so the maximum can be taken on bits
-    const unsigned w[8] = {v.lo.x, v.lo.y, v.lo.z, v.lo.w, v.hi.x, v.hi.y, v.hi.z, v.hi.w};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        m = max(m, w[i] & 0x7fffu);
-        m = max(m, (w[i] >> 16) & 0x7fffu);
-    }
-    return m;
-}
-
-__device__ inline float half_bits_to_float(unsigned bits)
-{
-    return __half2float(__ushort_as_half((unsigned short)bits));
-}
-
-__device__ inline int quant_code(unsigned hbits, float inv)
-{
-    const float t = half_bits_to_float(hbits) * inv;    // one fp32 multiply
-    float r = rintf(t);                                 // round half to even
-    r = fminf(fmaxf(r, -127.0f), 127.0f);
-    return (int)r;
-}
-
-__device__ inline unsigned quant_word(unsigned w0, unsigned w1, float inv)   // 4 halves -> 4 codes
-{
-    const unsigned a = quant_code(w0 & 0xffffu, inv) & 0xff;
-    const unsigned b = quant_code(w0 >> 16, inv) & 0xff;
-    const unsigned c = quant_code(w1 & 0xffffu, inv) & 0xff;
-    const unsigned d = quant_code(w1 >> 16, inv) & 0xff;
-    return a | (b << 8) | (c << 16) | (d << 24);
-}
-
-__device__ inline uint4 quant_chunk(const Half16 &v, float inv)
-{
-    uint4 q;
-    q.x = quant_word(v.lo.x, v.lo.y, inv);
-    q.y = quant_word(v.lo.z, v.lo.w, inv);
-    q.z = quant_word(v.hi.x, v.hi.y, inv);
-    q.w = quant_word(v.hi.z, v.hi.w, inv);
-    return q;
-}
 
 // One workgroup quantizes RPB consecutive tokens.  RPB = 8 (prefill): a wavefront covers 8 tokens x 8
 // chunks per step (lane = token % 8 + 8 * chunk), so that in the GEMM's tile order the 8 lanes of one
@@ -115,10 +66,8 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     mx = 0;
     for (int w = 0; w < nwaves; ++w) mx = max(mx, red[r][w]);
 
-    const float amax = half_bits_to_float(mx);
-    const bool zero = (mx == 0);
-    const float scale = zero ? 1.0f : amax / 127.0f;    // IEEE fp32 division
-    const float inv = zero ? 0.0f : 127.0f / amax;      // IEEE fp32 division
+    float scale, inv;
+    token_scales(mx, scale, inv);
     if (wave == 0 && cl == 0 && valid) sx[m] = scale;
 
     auto emit = [&](int c, const Half16 &h) {

@@ -147,6 +147,23 @@ int linear_common(const void *x, int64_t ldx, int M, int K, const void *wq, cons
     if (!aligned(wq, 256) || (sw && !aligned(sw, 16)) || (bias && !aligned(bias, 16)))
         return fail(QL_ERR_ALIGN, "wq needs 256-byte, sw/bias 16-byte alignment");
     QL_TRY(check_out(y, ldy, N));
+    if (M <= DECODE_MAX_M && (g_variant == 0 || g_variant >= 100) && decode_fuses_quant(M, K, g_variant)) {
+        // one or two tokens: the decode GEMM quantizes them itself, one launch instead of two
+        GemmArgs a = {};
+        a.x = static_cast<const __half *>(x);
+        a.ldx = ldx;
+        a.wq = wq;
+        a.sw = sw;
+        a.bias = static_cast<const __half *>(bias);
+        a.y = static_cast<__half *>(y);
+        a.ldy = ldy;
+        a.M = M;
+        a.N = N;
+        a.K = K;
+        a.bits = bits;
+        a.group = group;
+        return launch_gemm_decode(a, g_variant == 0 ? 100 : g_variant, st);
+    }
     QL_TRY(launch_act_quant(static_cast<const __half *>(x), ldx, M, K, nullptr, xq, sx, st));
     return gemm_common(xq, sx, M, K, wq, sw, bits, group, bias, N, y, ldy, ws, ws_bytes, st);
 }
@@ -165,7 +182,7 @@ const char *ql_last_error(void) { return g_err; }
 
 int ql_set_kernel_variant(int variant)
 {
-    if (variant < 0 || (variant > 19 && variant < 100) || (variant > 104 && variant != 111 && variant != 121))
+    if (variant < 0 || (variant > 19 && variant < 100) || (variant > 104 && variant != 111 && variant != 121 && variant != 130))
         return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);
     g_variant = variant;
     return QL_OK;

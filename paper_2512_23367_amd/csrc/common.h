@@ -87,6 +87,8 @@ int launch_export4(const uint8_t *kl, int N, int K, int group, uint8_t *canon, _
                    hipStream_t st);
 
 struct GemmArgs {
+    const __half *x;       // decode only: fp16 tokens [M, ldx] to quantize inside the GEMM (then xq, sx unused)
+    int64_t ldx;
     const int8_t *xq;      // kernel layout, ceil32(M) rows
     const float *sx;       // [M] (unused by the accumulator dump)
     const void *wq;        // kernel-layout blob
@@ -104,5 +106,6 @@ struct GemmArgs {
 };
 int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st);
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st);
+bool decode_fuses_quant(int M, int K, int variant);
 
 }  // namespace ql

@@ -6,8 +6,12 @@
 //   * weight fragments go global -> registers with 16-byte loads per lane, a ring of them in flight
 //     per wavefront, straight into the 16x16x64 int8 matrix instruction (int4: after a shift/mask
 //     unpack); nothing is reused, so nothing is staged in LDS;
-//   * the (at most 32) quantized tokens are re-read from L2 in the same tile order.
+//   * the (at most 32) quantized tokens are re-read from L2 in the same tile order, or staged in LDS when
+//     they are few; for one or two tokens the linear-layer entry points skip the separate quantization
+//     kernel and every workgroup quantizes the fp16 tokens itself on the way into LDS (paper Eq. 1-2,
+//     same arithmetic as the stand-alone quantizer), while its first weight fragments are in flight.
 #include "common.h"
+#include "quant_math.h"
 
 namespace ql {
 namespace {
@@ -19,6 +23,8 @@ typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 enum { EPI_F16 = 0, EPI_ACC = 1 };
 
 struct DecodeParams {
+    const __half *x;         // fused quantization: fp16 tokens [M, ldx]
+    int64_t ldx;
     const int8_t *xq;
     const char *wq;
     const float *sx;
@@ -36,10 +42,14 @@ struct DecodeParams {
 // C: groups of 16 output channels per workgroup (they share every token fragment that is loaded).
 // XL: the (few) quantized tokens are staged once per workgroup in LDS, [k-tile half][token] with one extra
 // all-zero token row that the lanes of absent tokens read; the ring then holds weights only.
-template <bool W4, int MH, int C, int EPI, int WAVES, bool XL>
+// FQ: the tokens arrive as fp16 and are quantized here (XL staging with the quantizer in front of it).
+constexpr int FQ_MAX_M = 2;
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL, bool FQ>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 {
+    static_assert(!FQ || (XL && EPI == EPI_F16), "fused quantization stages the tokens in LDS");
     __shared__ int red[WAVES][C][MH][4][64];
+    __shared__ unsigned amax_red[FQ ? WAVES : 1][FQ_MAX_M];
     extern __shared__ __attribute__((aligned(16))) char dyn_lds[];
     // W4A8: the group scales of this workgroup's C*16 channels, [C][K/128][16] fp16, then
     // XL: the staged tokens, (M + 1) * K bytes
@@ -86,9 +96,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     for (int e = 0; e < 4; ++e) e_sw[e] = 0.0f, e_b[e] = 0.0f;
     if (EPI == EPI_F16 && wave < C) {
         const int n0 = (rg0 + wave) * 16 + 4 * ch;
+        if (!FQ) {
 #pragma unroll
-        for (int h = 0; h < MH; ++h)
-            if (r + 16 * h < p.M) e_sx[h] = p.sx[r + 16 * h] * (W4 ? 0.0625f : 1.0f);
+            for (int h = 0; h < MH; ++h)
+                if (r + 16 * h < p.M) e_sx[h] = p.sx[r + 16 * h] * (W4 ? 0.0625f : 1.0f);
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (n0 + e < p.N) {
@@ -128,6 +140,60 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         __builtin_amdgcn_wave_barrier();
     };
 
+    // FQ: quantize tokens 0..M-1 (M <= FQ_MAX_M) over this wavefront's 16-k pieces th0 .. th1-1 into the same
+    // LDS layout.  The fp16 pieces are loaded BEFORE the first weight fragments are requested and stay in
+    // registers (loads return in order: behind the weight stream they would arrive an HBM latency late);
+    // the row maxima of the wavefronts' k-ranges meet in LDS (one workgroup barrier, reached by every
+    // wavefront), then the codes are produced from the registers while the weights are still in flight.
+    // A lane keeps FQ_SLOTS pieces: two rounds of one token or one round of two.
+    constexpr int FQ_SLOTS = 2;
+    Half16 keep[FQ ? FQ_SLOTS : 1];
+    auto load_tokens = [&](int th0, int th1) {
+#pragma unroll
+        for (int sl = 0; sl < FQ_SLOTS; ++sl) {
+            const int it = sl / p.M, m = sl % p.M;        // M = 1: (0,0) (1,0);  M = 2: (0,0) (0,1)
+            const int i = th0 + it * 64 + lane;
+            keep[sl] = Half16{uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
+            if (i < th1) keep[sl] = *reinterpret_cast<const Half16 *>(p.x + (size_t)m * p.ldx + (size_t)i * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto quantize_tokens = [&](int th0, int th1) {
+        unsigned mx[FQ_MAX_M] = {0, 0};
+#pragma unroll
+        for (int sl = 0; sl < FQ_SLOTS; ++sl) {
+            const unsigned v = abs_max_bits(keep[sl], 0);   // pieces beyond the range hold zeros
+            if (sl % p.M == 0) mx[0] = max(mx[0], v); else mx[1] = max(mx[1], v);
+        }
+#pragma unroll
+        for (int m = 0; m < FQ_MAX_M; ++m) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) mx[m] = max(mx[m], (unsigned)__shfl_xor((int)mx[m], off, 64));
+            if (lane == 0) amax_red[wave][m] = mx[m];
+        }
+        __syncthreads();
+        float inv[FQ_MAX_M];
+#pragma unroll
+        for (int m = 0; m < FQ_MAX_M; ++m) {
+            unsigned a = 0;
+            for (int w = 0; w < WAVES; ++w) a = max(a, amax_red[w][m]);
+            float scale;
+            token_scales(a, scale, inv[m]);
+            if (r == m) e_sx[0] = scale * (W4 ? 0.0625f : 1.0f);
+        }
+#pragma unroll
+        for (int sl = 0; sl < FQ_SLOTS; ++sl) {
+            const int it = sl / p.M, m = sl % p.M;
+            const int i = th0 + it * 64 + lane;
+            if (i < th1) {
+                *reinterpret_cast<uint4 *>(xs + ((size_t)i * xrows + m) * 16) = quant_chunk(keep[sl], m == 0 ? inv[0] : inv[1]);
+                if (m == 0) *reinterpret_cast<uint4 *>(xs + ((size_t)i * xrows + p.M) * 16) = uint4{0, 0, 0, 0};
+            }
+        }
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+    };
+
     // Both loops keep a ring of U weight fragments (1 KiB each per wavefront) in flight: slot u is
     // consumed, then immediately refilled with the fragment U steps ahead.
     if (!W4) {
@@ -151,9 +217,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                 }
             }
         };
+        const int th0 = 4 * c0, th1 = c0 < c1 ? 4 * c1 : 4 * c0;
+        if (FQ) load_tokens(th0, th1);
 #pragma unroll
         for (int u = 0; u < U; ++u) fetch(u, c0 + u);
-        if (XL && c0 < c1) stage_tokens(4 * c0, 4 * c1);
+        if (FQ) quantize_tokens(th0, th1);
+        else if (XL && c0 < c1) stage_tokens(4 * c0, 4 * c1);
         for (int c = c0; c < c1; c += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -198,6 +267,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                 }
             }
         };
+        const int th0 = 8 * g0, th1 = g0 < g1 ? 8 * g1 : 8 * g0;
+        if (FQ) load_tokens(th0, th1);
 #pragma unroll
         for (int u = 0; u < U; ++u) fetch(u, g0 + u);
         if (g0 < g1) {
@@ -212,10 +283,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                                                        ((size_t)(rg0 + j) * G + g0) * 32 + (size_t)o * 16);
                 *reinterpret_cast<v4i *>(ss + ((size_t)j * G + g0) * 32 + (size_t)o * 16) = v;
             }
-            if (XL) stage_tokens(8 * g0, 8 * g1);
+            if (XL && !FQ) stage_tokens(8 * g0, 8 * g1);
             asm volatile("" ::: "memory");
             __builtin_amdgcn_wave_barrier();
         }
+        if (FQ) quantize_tokens(th0, th1);
         for (int g = g0; g < g1; g += U) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -318,10 +390,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     }
 }
 
-template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false>
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false, bool FQ = false>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     DecodeParams p;
+    p.x = a.x;
+    p.ldx = a.ldx;
     p.xq = a.xq;
     p.wq = static_cast<const char *>(a.wq);
     p.sx = a.sx;
@@ -344,13 +418,13 @@ int launch_one(const GemmArgs &a, hipStream_t st)
         static bool attr_set = false;
         if (!attr_set) {
             QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(
-                                                     gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL>),
+                                                     gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, 40960 + 32768),
                              "hipFuncSetAttribute(max dynamic LDS)"));
             attr_set = true;
         }
     }
-    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL>), dim3(grid), dim3(WAVES * 64), xs_bytes, st, p);
+    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid), dim3(WAVES * 64), xs_bytes, st, p);
     return check_hip(hipGetLastError(), "gemm_decode launch");
 }
 
@@ -381,6 +455,15 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101;
     // few tokens: stage them in LDS (ring slots then hold weights only, more bytes in flight per register)
     const bool xl = (size_t)(a.M + 1) * a.K <= 24576 && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
+    if (a.x) {   // fp16 tokens: quantize in the prologue (the caller checked decode_fuses_quant)
+        if (EPI != EPI_F16 || !xl || a.M > FQ_MAX_M) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
+        if constexpr (EPI == EPI_F16) {
+            if (wide) return launch_one<W4, 1, 1, EPI, 16, true, true>(a, st);
+            if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, true>(a, st);
+            if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, true>(a, st);
+            return launch_one<W4, 1, 4, EPI, 8, true, true>(a, st);
+        }
+    }
     if (xl) {
         if (wide) return launch_one<W4, 1, 1, EPI, 16, true>(a, st);
         if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true>(a, st);
@@ -401,6 +484,17 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
 }
 
 }  // namespace
+
+// The linear-layer entry points hand fp16 tokens straight to the decode GEMM when this holds (the same
+// condition that stages the tokens in LDS, and few enough tokens that every workgroup re-reading and
+// re-quantizing all of them costs less than a kernel launch).
+bool decode_fuses_quant(int M, int K, int variant)
+{
+    // a wavefront (of at least 8) keeps its k-range in registers: 2 x 64 pieces of 16 k for one token, 64 for two
+    const int pieces = ceil_div(ceil_div(K, 128), 8) * 8;   // int4 splits whole 128-k groups, int8 64-k chunks: bound both
+    return M >= 1 && M <= FQ_MAX_M && (size_t)(M + 1) * K <= 24576 && pieces * M <= 128 && variant != 121 &&
+           variant != 130;
+}
 
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st)
 {

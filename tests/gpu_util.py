@@ -87,18 +87,24 @@ def gpu_acc(xq: np.ndarray, wq, want_partials=False):
     return acc.cpu().numpy(), (part.cpu().numpy() if part is not None else None)
 
 
-def gpu_linear(x16: np.ndarray, wq, bias16=None, ldy=None) -> np.ndarray:
+def gpu_linear(x16: np.ndarray, wq, bias16=None, ldy=None, ldx=None) -> np.ndarray:
     M, K = x16.shape
     N = wq["N"]
+    if ldx is None:
+        xd = dev(x16)
+    else:
+        xbuf = torch.full((M, ldx), float("nan"), dtype=torch.float16, device=DEV)
+        xbuf[:, :K] = dev(x16)
+        xd = xbuf[:, :K]
     ld = ldy or ((N + 7) // 8 * 8)
     ybuf = torch.full((M, ld), float("nan"), dtype=torch.float16, device=DEV)
     y = ybuf[:, :N]
     ws = empty_bytes(ql.ql_workspace_bytes(M, N, K, wq["bits"]))
     b = dev(bias16) if bias16 is not None else None
     if wq["bits"] == 8:
-        ql.ql_w8a8_linear(dev(x16), wq["kernel"], wq["scales_dev"].view(torch.float32), b, N, y, ws)
+        ql.ql_w8a8_linear(xd, wq["kernel"], wq["scales_dev"].view(torch.float32), b, N, y, ws)
     else:
-        ql.ql_w4a8_linear(dev(x16), wq["kernel"], wq["group"], b, N, y, ws)
+        ql.ql_w4a8_linear(xd, wq["kernel"], wq["group"], b, N, y, ws)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 

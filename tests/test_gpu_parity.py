@@ -195,6 +195,28 @@ def test_linear_fp16_within_tolerance(G, bits, M, K, N, bias):
     assert G.norm_err(y, ref["y64"]) <= 6e-4
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N,ldx", [(1, 4096, 520, None), (2, 4096, 200, 4104), (1, 11008, 72, None), (2, 512, 33, None),
+                                       (1, 128, 16, 136), (2, 8192, 48, None)])
+def test_decode_linear_with_fused_quantization_matches_two_kernel_path(G, bits, M, K, N, ldx):
+    """One or two tokens: the decode GEMM quantizes the fp16 tokens in its prologue.  Same codes, same integer
+    sums, same epilogue arithmetic as quantization kernel + GEMM, so the fp16 outputs must agree bit for bit
+    (variant 130 forces the two-kernel path), and both must be within tolerance of the oracle."""
+    x = synth.activations(M, K, 0, "single")
+    if M == 2:
+        x[1] = 0          # an all-zero token: scale 1, codes 0
+    w = synth.weights(N, K, 0, "single")
+    b = synth.bias(N, 0, "single")
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
+    y_fused = G.gpu_linear(x, g, b, ldx=ldx)
+    ql.ql_set_kernel_variant(130)
+    y_two = G.gpu_linear(x, g, b, ldx=ldx)
+    assert (y_fused.view(np.uint16) == y_two.view(np.uint16)).all()
+    ref = (oracle.linear_w8a8(x, g["canon"], g["scales"], b) if bits == 8
+           else oracle.linear_w4a8(x, g["canon"], g["scales"], 128, b))
+    assert G.norm_err(y_fused, ref["y64"]) <= TOL
+
+
 def test_config0_end_to_end(G):
     sh = synth.workload(0)[0]
     x, w, _ = synth.tensors(sh)
