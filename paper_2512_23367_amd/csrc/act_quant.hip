@@ -1,8 +1,8 @@
 // Per-token dynamic int8 activation quantization (paper Eq. 1-2 with n = 8; one scale per token
 // over its whole feature dimension, Preliminary section) for gfx950.
 //
-// One workgroup per 8 tokens (per token when there are at most 4).  The rows are read once: each lane keeps its 16-element chunks in
-// registers, the row maxima are reduced across lanes and wavefronts, then the codes are produced
+// One workgroup per 8 tokens (per token when there are at most 512).  The rows are read once: each lane
+// keeps its 16-element chunks in registers, the row maxima are reduced across lanes and wavefronts, then the codes are produced
 // from the registers and written row-major and/or in the GEMM's tile order, whole 128-byte lines
 // at a time.
 //
@@ -18,10 +18,13 @@ namespace {
 // One workgroup quantizes RPB consecutive tokens.  RPB = 8 (prefill): a wavefront covers 8 tokens x 8
 // chunks per step (lane = token % 8 + 8 * chunk), so that in the GEMM's tile order the 8 lanes of one
 // chunk write one whole 128-byte line (8 token slots x 16 bytes) and in the row-major copy each token
-// gets 128 contiguous bytes per step.  RPB = 1 (a handful of decode tokens): all 64 lanes of a wavefront
+// gets 128 contiguous bytes per step.  RPB = 1 (decode, short prefill): all 64 lanes of a wavefront
 // work on the same token, 64 chunks per step, so that a single token is not left to 8 lanes.
 // The NW wavefronts split K; the row maxima meet in LDS.
 // NIT: steps per wavefront kept in registers; NIT == 0: the row is read twice.
+// Up to this many tokens one workgroup per token is faster (2.5-8 us against 5-11 us at K = 4096..11008): the
+// 8-token workgroups are too few to cover the memory latency; beyond it their whole-line writes win.
+constexpr int SINGLE_TOKEN_MAX_M = 512;
 constexpr int MAX_RPB = 8;
 constexpr int MAX_WAVES = 8;
 
@@ -127,7 +130,7 @@ int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, 
                      float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
-    if (M <= 4) launch_aq<1>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
     else launch_aq<8>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant launch");
 }

@@ -29,7 +29,8 @@ def _auto_variant():
 
 # ------------------------------------------------------------------ quantizers
 @pytest.mark.parametrize("M,K,ldx", [(64, 512, None), (33, 1536, None), (5, 11008, None), (3, 64, None),
-                                     (7, 4096, 4104), (1, 4096, None), (2, 6144, None), (4, 40960, None)])
+                                     (7, 4096, 4104), (1, 4096, None), (2, 6144, None), (4, 40960, None),
+                                     (513, 512, None), (600, 1536, 1544), (515, 16384, None), (40, 40960, None)])
 def test_act_quant_bit_exact(G, M, K, ldx):
     x = synth.activations(M, K, 0, "single")
     x[M // 2, :] *= np.float16(0.01) if M > 1 else np.float16(1)
