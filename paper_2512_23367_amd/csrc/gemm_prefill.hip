@@ -100,11 +100,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     // Fragment f of a stage is loaded by wavefront f % NW.  When the count does not divide evenly the first
     // FR % NW wavefronts issue one load more per stage than the others (LPW_HI / LPW_LO loads).
     constexpr int FR = XFR + WFR;
-    constexpr bool SCALE_DMA = W4 && PP;                 // group scales travel with the stage, through LDS
+    constexpr bool SCALE_DMA = W4;                       // group scales travel with the stage, through LDS
     constexpr int LPW_HI = (FR + NW - 1) / NW + (SCALE_DMA ? 1 : 0);
     constexpr int LPW_LO = FR / NW + (SCALE_DMA ? 1 : 0);
     constexpr int NHI = FR % NW;                         // wavefronts 0 .. NHI-1 issue LPW_HI loads
-    static_assert(!W4 || KBS == 4, "W4A8: one stage is one scale group (128 k)");
+    static_assert(!W4 || (KBS == 4 && PP), "W4A8: one stage is one scale group (128 k); ping-pong loop only");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     // behind the stage buffers: the tile's token scales, channel scales and bias as fp32, fetched once at
@@ -306,7 +306,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     }
     if constexpr (W4 && PP) {
         // Ping-pong for int4 weights (same two phase-shifted groups as above; a stage is one scale group of
-        // 128 k).  Memory phase: read the stage's fragments (nibbles stay packed), fold the PREVIOUS group's
+        // 128 k).  Measured cost model of a gfx950 SIMD for this mix: cycles ~ 12 per matrix instruction + 4 per
+        // vector-ALU instruction + ~17 per LDS read, nearly additive whichever wavefront issues them, so what
+        // counts is the instruction count (176 vector ops per 16 matrix instructions: 128 fold, 48 unpack); an
+        // interleaved single-role loop with the same counts ran no faster than this split.  Memory phase: read the stage's fragments (nibbles stay packed), fold the PREVIOUS group's
         // int32 partial into the fp32 sums (accf += float(acc) * scale -- as many vector-ALU cycles as the
         // stage has matrix cycles, now running under the other group's matrix phase), issue loads, wait.
         // Compute phase: shift/mask unpack + matrix instructions, the first of each block with C = 0.
@@ -396,88 +399,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                     sg[i][q] = *reinterpret_cast<const h4 *>(slot + (i * 32 + 8 * q + 4 * (lane >> 5)) * 2);
         }
         fold_all(nstages - 1);
-    }
-    if constexpr (W4 && !PP) {
-        // Per stage (= one scale group of 128 k): 4*WN*WM matrix instructions, and the fold of the group's
-        // int32 partial into the fp32 sums (accf += float(acc) * scale: 2 vector-ALU ops per element, about
-        // as many cycles as the stage's matrix instructions).  The fold of stage it-1 is done block by block
-        // at the start of stage it, each block right before the first matrix instruction that overwrites it
-        // (C = 0), so the vector ALU works on block b+1 while the matrix pipe runs block b.
-        h4 sg[WN][4];                                // scales of the stage whose partial sits in acc
-#pragma unroll
-        for (int i = 0; i < WN; ++i)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) sg[i][q] = h4{0, 0, 0, 0};
-        auto load_sg = [&](int g) {
-#pragma unroll
-            for (int i = 0; i < WN; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = n_lane0 + i * 32 + 8 * q;     // whole 32-blocks are inside or outside Npad
-                    sg[i][q] = (n < p.Npad) ? *reinterpret_cast<const h4 *>(p.wscales + (size_t)g * p.Npad + n)
-                                            : h4{0, 0, 0, 0};
-                }
-        };
-        auto fold_block = [&](int i, int j, int g) {   // group g's partial of block (i, j); g < 0: nothing yet
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                if (EPI == EPI_F16) {
-                    accf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], (float)sg[i][r / 4][r % 4], accf[i][j][r]);
-                } else {
-                    tot[i][j][r] += acc[i][j][r];
-                    if (p.partials && g >= 0) {
-                        const int m = m_lane0 + j * 32, n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
-                        if (m >= p.row0 && m < p.row0 + p.nrows && m < p.M && n < p.N)
-                            p.partials[((size_t)(m - p.row0) * nstages + g) * p.N + n] = acc[i][j][r] >> 4;
-                    }
-                }
-            }
-        };
-        const v16i zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-        for (int it = 0; it < nstages; ++it) {
-            wait_stage();        // this wavefront's loads of stage `it` have landed
-            __builtin_amdgcn_s_barrier();            // ... everyone's; and stage it-1 is fully consumed
-            issue_stage(it + STAGES - 1);            // refills the buffer stage it-1 used
-            const char *buf = smem + (it % STAGES) * STAGE_BYTES;
-#pragma unroll
-            for (int kp = 0; kp < KBS / 2; ++kp) {
-                v4i wp[WN];
-#pragma unroll
-                for (int i = 0; i < WN; ++i)
-                    wp[i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * WKB + kp) * 1024 + lane * 16);
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int kb = 2 * kp + h;
-                    v4i xf[WM];
-#pragma unroll
-                    for (int j = 0; j < WM; ++j)
-                        xf[j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
-#pragma unroll
-                    for (int i = 0; i < WN; ++i) {
-                        const unsigned w0 = (unsigned)wp[i][2 * h], w1 = (unsigned)wp[i][2 * h + 1];
-                        v4i wf;
-                        wf[0] = (int)((w0 << 4) & 0xF0F0F0F0u);
-                        wf[1] = (int)(w0 & 0xF0F0F0F0u);
-                        wf[2] = (int)((w1 << 4) & 0xF0F0F0F0u);
-                        wf[3] = (int)(w1 & 0xF0F0F0F0u);
-#pragma unroll
-                        for (int j = 0; j < WM; ++j) {
-                            if (kb == 0) {
-                                fold_block(i, j, it - 1);
-                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[j], zero16, 0, 0, 0);
-                            } else {
-                                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, xf[j], acc[i][j], 0, 0, 0);
-                            }
-                        }
-                    }
-                }
-                if (kp == 0) load_sg(it);            // the previous scales were consumed by the folds above
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < WN; ++i)
-#pragma unroll
-            for (int j = 0; j < WM; ++j) fold_block(i, j, nstages - 1);
     }
     wait_vmcnt<0>();   // drain the dead tail loads before the LDS is released
 
@@ -609,7 +530,7 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     constexpr int XFR = WAVES_M * WM * KBS;
     constexpr int WFR = W4 ? WAVES_N * WN * KBS / 2 : WAVES_N * WN * KBS;
     constexpr int LDS = (XFR + WFR) * 1024 * STAGES + (TM + 2 * TN) * 4 +   // stages + epilogue side area
-                        ((W4 && PP) ? STAGES * WAVES_M * WAVES_N * WK * 256 : 0);  // + int4 group-scale slots
+                        (W4 ? STAGES * WAVES_M * WAVES_N * WK * 256 : 0);  // + int4 group-scale slots
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N * WK) + 1) <= 63, "vmcnt range");
     auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP, WK>;
@@ -652,8 +573,6 @@ template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
 {
     if (W4) {
-        if (variant == 1)   // 256 tokens x 128 channels, 8 wavefronts of 64x64, 3 stages, no ping-pong
-            return launch_one<4, 2, 2, 2, 4, 3, true, EPI>(a, st);
         // 128 tokens x 256 channels (equal bytes of both operands per stage), 8 wavefronts of 64x64 in two
         // ping-pong groups, 4 stages of one 128-k scale group each
         return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
