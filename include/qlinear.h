@@ -148,6 +148,17 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
  *   other values pick one implementation; unknown values -> QL_ERR_UNSUPPORTED. */
 int ql_set_kernel_variant(int variant);
 
+/* Ceiling probes for benchmarks (nothing of the method): what the GPU sustains on the two resources the
+ * layer is bound by, to be timed by the caller with events on `stream`.
+ *   ql_probe_mfma_int8: `workgroups` workgroups of 8 wavefronts each issue 4*iters register-resident
+ *     32x32x32 int8 matrix instructions; operands constant (random_operands = 0) or hashed per lane (the
+ *     shader clock depends on data toggling).  *ops (host, may be NULL) receives the operation count.
+ *   ql_probe_hbm_read: streams `bytes` bytes of `buf` once through non-temporal 16-byte loads.
+ * `sink` is a device int the kernels never actually write (it keeps their loops alive). */
+int ql_probe_mfma_int8(int workgroups, int iters, int random_operands, void *sink, int64_t *ops /* host */,
+                       void *stream);
+int ql_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

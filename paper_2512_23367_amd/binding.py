@@ -23,6 +23,7 @@ EXPORTS = [
     "ql_quant_act_per_token", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
     "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
     "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant",
+    "ql_probe_mfma_int8", "ql_probe_hbm_read",
 ]
 
 
@@ -66,6 +67,8 @@ def lib() -> ctypes.CDLL:
             "ql_w4a8_gemm": [vp, vp, i, i, vp, i, vp, i, vp, i64, vp, sz, vp],
             "ql_w8a8_gemm_acc_i32": [vp, i, i, vp, i, vp, vp, sz, vp],
             "ql_w4a8_gemm_acc_i32": [vp, i, i, vp, i, i, vp, vp, i, i, vp, sz, vp],
+            "ql_probe_mfma_int8": [i, i, i, vp, c.POINTER(c.c_int64), vp],
+            "ql_probe_hbm_read": [vp, sz, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(l, name)
@@ -109,6 +112,18 @@ def ql_last_error() -> str:
 
 def ql_set_kernel_variant(variant: int):
     _check(lib().ql_set_kernel_variant(variant))
+
+
+def ql_probe_mfma_int8(workgroups: int, iters: int, random_operands: bool, sink) -> int:
+    """Enqueues the matrix-pipe ceiling probe; returns the number of int8 operations it performs."""
+    ops = ctypes.c_int64()
+    _check(lib().ql_probe_mfma_int8(workgroups, iters, int(random_operands), _p(sink), ctypes.byref(ops), _stream()))
+    return ops.value
+
+
+def ql_probe_hbm_read(buf, sink):
+    """Enqueues one pass of the HBM read-stream probe over the whole of `buf`."""
+    _check(lib().ql_probe_hbm_read(_p(buf), buf.numel() * buf.element_size(), _p(sink), _stream()))
 
 
 def ql_weight_bytes(N, K, bits, group):

@@ -104,6 +104,8 @@ struct GemmArgs {
     void *ws;
     size_t ws_bytes;
 };
+int launch_probe_mfma(int workgroups, int iters, int random_operands, int *sink, hipStream_t st);
+int launch_probe_read(const void *buf, size_t bytes, int *sink, hipStream_t st);
 int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st);
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st);
 bool decode_fuses_quant(int M, int K, int variant);

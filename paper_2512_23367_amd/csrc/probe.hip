@@ -1,0 +1,77 @@
+// Ceiling probes for the benchmark: what this GPU sustains on the two resources the linear layer is
+// bound by, measured in the same job as the kernels (they compute nothing of the method).
+//   * int8 matrix pipe: register-resident v_mfma_i32_32x32x32_i8 loop on every CU, operands either
+//     constant or hashed per lane (the shader clock drops under data toggling, so the two differ);
+//   * HBM read stream: every lane sums 16-byte non-temporal loads over a buffer larger than the caches.
+#include "common.h"
+
+namespace ql {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+__device__ inline unsigned hash32(unsigned x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352dU;
+    x ^= x >> 15;
+    x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return x;
+}
+
+constexpr int PROBE_WAVES = 8, PROBE_ACC = 4;
+
+__global__ __launch_bounds__(PROBE_WAVES * 64) void probe_mfma_kernel(int iters, int random_operands, int *sink)
+{
+    v4i a = {0x01010101, 0x01010101, 0x01010101, 0x01010101}, b = a;
+    if (random_operands) {
+        const unsigned t = threadIdx.x * 977u + blockIdx.x * 131u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = (int)hash32(t + i), b[i] = (int)hash32(t + 17 + i);
+    }
+    v16i acc[PROBE_ACC];
+#pragma unroll
+    for (int i = 0; i < PROBE_ACC; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < PROBE_ACC; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < PROBE_ACC; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 0x7fffffff && iters < 0) sink[0] = s;   // never true: keeps the loop alive
+}
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__ p, size_t n16, int *sink)
+{
+    v4i s = {0, 0, 0, 0};
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const v4i v = __builtin_nontemporal_load(p + i);
+        s ^= v;
+    }
+    if ((s[0] ^ s[1] ^ s[2] ^ s[3]) == 0x5a5a5a5a && n16 == 0) sink[0] = s[0];   // never true
+}
+
+}  // namespace
+
+int launch_probe_mfma(int workgroups, int iters, int random_operands, int *sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(PROBE_WAVES * 64), 0, st, iters, random_operands, sink);
+    return check_hip(hipGetLastError(), "probe_mfma launch");
+}
+
+int launch_probe_read(const void *buf, size_t bytes, int *sink, hipStream_t st)
+{
+    hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, st, static_cast<const v4i *>(buf), bytes / 16,
+                       sink);
+    return check_hip(hipGetLastError(), "probe_read launch");
+}
+
+}  // namespace ql
