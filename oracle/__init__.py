@@ -3,7 +3,8 @@
 A plain, slow, obviously-correct implementation of what the hot path computes,
 written from the paper's definitions (its Eq. 1-2 quantizer, the per-token /
 per-channel / group-wise granularities of its Preliminary section, the
-symmetric setting of its Experimental Setup, and Y = XW of its Eq. 3).
+symmetric setting of its Experimental Setup, and Y = XW of its Eq. 3), plus the
+two operand transforms of its W4A8 variants (SmoothQuant, Eq. 3; Hadamard rotation, Eq. 4).
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may use this
 package.  It shares no code with the HIP path and imports nothing from it.
@@ -22,3 +23,11 @@ from .quantizers import (  # noqa: F401
     quant_eq2_literal,
 )
 from .linear import igemm, igemm_grouped, linear_w8a8, linear_w4a8  # noqa: F401
+from .transforms import (  # noqa: F401
+    channel_absmax,
+    smooth_scales,
+    smooth_act,
+    smooth_weight,
+    hadamard_block,
+    fwht_blocks,
+)

@@ -23,8 +23,9 @@ F32 = np.float32
 
 
 def _as_f32(x16: np.ndarray) -> np.ndarray:
-    if x16.dtype != np.float16:
-        raise TypeError("oracle quantizers take fp16 input")
+    # fp16 = the layer's own operands; fp32 = operands after one of the paper's transforms (Eq. 3-4)
+    if x16.dtype not in (np.float16, np.float32):
+        raise TypeError("oracle quantizers take fp16 (or already transformed fp32) input")
     x = x16.astype(F32)                       # exact widening
     if not np.isfinite(x).all():
         raise ValueError("non-finite input: behaviour is unspecified")

@@ -1,0 +1,90 @@
+"""Oracle for the two outlier-mitigation transforms of the paper's W4A8 variants -- test infrastructure.
+
+SmoothQuant variant (Eq. 3):  Y = (X S^-1)(S W),  S = diag(s),
+    s_j = max|X_j|^alpha / max|W_j|^(1 - alpha)   (alpha = 0.5 in the paper's experiments)
+Hadamard variant (Eq. 4):     Y = (X H)(H^T W),   H a normalized Hadamard matrix.
+
+Both leave Y unchanged in exact arithmetic; what changes is what the quantizers (Eq. 1-2) see.  The
+transformed operands are fp32 arrays here and go to the same quantizers as the plain ones.
+
+Readings (the paper gives the formulas only):
+  * X_j is input channel j of a calibration batch (column j of X[M,K]), W_j the weights that multiply it
+    (row j of W in Y = XW, i.e. column j of the stored w[N,K]); a channel whose activation or weight
+    maximum is 0 keeps s_j = 1.
+  * s is an offline parameter vector in fp32; activations are multiplied by the fp32 reciprocal 1/s_j (one
+    IEEE division, done once), weights by s_j -- one fp32 multiply per element, no rounding back to fp16.
+  * H is the Sylvester (natural-order) Hadamard matrix.  The paper does not say what happens when K is not a
+    power of two; here H is block diagonal, I (x) H_B / sqrt(B), with B the largest power of two that divides
+    K, capped at 4096 -- still orthogonal, so Eq. 4 holds.  It is applied as the textbook in-place butterfly
+    in fp32, stages h = 1, 2, 4, ..., B/2 in that order ((a, b) -> (a + b, a - b), one addition each), then
+    one multiply by fp32(1/sqrt(B)).  With the stage order fixed every result is a fixed sequence of single
+    fp32 operations, so an implementation that keeps the order is bit-identical however it assigns the work.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F32 = np.float32
+MAX_BLOCK = 4096
+
+
+def channel_absmax(x16: np.ndarray) -> np.ndarray:
+    """max|X_j| per input channel of a calibration batch x[M,K] (fp16) -> float32 [K] (exact)."""
+    if x16.dtype != np.float16:
+        raise TypeError("calibration activations are fp16")
+    return np.abs(x16.astype(F32)).max(axis=0) if x16.shape[0] else np.zeros(x16.shape[1], F32)
+
+
+def smooth_scales(x_absmax: np.ndarray, w16: np.ndarray, alpha: float = 0.5):
+    """Eq. 3: s_j = max|X_j|^alpha / max|W_j|^(1-alpha) for w[N,K] (fp16) -> (s, 1/s) float32 [K]."""
+    if w16.dtype != np.float16:
+        raise TypeError("weights are fp16")
+    wmax = np.abs(w16.astype(np.float64)).max(axis=0)
+    xmax = x_absmax.astype(np.float64)
+    live = (xmax > 0) & (wmax > 0)
+    s = np.ones_like(xmax)
+    s[live] = xmax[live] ** alpha / wmax[live] ** (1.0 - alpha)
+    s = s.astype(F32)
+    inv = (F32(1) / s).astype(F32)                        # one fp32 division per channel
+    return s, inv
+
+
+def smooth_act(x16: np.ndarray, inv_s: np.ndarray) -> np.ndarray:
+    """X S^-1: one fp32 multiply per element."""
+    return (x16.astype(F32) * inv_s.astype(F32)[None, :]).astype(F32)
+
+
+def smooth_weight(w16: np.ndarray, s: np.ndarray) -> np.ndarray:
+    """S W for the stored w[N,K]: column j times s_j, one fp32 multiply per element."""
+    return (w16.astype(F32) * s.astype(F32)[None, :]).astype(F32)
+
+
+def hadamard_block(K: int) -> int:
+    """Largest power of two that divides K, capped at MAX_BLOCK."""
+    if K <= 0:
+        raise ValueError("K must be positive")
+    b = K & -K
+    return min(b, MAX_BLOCK)
+
+
+def fwht_blocks(v: np.ndarray, block: int) -> np.ndarray:
+    """v[..., K] (fp16 or fp32) times the block-diagonal normalized Hadamard matrix, along the last axis.
+
+    Stages h = 1, 2, ..., block/2 in order, every output one fp32 addition or subtraction of two inputs;
+    then one fp32 multiply by fp32(1/sqrt(block)).
+    """
+    if block < 1 or block & (block - 1):
+        raise ValueError("block must be a power of two")
+    K = v.shape[-1]
+    if K % block:
+        raise ValueError("block must divide K")
+    a = v.astype(F32).reshape(-1, K // block, block).copy()
+    h = 1
+    while h < block:
+        a = a.reshape(a.shape[0], K // block, block // (2 * h), 2, h)
+        lo = a[:, :, :, 0, :] + a[:, :, :, 1, :]          # one fp32 addition
+        hi = a[:, :, :, 0, :] - a[:, :, :, 1, :]          # one fp32 subtraction
+        a = np.stack([lo, hi], axis=3).reshape(a.shape[0], K // block, block)
+        h *= 2
+    norm = F32(1.0 / np.sqrt(float(block)))
+    return (a * norm).astype(F32).reshape(v.shape)
