@@ -249,4 +249,8 @@ def test_rejects_non_finite_and_wrong_dtype():
     with pytest.raises(ValueError):
         oracle.quant_act_per_token(f16([[1.0, np.inf]]))
     with pytest.raises(TypeError):
-        oracle.quant_act_per_token(np.ones((1, 4), dtype=np.float32))
+        oracle.quant_act_per_token(np.ones((1, 4), dtype=np.float64))
+    # fp32 = operands after the SmoothQuant / Hadamard transforms: same quantizer, same result as the fp16 values
+    x = f16([[0.5, -2.0, 1.25, 0.0]])
+    a, b = oracle.quant_act_per_token(x), oracle.quant_act_per_token(x.astype(np.float32))
+    assert (a[0] == b[0]).all() and (a[1] == b[1]).all()
