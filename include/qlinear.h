@@ -148,6 +148,40 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
  *   other values pick one implementation; unknown values -> QL_ERR_UNSUPPORTED. */
 int ql_set_kernel_variant(int variant);
 
+/* ---- The two enhanced W4A8 configurations of the paper (usable with int8 weights as well) -------------------
+ * SmoothQuant (Eq. 3): Y = (X S^-1)(S W), s_j = max|X_j|^alpha / max|W_j|^(1-alpha) per input channel j.
+ * Hadamard (Eq. 4):    Y = (X H)(H^T W), H a normalized Hadamard matrix: here the natural-order (Sylvester)
+ *   matrix, block diagonal with `hadamard_block` = a power of two in [16,4096] that divides K
+ *   (ql_hadamard_block gives the largest), applied as the in-place butterfly in fp32 (stages 1,2,4,... in
+ *   order, then one multiply by fp32(1/sqrt(block))).
+ * Offline: calibrate -> scales -> ql_quant_weight_transformed.  Online: ql_quant_act_per_token_transformed,
+ * then ql_w8a8_gemm / ql_w4a8_gemm on its output.  Transformed values are fp32 and are never rounded to
+ * fp16; the quantizers are those of ql_quant_act_per_token / ql_quant_weight.  Limit: K <= 16384. */
+
+/* Largest power of two dividing K, at most 4096 (host output). */
+int ql_hadamard_block(int K, int *block /* host */);
+
+/* Running max|X_j| over calibration batches: xmax[j] = max(xmax[j], max_m |x[m,j]|).  xmax is fp32 [K] and
+ * must hold zeros (or earlier results) on entry. */
+int ql_smooth_calibrate(const void *x, int64_t ldx, int M, int K, float *xmax, void *stream);
+
+/* smooth[j] = xmax[j]^alpha / (max_n |w[n,j]|)^(1-alpha), 1 where either maximum is 0;
+ * inv_smooth[j] = 1 / smooth[j].  w fp16 [N,K] contiguous, alpha in [0,1] (the paper uses 0.5). */
+int ql_smooth_scales(const float *xmax, const void *w, int N, int K, float alpha, float *smooth,
+                     float *inv_smooth, void *stream);
+
+/* Per-token int8 quantization of x * diag(inv_smooth) (inv_smooth fp32 [K] or NULL) followed by the block
+ * Hadamard transform (hadamard_block, 0 = none); outputs as ql_quant_act_per_token. */
+int ql_quant_act_per_token_transformed(const void *x, int64_t ldx, int M, int K, const float *inv_smooth,
+                                       int hadamard_block, int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx,
+                                       void *stream);
+
+/* ql_quant_weight applied to w * diag(smooth) (smooth fp32 [K] or NULL), rows then Hadamard-transformed
+ * (hadamard_block, 0 = none).  w32: fp32 [N,K] scratch that receives the transformed weights. */
+int ql_quant_weight_transformed(const void *w, int N, int K, int bits, int group, const float *smooth,
+                                int hadamard_block, float *w32, void *wq_canonical, void *scales,
+                                void *wq_kernel, void *stream);
+
 /* Ceiling probes for benchmarks (nothing of the method): what the GPU sustains on the two resources the
  * layer is bound by, to be timed by the caller with events on `stream`.
  *   ql_probe_mfma_int8: `workgroups` workgroups of 8 wavefronts each issue 4*iters register-resident

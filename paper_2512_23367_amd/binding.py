@@ -24,6 +24,8 @@ EXPORTS = [
     "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
     "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant",
     "ql_probe_mfma_int8", "ql_probe_hbm_read",
+    "ql_hadamard_block", "ql_smooth_calibrate", "ql_smooth_scales",
+    "ql_quant_act_per_token_transformed", "ql_quant_weight_transformed",
 ]
 
 
@@ -69,6 +71,11 @@ def lib() -> ctypes.CDLL:
             "ql_w4a8_gemm_acc_i32": [vp, i, i, vp, i, i, vp, vp, i, i, vp, sz, vp],
             "ql_probe_mfma_int8": [i, i, i, vp, c.POINTER(c.c_int64), vp],
             "ql_probe_hbm_read": [vp, sz, vp, vp],
+            "ql_hadamard_block": [i, c.POINTER(c.c_int)],
+            "ql_smooth_calibrate": [vp, i64, i, i, vp, vp],
+            "ql_smooth_scales": [vp, vp, i, i, c.c_float, vp, vp, vp],
+            "ql_quant_act_per_token_transformed": [vp, i64, i, i, vp, i, vp, vp, vp, vp],
+            "ql_quant_weight_transformed": [vp, i, i, i, i, vp, i, vp, vp, vp, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(l, name)
@@ -124,6 +131,38 @@ def ql_probe_mfma_int8(workgroups: int, iters: int, random_operands: bool, sink)
 def ql_probe_hbm_read(buf, sink):
     """Enqueues one pass of the HBM read-stream probe over the whole of `buf`."""
     _check(lib().ql_probe_hbm_read(_p(buf), buf.numel() * buf.element_size(), _p(sink), _stream()))
+
+
+def ql_hadamard_block(K: int) -> int:
+    b = ctypes.c_int()
+    _check(lib().ql_hadamard_block(K, ctypes.byref(b)))
+    return b.value
+
+
+def ql_smooth_calibrate(x, xmax):
+    _want(x, torch.float16, "x"), _want(xmax, torch.float32, "xmax")
+    M, K = x.shape
+    _check(lib().ql_smooth_calibrate(_p(x), _ld(x) if M else K, M, K, _p(xmax), _stream()))
+
+
+def ql_smooth_scales(xmax, w, alpha, smooth, inv_smooth):
+    _want(w, torch.float16, "w"), _want(xmax, torch.float32, "xmax")
+    N, K = w.shape
+    _check(lib().ql_smooth_scales(_p(xmax), _p(w), N, K, float(alpha), _p(smooth), _p(inv_smooth), _stream()))
+
+
+def ql_quant_act_per_token_transformed(x, inv_smooth, hadamard_block, xq_rowmajor, xq_kernel, sx):
+    _want(x, torch.float16, "x")
+    M, K = x.shape
+    _check(lib().ql_quant_act_per_token_transformed(_p(x), _ld(x) if M else K, M, K, _p(inv_smooth), hadamard_block,
+                                                    _p(xq_rowmajor), _p(xq_kernel), _p(sx), _stream()))
+
+
+def ql_quant_weight_transformed(w, bits, group, smooth, hadamard_block, w32, wq_canonical, scales, wq_kernel):
+    _want(w, torch.float16, "w"), _want(w32, torch.float32, "w32")
+    N, K = w.shape
+    _check(lib().ql_quant_weight_transformed(_p(w), N, K, bits, group, _p(smooth), hadamard_block, _p(w32),
+                                             _p(wq_canonical), _p(scales), _p(wq_kernel), _stream()))
 
 
 def ql_weight_bytes(N, K, bits, group):

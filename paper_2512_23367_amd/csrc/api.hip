@@ -282,6 +282,89 @@ int ql_quant_weight(const void *w, int N, int K, int bits, int group, void *wq_c
                                 static_cast<__half *>(scales), static_cast<uint8_t *>(wq_kernel), st);
 }
 
+// ---- SmoothQuant / Hadamard variants (Eq. 3-4)
+static int check_transform(int K, int hadamard_block)
+{
+    if (K > 16384) return fail(QL_ERR_UNSUPPORTED, "transforms: K=%d above 16384", K);
+    if (hadamard_block != 0) {
+        const bool pow2 = (hadamard_block & (hadamard_block - 1)) == 0;
+        if (!pow2 || hadamard_block < 16 || hadamard_block > 4096 || K % hadamard_block)
+            return fail(QL_ERR_SHAPE, "hadamard_block=%d must be 0 or a power of two in [16,4096] that divides K=%d",
+                        hadamard_block, K);
+    }
+    return QL_OK;
+}
+
+int ql_hadamard_block(int K, int *block)
+{
+    if (K <= 0 || K % 64) return fail(QL_ERR_SHAPE, "K=%d must be a positive multiple of 64", K);
+    if (!block) return fail(QL_ERR_NULL, "block is NULL");
+    *block = hadamard_block_of(K);
+    return QL_OK;
+}
+
+int ql_smooth_calibrate(const void *x, int64_t ldx, int M, int K, float *xmax, void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    if (M == 0) return QL_OK;
+    if (!x || !xmax) return fail(QL_ERR_NULL, "x or xmax is NULL");
+    if (!aligned(x, 16) || ldx < K || ldx % 8 || !aligned(xmax, 16))
+        return fail(QL_ERR_ALIGN, "x, xmax 16-byte aligned, ldx >= K and a multiple of 8");
+    return launch_channel_absmax(static_cast<const __half *>(x), ldx, M, K, xmax, static_cast<hipStream_t>(stream));
+}
+
+int ql_smooth_scales(const float *xmax, const void *w, int N, int K, float alpha, float *smooth, float *inv_smooth,
+                     void *stream)
+{
+    QL_TRY(check_nk(N, K, 8));
+    if (!xmax || !w || !smooth || !inv_smooth) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return fail(QL_ERR_SHAPE, "alpha must lie in [0,1]");
+    if (!aligned(xmax, 16) || !aligned(w, 16) || !aligned(smooth, 16) || !aligned(inv_smooth, 16))
+        return fail(QL_ERR_ALIGN, "xmax, w, smooth, inv_smooth need 16-byte alignment");
+    return launch_smooth_scales(xmax, static_cast<const __half *>(w), N, K, alpha, smooth, inv_smooth,
+                                static_cast<hipStream_t>(stream));
+}
+
+int ql_quant_act_per_token_transformed(const void *x, int64_t ldx, int M, int K, const float *inv_smooth,
+                                       int hadamard_block, int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx,
+                                       void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_transform(K, hadamard_block));
+    if (M == 0) return QL_OK;
+    if (!x || !sx || (!xq_rowmajor && !xq_kernel)) return fail(QL_ERR_NULL, "a required pointer is NULL");
+    if (!aligned(x, 16) || ldx < K || ldx % 8)
+        return fail(QL_ERR_ALIGN, "x must be 16-byte aligned, ldx >= K and a multiple of 8 (ldx=%lld)", (long long)ldx);
+    if ((xq_rowmajor && !aligned(xq_rowmajor, 16)) || (xq_kernel && !aligned(xq_kernel, 256)) || !aligned(sx, 4) ||
+        (inv_smooth && !aligned(inv_smooth, 16)))
+        return fail(QL_ERR_ALIGN, "xq_rowmajor/inv_smooth need 16-byte, xq_kernel 256-byte alignment");
+    return launch_act_quant_transform(static_cast<const __half *>(x), ldx, M, K, inv_smooth, hadamard_block, xq_rowmajor,
+                                      xq_kernel, sx, static_cast<hipStream_t>(stream));
+}
+
+int ql_quant_weight_transformed(const void *w, int N, int K, int bits, int group, const float *smooth,
+                                int hadamard_block, float *w32, void *wq_canonical, void *scales, void *wq_kernel,
+                                void *stream)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_nk(N, K, bits));
+    QL_TRY(check_transform(K, hadamard_block));
+    if (!w || !w32) return fail(QL_ERR_NULL, "w or w32 is NULL");
+    if (bits == 8 && !scales) return fail(QL_ERR_NULL, "scales is required for int8 weights");
+    if (!wq_canonical && !wq_kernel && !scales) return fail(QL_ERR_NULL, "no output requested");
+    if (!aligned(w, 16) || !aligned(w32, 16) || (smooth && !aligned(smooth, 16)) ||
+        (wq_canonical && !aligned(wq_canonical, 16)) || (scales && !aligned(scales, 16)) ||
+        (wq_kernel && !aligned(wq_kernel, 256)))
+        return fail(QL_ERR_ALIGN, "w/w32/smooth/wq_canonical/scales need 16-byte, wq_kernel 256-byte alignment");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    QL_TRY(launch_weight_transform(static_cast<const __half *>(w), N, K, smooth, hadamard_block, w32, st));
+    if (bits == 8)
+        return launch_weight_quant8_f32(w32, N, K, static_cast<int8_t *>(wq_canonical), static_cast<float *>(scales),
+                                        static_cast<int8_t *>(wq_kernel), st);
+    return launch_weight_quant4_f32(w32, N, K, group, static_cast<uint8_t *>(wq_canonical),
+                                    static_cast<__half *>(scales), static_cast<uint8_t *>(wq_kernel), st);
+}
+
 int ql_export_canonical(const void *wq_kernel, int N, int K, int bits, int group, void *wq_canonical,
                         void *scales, void *stream)
 {

@@ -82,6 +82,18 @@ int launch_weight_quant8(const __half *w, int N, int K, int8_t *canon, float *sc
                          hipStream_t st);
 int launch_weight_quant4(const __half *w, int N, int K, int group, uint8_t *canon, __half *scales,
                          uint8_t *kl, hipStream_t st);
+int launch_weight_quant8_f32(const float *w, int N, int K, int8_t *canon, float *scales, int8_t *kl,
+                             hipStream_t st);
+int launch_weight_quant4_f32(const float *w, int N, int K, int group, uint8_t *canon, __half *scales,
+                             uint8_t *kl, hipStream_t st);
+int hadamard_block_of(int K);
+int launch_act_quant_transform(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, int hblock,
+                               int8_t *xq_rm, int8_t *xq_kl, float *sx, hipStream_t st);
+int launch_weight_transform(const __half *w, int N, int K, const float *smooth, int hblock, float *out,
+                            hipStream_t st);
+int launch_channel_absmax(const __half *x, int64_t ldx, int M, int K, float *xmax, hipStream_t st);
+int launch_smooth_scales(const float *xmax, const __half *w, int N, int K, float alpha, float *s, float *inv_s,
+                         hipStream_t st);
 int launch_export8(const int8_t *kl, int N, int K, int8_t *canon, hipStream_t st);
 int launch_export4(const uint8_t *kl, int N, int K, int group, uint8_t *canon, __half *scales,
                    hipStream_t st);

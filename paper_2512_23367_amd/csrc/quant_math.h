@@ -61,6 +61,29 @@ __device__ inline uint4 quant_chunk(const Half16 &v, float inv)
     return q;
 }
 
+// the same code decision for an fp32 value (operands after one of the paper's transforms, Eq. 3-4)
+__device__ inline int quant_code_f32(float x, float inv)
+{
+    float r = rintf(x * inv);                           // one fp32 multiply, round half to even
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+__device__ inline uint4 quant_chunk_f32(const float (&v)[16], float inv)
+{
+    unsigned q[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) q[i / 4] |= (unsigned)(quant_code_f32(v[i], inv) & 0xff) << (8 * (i % 4));
+    return make_uint4(q[0], q[1], q[2], q[3]);
+}
+
+__device__ inline void token_scales_f32(float amax, float &scale, float &inv)
+{
+    const bool zero = (amax == 0.0f);
+    scale = zero ? 1.0f : amax / 127.0f;    // IEEE fp32 division
+    inv = zero ? 0.0f : 127.0f / amax;      // IEEE fp32 division
+}
+
 // token scale and its reciprocal from the bit pattern of the largest |x|
 __device__ inline void token_scales(unsigned amax_bits, float &scale, float &inv)
 {

@@ -1,0 +1,260 @@
+// The operand transforms of the paper's two enhanced W4A8 configurations, for gfx950:
+//   SmoothQuant (Eq. 3):  Y = (X S^-1)(S W),  s_j = max|X_j|^alpha / max|W_j|^(1-alpha)
+//   Hadamard   (Eq. 4):  Y = (X H)(H^T W),   H a normalized Hadamard matrix
+// Online: the activation side (per-channel multiply by 1/s_j, or a fast Walsh-Hadamard transform of every
+// token) is fused in front of the per-token int8 quantizer (Eq. 1-2), one workgroup per token, fp32 throughout.
+// Offline: calibration statistics, the scale vector, and the transformed fp32 weights handed to the weight
+// quantizer.
+//
+// H is the natural-order (Sylvester) matrix, block diagonal with blocks of B = the largest power of two that
+// divides K (at most 4096) so that any K % 64 == 0 works.  It is applied as the in-place butterfly in fp32,
+// stages h = 1, 2, ..., B/2 in that order, every output one addition or subtraction, then one multiply by
+// fp32(1/sqrt(B)): a fixed sequence of single fp32 operations per element, whatever lane does them.
+// A lane holds chunks of 16 consecutive elements: stages h <= 8 in registers, the next six across the lanes
+// of a wavefront, the last two (B > 1024) across wavefronts through LDS.
+#include "common.h"
+#include "quant_math.h"
+#include <cmath>
+
+namespace ql {
+namespace {
+
+constexpr int TW = 256;                 // threads per workgroup (one token / one weight row)
+constexpr int MAX_NIT = 4;              // chunks per thread: K <= 16384
+
+__device__ inline void load_chunk(const __half *row, int c, float (&v)[16])
+{
+    const Half16 h = reinterpret_cast<const Half16 *>(row)[c];
+    const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[2 * i] = half_bits_to_float(w[i] & 0xffffu);
+        v[2 * i + 1] = half_bits_to_float(w[i] >> 16);
+    }
+}
+
+__device__ inline void scale_chunk(const float *__restrict__ s, int c, float (&v)[16])
+{
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+        const float4 f = *reinterpret_cast<const float4 *>(s + (size_t)c * 16 + i);
+        v[i] *= f.x, v[i + 1] *= f.y, v[i + 2] *= f.z, v[i + 3] *= f.w;   // one fp32 multiply each
+    }
+}
+
+// Block-diagonal Hadamard transform of the row whose chunk (it * TW + tid) sits in v[it]; lanes per block
+// = hblock / 16 (a power of two that divides TW and the number of chunks, so a block never straddles an `it`).
+template <int NIT>
+__device__ inline void fwht_row(float (&v)[NIT][16], int hblock, float norm, float *xchg /* [TW][16] */)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+#pragma unroll
+        for (int h = 1; h < 16; h <<= 1)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if ((i & h) == 0) {
+                    const float a = v[it][i], b = v[it][i | h];
+                    v[it][i] = a + b;
+                    v[it][i | h] = a - b;
+                }
+    }
+    const int lanes = hblock / 16;
+    for (int bit = 1; bit < lanes; bit <<= 1) {
+        const bool upper = (tid & bit) != 0;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            float o[16];
+            if (bit < 64) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[i] = __shfl_xor(v[it][i], bit, 64);
+            } else {
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < 16; ++i) xchg[i * TW + tid] = v[it][i];
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[i] = xchg[i * TW + (tid ^ bit)];
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[it][i] = upper ? o[i] - v[it][i] : v[it][i] + o[i];
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[it][i] *= norm;
+}
+
+// One workgroup per token: load, transform, per-token abs-max, quantize, store (row-major and/or tile order).
+template <int NIT>
+__global__ __launch_bounds__(TW) void act_quant_transform_kernel(const __half *__restrict__ x, int64_t ldx, int K,
+                                                                 const float *__restrict__ inv_smooth, int hblock,
+                                                                 float norm, int8_t *__restrict__ xq_rm,
+                                                                 int8_t *__restrict__ xq_kl, float *__restrict__ sx)
+{
+    __shared__ float xchg[16 * TW];
+    __shared__ float red[TW / 64];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const int nchunks = K / 16;
+    const __half *row = x + (size_t)m * ldx;
+    float v[NIT][16];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int c = it * TW + tid;
+        if (c < nchunks) {
+            load_chunk(row, c, v[it]);
+            if (inv_smooth) scale_chunk(inv_smooth, c, v[it]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[it][i] = 0.0f;
+        }
+    }
+    if (hblock > 1) fwht_row<NIT>(v, hblock, norm, xchg);
+
+    float amax = 0.0f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[it][i]));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    __syncthreads();
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float scale, inv;
+    token_scales_f32(amax, scale, inv);
+    if (tid == 0) sx[m] = scale;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int c = it * TW + tid;
+        if (c < nchunks) {
+            const uint4 q = quant_chunk_f32(v[it], inv);
+            if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * 16) = q;
+            if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * 16, K)) = q;
+        }
+    }
+}
+
+// Offline: one workgroup per weight row (output channel): S W and/or H^T W as fp32
+template <int NIT>
+__global__ __launch_bounds__(TW) void weight_transform_kernel(const __half *__restrict__ w, int K,
+                                                              const float *__restrict__ smooth, int hblock, float norm,
+                                                              float *__restrict__ out)
+{
+    __shared__ float xchg[16 * TW];
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const int nchunks = K / 16;
+    float v[NIT][16];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int c = it * TW + tid;
+        if (c < nchunks) {
+            load_chunk(w + (size_t)n * K, c, v[it]);
+            if (smooth) scale_chunk(smooth, c, v[it]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[it][i] = 0.0f;
+        }
+    }
+    if (hblock > 1) fwht_row<NIT>(v, hblock, norm, xchg);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int c = it * TW + tid;
+        if (c < nchunks) {
+#pragma unroll
+            for (int i = 0; i < 16; i += 4)
+                *reinterpret_cast<float4 *>(out + (size_t)n * K + (size_t)c * 16 + i) =
+                    make_float4(v[it][i], v[it][i + 1], v[it][i + 2], v[it][i + 3]);
+        }
+    }
+}
+
+// Calibration: running max|X_j| per input channel (non-negative floats order like their bit patterns)
+__global__ void channel_absmax_kernel(const __half *__restrict__ x, int64_t ldx, int M, int K, int rows_per_block,
+                                      unsigned *__restrict__ xmax_bits)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    const int m0 = blockIdx.y * rows_per_block;
+    const int m1 = min(M, m0 + rows_per_block);
+    float mx = 0.0f;
+    for (int m = m0; m < m1; ++m) mx = fmaxf(mx, fabsf(__half2float(x[(size_t)m * ldx + k])));
+    atomicMax(xmax_bits + k, __float_as_uint(mx));
+}
+
+// s_j = xmax_j^alpha / wmax_j^(1-alpha), 1 where either maximum is 0; inv_j = 1 / s_j (IEEE fp32 division)
+__global__ void smooth_scales_kernel(const float *__restrict__ xmax, const __half *__restrict__ w, int N, int K,
+                                     float alpha, float *__restrict__ s, float *__restrict__ inv_s)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    float wmax = 0.0f;
+    for (int n = 0; n < N; ++n) wmax = fmaxf(wmax, fabsf(__half2float(w[(size_t)n * K + k])));
+    const float xm = xmax[k];
+    float sj = 1.0f;
+    if (xm > 0.0f && wmax > 0.0f) sj = (float)(pow((double)xm, (double)alpha) / pow((double)wmax, 1.0 - (double)alpha));
+    s[k] = sj;
+    inv_s[k] = 1.0f / sj;
+}
+
+float block_norm(int hblock) { return (float)(1.0 / std::sqrt((double)hblock)); }
+
+}  // namespace
+
+int hadamard_block_of(int K)
+{
+    const int b = K & -K;
+    return b < 4096 ? b : 4096;
+}
+
+int launch_act_quant_transform(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, int hblock,
+                               int8_t *xq_rm, int8_t *xq_kl, float *sx, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    const int nit = ceil_div(K / 16, TW);
+    const float norm = block_norm(hblock > 1 ? hblock : 1);
+#define QL_LAUNCH(NIT)                                                                                              \
+    hipLaunchKernelGGL((act_quant_transform_kernel<NIT>), dim3(M), dim3(TW), 0, st, x, ldx, K, inv_smooth, hblock, \
+                       norm, xq_rm, xq_kl, sx)
+    if (nit == 1) QL_LAUNCH(1);
+    else if (nit == 2) QL_LAUNCH(2);
+    else if (nit == 3) QL_LAUNCH(3);
+    else QL_LAUNCH(4);
+#undef QL_LAUNCH
+    return check_hip(hipGetLastError(), "act_quant_transform launch");
+}
+
+int launch_weight_transform(const __half *w, int N, int K, const float *smooth, int hblock, float *out, hipStream_t st)
+{
+    const int nit = ceil_div(K / 16, TW);
+    const float norm = block_norm(hblock > 1 ? hblock : 1);
+#define QL_LAUNCH(NIT) \
+    hipLaunchKernelGGL((weight_transform_kernel<NIT>), dim3(N), dim3(TW), 0, st, w, K, smooth, hblock, norm, out)
+    if (nit == 1) QL_LAUNCH(1);
+    else if (nit == 2) QL_LAUNCH(2);
+    else if (nit == 3) QL_LAUNCH(3);
+    else QL_LAUNCH(4);
+#undef QL_LAUNCH
+    return check_hip(hipGetLastError(), "weight_transform launch");
+}
+
+int launch_channel_absmax(const __half *x, int64_t ldx, int M, int K, float *xmax, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    const int rows_per_block = 64;
+    hipLaunchKernelGGL(channel_absmax_kernel, dim3(ceil_div(K, 256), ceil_div(M, rows_per_block)), dim3(256), 0, st, x,
+                       ldx, M, K, rows_per_block, reinterpret_cast<unsigned *>(xmax));
+    return check_hip(hipGetLastError(), "channel_absmax launch");
+}
+
+int launch_smooth_scales(const float *xmax, const __half *w, int N, int K, float alpha, float *s, float *inv_s,
+                         hipStream_t st)
+{
+    hipLaunchKernelGGL(smooth_scales_kernel, dim3(ceil_div(K, 256)), dim3(256), 0, st, xmax, w, N, K, alpha, s, inv_s);
+    return check_hip(hipGetLastError(), "smooth_scales launch");
+}
+
+}  // namespace ql

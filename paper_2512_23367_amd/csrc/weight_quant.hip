@@ -17,39 +17,49 @@ struct alignas(16) Half16 {
     uint4 lo, hi;
 };
 
-__device__ inline void unpack16(const Half16 &v, unsigned short (&h)[16])
+// 16 consecutive weights as fp32: from fp16 (exact widening) or from the fp32 output of a transform kernel
+__device__ inline void load16(const __half *row, int c, float (&v)[16])
 {
-    const unsigned w[8] = {v.lo.x, v.lo.y, v.lo.z, v.lo.w, v.hi.x, v.hi.y, v.hi.z, v.hi.w};
+    const Half16 h = reinterpret_cast<const Half16 *>(row)[c];
+    const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        h[2 * i] = (unsigned short)(w[i] & 0xffffu);
-        h[2 * i + 1] = (unsigned short)(w[i] >> 16);
+        v[2 * i] = __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
+        v[2 * i + 1] = __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
     }
 }
 
-__device__ inline unsigned amax_bits16(const unsigned short (&h)[16])
+__device__ inline void load16(const float *row, int c, float (&v)[16])
 {
-    unsigned m = 0;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) m = max(m, (unsigned)(h[i] & 0x7fffu));
+    for (int i = 0; i < 16; i += 4) {
+        const float4 f = *reinterpret_cast<const float4 *>(row + (size_t)c * CHUNK + i);
+        v[i] = f.x, v[i + 1] = f.y, v[i + 2] = f.z, v[i + 3] = f.w;
+    }
+}
+
+__device__ inline float amax16(const float (&v)[16])
+{
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) m = fmaxf(m, fabsf(v[i]));
     return m;
 }
 
-__device__ inline float hbits_to_float(unsigned short b) { return __half2float(__ushort_as_half(b)); }
-
-__device__ inline int code_div(unsigned short hbits, float scale, float lim)
+__device__ inline int code_div(float x, float scale, float lim)
 {
-    const float t = hbits_to_float(hbits) / scale;   // IEEE fp32 division by the stored scale
+    const float t = x / scale;   // IEEE fp32 division by the stored scale
     float r = rintf(t);
     r = fminf(fmaxf(r, -lim), lim);
     return (int)r;
 }
 
-__global__ void weight_quant8_kernel(const __half *__restrict__ w, int N, int K,
+template <typename T>
+__global__ void weight_quant8_kernel(const T *__restrict__ w, int N, int K,
                                      int8_t *__restrict__ canon, float *__restrict__ scales,
                                      int8_t *__restrict__ kl)
 {
-    __shared__ unsigned red[4];
+    __shared__ float red[4];
     const int n = blockIdx.x;
     const int nchunks = K / CHUNK;
     if (n >= N) {   // padding rows of the kernel layout
@@ -58,26 +68,26 @@ __global__ void weight_quant8_kernel(const __half *__restrict__ w, int N, int K,
                 *reinterpret_cast<uint4 *>(kl + tile_offset_i8(n, c * CHUNK, K)) = make_uint4(0, 0, 0, 0);
         return;
     }
-    const Half16 *row = reinterpret_cast<const Half16 *>(w + (size_t)n * K);
-    unsigned mx = 0;
+    const T *row = w + (size_t)n * K;
+    float mx = 0.0f;
     for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
-        unsigned short h[16];
-        unpack16(row[c], h);
-        mx = max(mx, amax_bits16(h));
+        float h[16];
+        load16(row, c, h);
+        mx = fmaxf(mx, amax16(h));
     }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
     __syncthreads();
-    mx = max(max(red[0], red[1]), max(red[2], red[3]));
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 
-    float s = hbits_to_float((unsigned short)mx) / 127.0f;
+    float s = mx / 127.0f;
     if (s == 0.0f) s = 1.0f;
     if (threadIdx.x == 0 && scales) scales[n] = s;
 
     for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
-        unsigned short h[16];
-        unpack16(row[c], h);
+        float h[16];
+        load16(row, c, h);
         unsigned q[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int i = 0; i < 16; ++i) q[i / 4] |= (unsigned)(code_div(h[i], s, 127.0f) & 0xff) << (8 * (i % 4));
@@ -88,7 +98,8 @@ __global__ void weight_quant8_kernel(const __half *__restrict__ w, int N, int K,
 }
 
 // group == 128: eight consecutive lanes hold one group.
-__global__ void weight_quant4_kernel(const __half *__restrict__ w, int N, int Npad, int K,
+template <typename T>
+__global__ void weight_quant4_kernel(const T *__restrict__ w, int N, int Npad, int K,
                                      uint8_t *__restrict__ canon, __half *__restrict__ scales,
                                      uint8_t *__restrict__ kl_codes, __half *__restrict__ kl_scales,
                                      __half *__restrict__ kl_scales_dec)
@@ -97,18 +108,18 @@ __global__ void weight_quant4_kernel(const __half *__restrict__ w, int N, int Np
     const int nchunks = K / CHUNK;
     const int G = K / 128;
     for (int c = threadIdx.x; c < nchunks; c += blockDim.x) {
-        unsigned short h[16];
+        float h[16];
         if (n < N) {
-            unpack16(reinterpret_cast<const Half16 *>(w + (size_t)n * K)[c], h);
+            load16(w + (size_t)n * K, c, h);
         } else {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) h[i] = 0;
+            for (int i = 0; i < 16; ++i) h[i] = 0.0f;
         }
-        unsigned mx = amax_bits16(h);
-        mx = max(mx, (unsigned)__shfl_xor((int)mx, 1, 64));
-        mx = max(mx, (unsigned)__shfl_xor((int)mx, 2, 64));
-        mx = max(mx, (unsigned)__shfl_xor((int)mx, 4, 64));
-        const float s32 = hbits_to_float((unsigned short)mx) / 7.0f;   // IEEE fp32 division
+        float mx = amax16(h);
+        mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
+        const float s32 = mx / 7.0f;   // IEEE fp32 division
         __half s16 = __float2half_rn(s32);
         if (__half2float(s16) == 0.0f) s16 = __float2half_rn(1.0f);
         const float s = __half2float(s16);
@@ -176,24 +187,49 @@ __global__ void export4_kernel(const uint8_t *__restrict__ kl_codes, const __hal
 
 }  // namespace
 
-int launch_weight_quant8(const __half *w, int N, int K, int8_t *canon, float *scales, int8_t *kl,
-                         hipStream_t st)
+template <typename T>
+static int launch_wq8(const T *w, int N, int K, int8_t *canon, float *scales, int8_t *kl, hipStream_t st)
 {
     const int rows = kl ? round_up(N, TILE_ROWS) : N;
-    hipLaunchKernelGGL(weight_quant8_kernel, dim3(rows), dim3(256), 0, st, w, N, K, canon, scales, kl);
+    hipLaunchKernelGGL(weight_quant8_kernel<T>, dim3(rows), dim3(256), 0, st, w, N, K, canon, scales, kl);
     return check_hip(hipGetLastError(), "weight_quant8 launch");
 }
 
-int launch_weight_quant4(const __half *w, int N, int K, int group, uint8_t *canon, __half *scales,
-                         uint8_t *kl, hipStream_t st)
+template <typename T>
+static int launch_wq4(const T *w, int N, int K, int group, uint8_t *canon, __half *scales, uint8_t *kl, hipStream_t st)
 {
     const int Npad = round_up(N, TILE_ROWS);
     const int rows = kl ? Npad : N;
     __half *kls = kl ? reinterpret_cast<__half *>(kl + w4_scales_offset(N, K)) : nullptr;
     __half *klsd = kl ? reinterpret_cast<__half *>(kl + w4_scales_dec_offset(N, K, group)) : nullptr;
-    hipLaunchKernelGGL(weight_quant4_kernel, dim3(rows), dim3(256), 0, st, w, N, Npad, K, canon, scales,
+    hipLaunchKernelGGL(weight_quant4_kernel<T>, dim3(rows), dim3(256), 0, st, w, N, Npad, K, canon, scales,
                        kl, kls, klsd);
     return check_hip(hipGetLastError(), "weight_quant4 launch");
+}
+
+int launch_weight_quant8(const __half *w, int N, int K, int8_t *canon, float *scales, int8_t *kl,
+                         hipStream_t st)
+{
+    return launch_wq8(w, N, K, canon, scales, kl, st);
+}
+
+int launch_weight_quant4(const __half *w, int N, int K, int group, uint8_t *canon, __half *scales,
+                         uint8_t *kl, hipStream_t st)
+{
+    return launch_wq4(w, N, K, group, canon, scales, kl, st);
+}
+
+// the same quantizers on fp32 weights (the output of a transform, Eq. 3-4)
+int launch_weight_quant8_f32(const float *w, int N, int K, int8_t *canon, float *scales, int8_t *kl,
+                             hipStream_t st)
+{
+    return launch_wq8(w, N, K, canon, scales, kl, st);
+}
+
+int launch_weight_quant4_f32(const float *w, int N, int K, int group, uint8_t *canon, __half *scales,
+                             uint8_t *kl, hipStream_t st)
+{
+    return launch_wq4(w, N, K, group, canon, scales, kl, st);
 }
 
 int launch_export8(const int8_t *kl, int N, int K, int8_t *canon, hipStream_t st)

@@ -1,0 +1,196 @@
+"""GPU parity of the SmoothQuant (paper Eq. 3) and Hadamard (Eq. 4) variants against the oracle: calibration
+statistics, scale vector, transformed + quantized activations and weights (codes and scales bit-exact), and the
+end-to-end layer through the ordinary GEMM entry points."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2512_23367_amd import binding as ql, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+@pytest.fixture(autouse=True)
+def _auto_variant():
+    yield
+    ql.ql_set_kernel_variant(0)
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def gpu_act(G, x, inv_s, block, ldx=None):
+    import torch
+    M, K = x.shape
+    if ldx is None:
+        xd = _dev(x)
+    else:
+        buf = torch.full((M, ldx), float("nan"), dtype=torch.float16, device="cuda:0")
+        buf[:, :K] = _dev(x)
+        xd = buf[:, :K]
+    xq = torch.empty((M, K), dtype=torch.int8, device="cuda:0")
+    sx = torch.empty((M,), dtype=torch.float32, device="cuda:0")
+    xk = G.empty_bytes(ql.ql_act_kernel_bytes(M, K))
+    ql.ql_quant_act_per_token_transformed(xd, None if inv_s is None else _dev(inv_s), block, xq, xk, sx)
+    torch.cuda.synchronize()
+    return xq.cpu().numpy(), sx.cpu().numpy(), xk, sx
+
+
+def gpu_weight(G, w, bits, smooth, block):
+    import torch
+    N, K = w.shape
+    group = 0 if bits == 8 else 128
+    cb, sb, kb = ql.ql_weight_bytes(N, K, bits, group)
+    canon, scales, kern = G.empty_bytes(cb), G.empty_bytes(sb), G.empty_bytes(kb)
+    w32 = torch.empty((N, K), dtype=torch.float32, device="cuda:0")
+    ql.ql_quant_weight_transformed(_dev(w), bits, group, None if smooth is None else _dev(smooth), block, w32, canon,
+                                   scales, kern)
+    torch.cuda.synchronize()
+    if bits == 8:
+        c = canon.cpu().numpy().view(np.int8).reshape(N, K)
+        s = scales.cpu().numpy().view(np.float32).reshape(N)
+    else:
+        c = canon.cpu().numpy().reshape(N, K // 2)
+        s = scales.cpu().numpy().view(np.float16).reshape(N, K // 128)
+    return dict(canon=c, scales=s, scales_dev=scales, kernel=kern, N=N, K=K, bits=bits, group=group,
+                w32=w32.cpu().numpy())
+
+
+@pytest.mark.parametrize("K", [64, 192, 512, 1536, 4096, 6144, 11008, 16384])
+def test_hadamard_block_query(K):
+    assert ql.ql_hadamard_block(K) == oracle.hadamard_block(K)
+
+
+def test_calibration_statistics_and_smooth_scales(G):
+    import torch
+    x1, x2 = synth.activations(100, 1536, 1, "qkv"), synth.activations(37, 1536, 2, "qkv")
+    w = synth.weights(200, 1536, 1, "qkv")
+    w[:, 5] = 0                                           # a dead weight channel keeps s = 1
+    x1[:, 9] = 0
+    x2[:, 9] = 0                                          # a dead activation channel too
+    xmax = torch.zeros(1536, dtype=torch.float32, device="cuda:0")
+    ql.ql_smooth_calibrate(_dev(x1), xmax)
+    ql.ql_smooth_calibrate(_dev(x2), xmax)                # running maximum over batches
+    ref = np.maximum(oracle.channel_absmax(x1), oracle.channel_absmax(x2))
+    assert (xmax.cpu().numpy() == ref).all()
+    s = torch.empty(1536, dtype=torch.float32, device="cuda:0")
+    inv = torch.empty_like(s)
+    for alpha in (0.5, 0.25, 1.0):
+        ql.ql_smooth_scales(xmax, _dev(w), alpha, s, inv)
+        torch.cuda.synchronize()
+        s_o, inv_o = oracle.smooth_scales(ref, w, alpha)
+        np.testing.assert_allclose(s.cpu().numpy(), s_o, rtol=3e-7)
+        np.testing.assert_allclose(inv.cpu().numpy(), inv_o, rtol=4e-7)
+        assert s.cpu().numpy()[5] == 1 and s.cpu().numpy()[9] == 1
+        assert (inv.cpu().numpy() == (np.float32(1) / s.cpu().numpy())).all()
+
+
+@pytest.mark.parametrize("M,K,ldx", [(33, 512, None), (5, 1536, 1544), (64, 4096, None), (3, 11008, None), (2, 192, None),
+                                     (7, 6144, None), (1, 16384, None), (40, 64, 72)])
+def test_hadamard_activation_quantization_bit_exact(G, M, K, ldx):
+    x = synth.activations(M, K, 0, "single")
+    if M > 1:
+        x[M // 2] = 0                                     # an all-zero token: scale 1, codes 0
+    B = oracle.hadamard_block(K)
+    xq_o, sx_o = oracle.quant_act_per_token(oracle.fwht_blocks(x, B))
+    xq, sx, xk, _ = gpu_act(G, x, None, B, ldx)
+    assert (sx == sx_o).all()
+    assert (xq == xq_o).all()
+    # the tile-order copy holds the same codes (bytes of rows >= M are never written)
+    Mp = (M + 31) // 32 * 32
+    idx = np.arange(Mp * K)
+    valid = (idx // 1024 // (K // 32)) * 32 + (idx % 1024 // 16) % 32 < M
+    assert (G.repack_act(xq_o).cpu().numpy()[valid] == xk.cpu().numpy()[valid]).all()
+    # a smaller block is a different (still orthogonal) transform and must match the oracle as well
+    if B >= 64:
+        xq2, sx2, _, _ = gpu_act(G, x, None, B // 4)
+        xq_o2, sx_o2 = oracle.quant_act_per_token(oracle.fwht_blocks(x, B // 4))
+        assert (sx2 == sx_o2).all() and (xq2 == xq_o2).all()
+
+
+@pytest.mark.parametrize("M,K", [(33, 512), (9, 1536), (4, 11008)])
+def test_smooth_activation_quantization_bit_exact(G, M, K):
+    x = synth.activations(M, K, 0, "single")
+    w = synth.weights(64, K, 0, "single")
+    s, inv = oracle.smooth_scales(oracle.channel_absmax(synth.activations(64, K, 5, "single")), w, 0.5)
+    xq_o, sx_o = oracle.quant_act_per_token(oracle.smooth_act(x, inv))
+    xq, sx, _, _ = gpu_act(G, x, inv, 0)
+    assert (sx == sx_o).all() and (xq == xq_o).all()
+    # both transforms together (scale, then rotate) are also a fixed sequence of fp32 operations
+    B = oracle.hadamard_block(K)
+    xq_o, sx_o = oracle.quant_act_per_token(oracle.fwht_blocks(oracle.smooth_act(x, inv), B))
+    xq, sx, _, _ = gpu_act(G, x, inv, B)
+    assert (sx == sx_o).all() and (xq == xq_o).all()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("N,K", [(100, 512), (48, 1536), (33, 11008), (64, 4096)])
+def test_transformed_weight_quantization_bit_exact(G, bits, N, K):
+    w = synth.weights(N, K, 0, "single")
+    s, _ = oracle.smooth_scales(oracle.channel_absmax(synth.activations(64, K, 5, "single")), w, 0.5)
+    B = oracle.hadamard_block(K)
+    for smooth, block, w_t in ((None, B, oracle.fwht_blocks(w, B)), (s, 0, oracle.smooth_weight(w, s))):
+        g = gpu_weight(G, w, bits, smooth, block)
+        assert (g["w32"] == w_t).all()
+        if bits == 8:
+            q_o, s_o = oracle.quant_weight_int8(w_t)
+            assert (g["scales"] == s_o).all() and (g["canon"] == q_o).all()
+        else:
+            p_o, _, s_o = oracle.quant_weight_int4(w_t, 128)
+            assert (g["scales"] == s_o).all() and (g["canon"] == p_o).all()
+        c2, s2 = G.gpu_export(g["kernel"], N, K, bits, g["group"])
+        assert (c2 == g["canon"]).all()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N", [(100, 1024, 200), (8, 4096, 136), (300, 1536, 264)])
+def test_transformed_layer_end_to_end(G, bits, M, K, N):
+    """quantize(transform(x)) x quantize(transform(w)) through the ordinary GEMM entry points: within tolerance of
+    the oracle on the same transformed operands, and closer to the exact fp64 product than the plain layer."""
+    import torch
+    x = synth.activations(M, K, 3, "qkv")
+    w = synth.weights(N, K, 3, "qkv")
+    b = synth.bias(N, 3, "qkv")
+    exact = x.astype(np.float64) @ w.astype(np.float64).T + b.astype(np.float64)
+    rel = lambda y: np.linalg.norm(y.astype(np.float64) - exact) / np.linalg.norm(exact)
+    plain = rel(G.gpu_linear(x, G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128), b))
+    B = oracle.hadamard_block(K)
+    s, inv = oracle.smooth_scales(oracle.channel_absmax(x), w, 0.5)
+    for smooth, inv_s, block, x_t, w_t in ((None, None, B, oracle.fwht_blocks(x, B), oracle.fwht_blocks(w, B)),
+                                           (s, inv, 0, oracle.smooth_act(x, inv), oracle.smooth_weight(w, s))):
+        g = gpu_weight(G, w, bits, smooth, block)
+        _, _, xk, sx = gpu_act(G, x, inv_s, block)
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda:0")
+        if bits == 8:
+            ql.ql_w8a8_gemm(xk, sx, M, K, g["kernel"], g["scales_dev"].view(torch.float32), _dev(b), N, y)
+            ref = oracle.linear_w8a8(x_t, g["canon"], g["scales"], b)
+        else:
+            ql.ql_w4a8_gemm(xk, sx, M, K, g["kernel"], 128, _dev(b), N, y)
+            ref = oracle.linear_w4a8(x_t, g["canon"], g["scales"], 128, b)
+        torch.cuda.synchronize()
+        y = y.cpu().numpy()
+        assert G.norm_err(y, ref["y64"]) <= TOL
+        assert rel(y) < plain * (0.6 if bits == 8 else 1.0)
+
+
+def test_transform_argument_errors(G):
+    import torch
+    x = torch.zeros((4, 512), dtype=torch.float16, device="cuda:0")
+    xq = torch.empty((4, 512), dtype=torch.int8, device="cuda:0")
+    sx = torch.empty(4, dtype=torch.float32, device="cuda:0")
+    for bad in (3, 8, 48, 1024, 8192):                    # not a power of two / below 16 / does not divide K / too large
+        with pytest.raises(ql.QlError):
+            ql.ql_quant_act_per_token_transformed(x, None, bad, xq, None, sx)
+    big = torch.zeros((1, 32768), dtype=torch.float16, device="cuda:0")
+    with pytest.raises(ql.QlError):
+        ql.ql_quant_act_per_token_transformed(big, None, 4096, torch.empty((1, 32768), dtype=torch.int8, device="cuda:0"),
+                                              None, sx[:1])
