@@ -28,13 +28,36 @@ constexpr int SINGLE_TOKEN_MAX_M = 512;
 constexpr int MAX_RPB = 8;
 constexpr int MAX_WAVES = 8;
 
-template <int NIT, int RPB>
+// SM: the SmoothQuant variant (paper Eq. 3): every element is first multiplied by inv_smooth[k] = 1 / s_k (one
+// fp32 multiply, done again when the codes are produced -- cheaper than keeping fp32 copies in registers), the
+// row maximum is taken on those fp32 products (non-negative floats order like their bit patterns).
+template <int NIT, int RPB, bool SM>
 __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half *__restrict__ x, int64_t ldx,
                                                                     int M, int K, int per_wave,
+                                                                    const float *__restrict__ inv_smooth,
                                                                     int8_t *__restrict__ xq_rm,
                                                                     int8_t *__restrict__ xq_kl,
                                                                     float *__restrict__ sx)
 {
+    auto smoothed = [&](const Half16 &h, int c, float (&f)[16]) {
+        const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
+#pragma unroll
+        for (int i = 0; i < 16; i += 4) {
+            const float4 s4 = *reinterpret_cast<const float4 *>(inv_smooth + (size_t)c * CHUNK + i);
+            f[i] = half_bits_to_float(w[i / 2] & 0xffffu) * s4.x;
+            f[i + 1] = half_bits_to_float(w[i / 2] >> 16) * s4.y;
+            f[i + 2] = half_bits_to_float(w[i / 2 + 1] & 0xffffu) * s4.z;
+            f[i + 3] = half_bits_to_float(w[i / 2 + 1] >> 16) * s4.w;
+        }
+    };
+    auto row_max = [&](const Half16 &h, int c, unsigned m) {
+        if (!SM) return abs_max_bits(h, m);
+        float f[16];
+        smoothed(h, c, f);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) m = max(m, __float_as_uint(fabsf(f[i])));
+        return m;
+    };
     __shared__ unsigned red[MAX_RPB][MAX_WAVES];
     constexpr int CPS = 64 / RPB;                       // chunks per wavefront per step
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
@@ -53,13 +76,13 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
             const int c = (s0 + i) * CPS + cl;
             if (i < per_wave && c < nchunks && valid) {
                 v[i] = row[c];
-                mx = abs_max_bits(v[i], mx);
+                mx = row_max(v[i], c, mx);
             }
         }
     } else {
         for (int i = 0; i < per_wave; ++i) {
             const int c = (s0 + i) * CPS + cl;
-            if (c < nchunks && valid) mx = abs_max_bits(row[c], mx);
+            if (c < nchunks && valid) mx = row_max(row[c], c, mx);
         }
     }
 #pragma unroll
@@ -70,11 +93,19 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     for (int w = 0; w < nwaves; ++w) mx = max(mx, red[r][w]);
 
     float scale, inv;
-    token_scales(mx, scale, inv);
+    if (SM) token_scales_f32(__uint_as_float(mx), scale, inv);
+    else token_scales(mx, scale, inv);
     if (wave == 0 && cl == 0 && valid) sx[m] = scale;
 
     auto emit = [&](int c, const Half16 &h) {
-        const uint4 q = quant_chunk(h, inv);
+        uint4 q;
+        if (SM) {
+            float f[16];
+            smoothed(h, c, f);
+            q = quant_chunk_f32(f, inv);
+        } else {
+            q = quant_chunk(h, inv);
+        }
         if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK) = q;
         if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = q;
     };
@@ -107,16 +138,17 @@ __global__ void act_repack_kernel(const int8_t *__restrict__ xq_rm, int M, int K
 
 }  // namespace
 
-template <int RPB>
-static void launch_aq(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, int8_t *xq_kl, float *sx,
-                      hipStream_t st)
+template <int RPB, bool SM>
+static void launch_aq(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, int8_t *xq_rm,
+                      int8_t *xq_kl, float *sx, hipStream_t st)
 {
     const int steps = ceil_div(K / CHUNK, 64 / RPB);
     const int nw = steps < MAX_WAVES ? steps : MAX_WAVES;
     const int per_wave = ceil_div(steps, nw);
     dim3 grid(ceil_div(M, RPB)), block(nw * 64);
 #define QL_LAUNCH_AQ(NIT) \
-    hipLaunchKernelGGL((act_quant_kernel<NIT, RPB>), grid, block, 0, st, x, ldx, M, K, per_wave, xq_rm, xq_kl, sx)
+    hipLaunchKernelGGL((act_quant_kernel<NIT, RPB, SM>), grid, block, 0, st, x, ldx, M, K, per_wave, inv_smooth, xq_rm, \
+                       xq_kl, sx)
     if (per_wave <= 1) QL_LAUNCH_AQ(1);
     else if (per_wave <= 2) QL_LAUNCH_AQ(2);
     else if (per_wave <= 4) QL_LAUNCH_AQ(4);
@@ -130,9 +162,18 @@ int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, 
                      float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
-    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
-    else launch_aq<8>(x, ldx, M, K, xq_rm, xq_kl, sx, st);
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, false>(x, ldx, M, K, nullptr, xq_rm, xq_kl, sx, st);
+    else launch_aq<8, false>(x, ldx, M, K, nullptr, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant launch");
+}
+
+int launch_act_quant_smooth(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, int8_t *xq_rm,
+                            int8_t *xq_kl, float *sx, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, true>(x, ldx, M, K, inv_smooth, xq_rm, xq_kl, sx, st);
+    else launch_aq<8, true>(x, ldx, M, K, inv_smooth, xq_rm, xq_kl, sx, st);
+    return check_hip(hipGetLastError(), "act_quant (smooth) launch");
 }
 
 int launch_act_repack(const int8_t *xq_rm, int M, int K, int8_t *xq_kl, hipStream_t st)

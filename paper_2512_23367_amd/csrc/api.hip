@@ -330,7 +330,7 @@ int ql_quant_act_per_token_transformed(const void *x, int64_t ldx, int M, int K,
                                        void *stream)
 {
     QL_TRY(check_mk(M, K));
-    QL_TRY(check_transform(K, hadamard_block));
+    if (hadamard_block != 0) QL_TRY(check_transform(K, hadamard_block));
     if (M == 0) return QL_OK;
     if (!x || !sx || (!xq_rowmajor && !xq_kernel)) return fail(QL_ERR_NULL, "a required pointer is NULL");
     if (!aligned(x, 16) || ldx < K || ldx % 8)
@@ -338,8 +338,13 @@ int ql_quant_act_per_token_transformed(const void *x, int64_t ldx, int M, int K,
     if ((xq_rowmajor && !aligned(xq_rowmajor, 16)) || (xq_kernel && !aligned(xq_kernel, 256)) || !aligned(sx, 4) ||
         (inv_smooth && !aligned(inv_smooth, 16)))
         return fail(QL_ERR_ALIGN, "xq_rowmajor/inv_smooth need 16-byte, xq_kernel 256-byte alignment");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hadamard_block == 0) {   // per-channel multiply only: the ordinary quantizer's layouts and any K
+        if (!inv_smooth) return launch_act_quant(static_cast<const __half *>(x), ldx, M, K, xq_rowmajor, xq_kernel, sx, st);
+        return launch_act_quant_smooth(static_cast<const __half *>(x), ldx, M, K, inv_smooth, xq_rowmajor, xq_kernel, sx, st);
+    }
     return launch_act_quant_transform(static_cast<const __half *>(x), ldx, M, K, inv_smooth, hadamard_block, xq_rowmajor,
-                                      xq_kernel, sx, static_cast<hipStream_t>(stream));
+                                      xq_kernel, sx, st);
 }
 
 int ql_quant_weight_transformed(const void *w, int N, int K, int bits, int group, const float *smooth,
