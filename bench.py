@@ -379,6 +379,24 @@ def main():
                     log("[detail]", json.dumps(row))
                 del base, l
                 torch.cuda.empty_cache()
+        # the activation quantizer alone and with the paper's two operand transforms fused in front of it
+        # (SmoothQuant per-channel multiply, block Hadamard rotation), graph-replayed; 3 B per element
+        for M, K in ((2048, 1536), (4096, 4096), (4096, 11008)):
+            x = torch.randn((M, K), dtype=torch.float16, device="cuda:0")
+            kl = torch.empty(ql.ql_act_kernel_bytes(M, K), dtype=torch.uint8, device="cuda:0")
+            sxv = torch.empty(M, dtype=torch.float32, device="cuda:0")
+            inv = torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5
+            B = ql.ql_hadamard_block(K)
+            row = {"shape": f"act_quant.M{M}.K{K}", "hadamard_block": B}
+            for name, fn in (("plain", lambda i: ql.ql_quant_act_per_token(x, None, kl, sxv)),
+                             ("smoothquant", lambda i: ql.ql_quant_act_per_token_transformed(x, inv, 0, None, kl, sxv)),
+                             ("hadamard", lambda i: ql.ql_quant_act_per_token_transformed(x, None, B, None, kl, sxv))):
+                t = graph_time_ms(torch, fn, 50)
+                row[name + "_us"] = round(t * 1e3, 2)
+                row[name + "_gbs"] = round(3 * M * K / (t * 1e-3) / 1e9, 1)
+            log("[detail]", json.dumps(row))
+            detail.append(row)
+            del x, kl
         out["detail"] = detail
 
     if not args.no_cpu:

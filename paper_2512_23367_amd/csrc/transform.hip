@@ -87,74 +87,55 @@ __device__ inline void fwht_row(float (&v)[NIT][16], int hblock, float norm, flo
         for (int i = 0; i < 16; ++i) v[it][i] *= norm;
 }
 
-// One workgroup per TPB tokens, one after the other: load, transform, per-token abs-max, quantize, store
-// (row-major and/or tile order).  TPB = 8 (prefill): the codes of the 8 tokens are collected in LDS and written
-// to the tile order as whole 128-byte lines (8 token slots x 16 bytes), which is what makes the plain quantizer
-// fast at large M; TPB = 1 writes 16-byte pieces directly.
-template <int NIT, int TPB>
-__global__ __launch_bounds__(TW) void act_quant_transform_kernel(const __half *__restrict__ x, int64_t ldx, int M, int K,
+// One workgroup per token: load, transform, per-token abs-max, quantize, store (row-major and/or tile order).
+// (Collecting 8 tokens per workgroup for whole-line writes of the tile order, as the plain quantizer does at
+// large M, was measured and is slower here: a workgroup transforms its tokens one after the other, and that
+// serial latency costs more than the 16-byte writes save -- 37 us against 27 us for 4096 x 4096.)
+template <int NIT>
+__global__ __launch_bounds__(TW) void act_quant_transform_kernel(const __half *__restrict__ x, int64_t ldx, int K,
                                                                  const float *__restrict__ inv_smooth, int hblock,
                                                                  float norm, int8_t *__restrict__ xq_rm,
                                                                  int8_t *__restrict__ xq_kl, float *__restrict__ sx)
 {
     __shared__ float xchg[16 * TW];
-    __shared__ float red[2][TW / 64];
-    extern __shared__ __attribute__((aligned(16))) char stage[];   // TPB = 8: [8][K] codes
-    const int tid = threadIdx.x;
+    __shared__ float red[TW / 64];
+    const int m = blockIdx.x, tid = threadIdx.x;
     const int nchunks = K / 16;
-    for (int t = 0; t < TPB; ++t) {
-        const int m = blockIdx.x * TPB + t;
-        if (m >= M) break;                               // uniform
-        const __half *row = x + (size_t)m * ldx;
-        float v[NIT][16];
+    const __half *row = x + (size_t)m * ldx;
+    float v[NIT][16];
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int c = it * TW + tid;
-            if (c < nchunks) {
-                load_chunk(row, c, v[it]);
-                if (inv_smooth) scale_chunk(inv_smooth, c, v[it]);
-            } else {
+    for (int it = 0; it < NIT; ++it) {
+        const int c = it * TW + tid;
+        if (c < nchunks) {
+            load_chunk(row, c, v[it]);
+            if (inv_smooth) scale_chunk(inv_smooth, c, v[it]);
+        } else {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) v[it][i] = 0.0f;
-            }
-        }
-        if (hblock > 1) fwht_row<NIT>(v, hblock, norm, xchg);
-
-        float amax = 0.0f;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[it][i]));
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
-        if ((tid & 63) == 0) red[t & 1][tid >> 6] = amax;   // two buffers: one barrier per token is enough
-        __syncthreads();
-        amax = fmaxf(fmaxf(red[t & 1][0], red[t & 1][1]), fmaxf(red[t & 1][2], red[t & 1][3]));
-        float scale, inv;
-        token_scales_f32(amax, scale, inv);
-        if (tid == 0) sx[m] = scale;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int c = it * TW + tid;
-            if (c < nchunks) {
-                const uint4 q = quant_chunk_f32(v[it], inv);
-                if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * 16) = q;
-                if (xq_kl) {
-                    if (TPB == 1) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * 16, K)) = q;
-                    else *reinterpret_cast<uint4 *>(stage + ((size_t)t * nchunks + c) * 16) = q;
-                }
-            }
+            for (int i = 0; i < 16; ++i) v[it][i] = 0.0f;
         }
     }
-    if (TPB > 1 && xq_kl) {
-        __syncthreads();
-        // thread j: token j % 8, chunk j / 8 -> 8 consecutive threads fill one 128-byte line of the tile order
-        for (int j = tid; j < nchunks * TPB; j += TW) {
-            const int t = j % TPB, c = j / TPB;
-            const int m = blockIdx.x * TPB + t;
-            if (m < M)
-                *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * 16, K)) =
-                    *reinterpret_cast<const uint4 *>(stage + ((size_t)t * nchunks + c) * 16);
+    if (hblock > 1) fwht_row<NIT>(v, hblock, norm, xchg);
+
+    float amax = 0.0f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) amax = fmaxf(amax, fabsf(v[it][i]));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off, 64));
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float scale, inv;
+    token_scales_f32(amax, scale, inv);
+    if (tid == 0) sx[m] = scale;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int c = it * TW + tid;
+        if (c < nchunks) {
+            const uint4 q = quant_chunk_f32(v[it], inv);
+            if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * 16) = q;
+            if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * 16, K)) = q;
         }
     }
 }
@@ -237,32 +218,15 @@ int launch_act_quant_transform(const __half *x, int64_t ldx, int M, int K, const
     if (M == 0) return QL_OK;
     const int nit = ceil_div(K / 16, TW);
     const float norm = block_norm(hblock > 1 ? hblock : 1);
-    // Collecting 8 tokens per workgroup (whole-line writes) was measured and is slower here: the tokens of a
-    // workgroup are transformed one after the other, and that serial latency costs more than the 16-byte
-    // writes of the one-token workgroups (4096 x 4096: 37 us against 27 us).
-    const bool grouped = false;
-    auto launch = [&](auto kern, int tpb, bool &attr_set) -> int {
-        const size_t lds = tpb > 1 ? (size_t)tpb * K : 0;
-        if (tpb > 1 && !attr_set) {   // 8 tokens x K <= 16384 bytes of codes next to the 16 KB exchange buffer
-            QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 8 * 16384),
-                             "hipFuncSetAttribute(max dynamic LDS)"));
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(kern, dim3(ceil_div(M, tpb)), dim3(TW), lds, st, x, ldx, M, K, inv_smooth, hblock, norm, xq_rm,
-                           xq_kl, sx);
-        return check_hip(hipGetLastError(), "act_quant_transform launch");
-    };
-    static bool attr[MAX_NIT + 1] = {};
-    bool none = true;
-#define QL_LAUNCH(NIT)                                                                      \
-    return grouped ? launch(act_quant_transform_kernel<NIT, 8>, 8, attr[NIT]) \
-                   : launch(act_quant_transform_kernel<NIT, 1>, 1, none)
+#define QL_LAUNCH(NIT)                                                                                              \
+    hipLaunchKernelGGL((act_quant_transform_kernel<NIT>), dim3(M), dim3(TW), 0, st, x, ldx, K, inv_smooth, hblock, \
+                       norm, xq_rm, xq_kl, sx)
     if (nit == 1) QL_LAUNCH(1);
     else if (nit == 2) QL_LAUNCH(2);
     else if (nit == 3) QL_LAUNCH(3);
     else QL_LAUNCH(4);
 #undef QL_LAUNCH
+    return check_hip(hipGetLastError(), "act_quant_transform launch");
 }
 
 int launch_weight_transform(const __half *w, int N, int K, const float *smooth, int hblock, float *out, hipStream_t st)
