@@ -19,8 +19,7 @@
 namespace ql {
 namespace {
 
-constexpr int TW = 256;                 // threads per workgroup (one token / one weight row)
-constexpr int MAX_NIT = 4;              // chunks per thread: K <= 16384
+constexpr int TW = 256;                 // threads per workgroup (one token / one weight row); at most 4 chunks of 16 per thread: K <= 16384
 
 __device__ inline void load_chunk(const __half *row, int c, float (&v)[16])
 {
