@@ -379,6 +379,33 @@ def main():
                     log("[detail]", json.dumps(row))
                 del base, l
                 torch.cuda.empty_cache()
+        # context for the paper's Table 3 (INT8 against FP16 prefill latency, weight memory): the same linears
+        # as FP16 GEMMs of the vendor library (torch.matmul -> hipBLASLt/rocBLAS), a comparison system, not
+        # part of this library; W8A8 / W4A8 = quantize + GEMM + epilogue through ql_*_linear
+        for c, bits_list in ((1, (8,)), (2, (8, 4))):
+            tot = {"fp16": 0.0, "w8a8": 0.0, "w4a8": 0.0}
+            mem = {"fp16": 0, "w8a8": 0, "w4a8": 0}
+            for sh in [s_ for s_ in synth.workload(c) if s_.M > 32]:
+                xh = torch.randn((sh.M, sh.K), dtype=torch.float16, device="cuda:0")
+                wh = torch.randn((sh.N, sh.K), dtype=torch.float16, device="cuda:0") * 0.02
+                tot["fp16"] += best_time_ms(torch, lambda i: torch.matmul(xh, wh.t()), 20, warm=5, rounds=3)
+                mem["fp16"] += sh.N * sh.K * 2
+                del xh, wh
+                for b in bits_list + ((4,) if c == 1 else ()):
+                    l = Layer(synth.Shape(sh.config, sh.layer, sh.M, sh.K, sh.N, b, 0 if b == 8 else 128, sh.bias),
+                              torch, ql, synth)
+                    key = "w8a8" if b == 8 else "w4a8"
+                    tot[key] += best_time_ms(torch, l.linear, 20, warm=5, rounds=3)
+                    mem[key] += l.weight_bytes + (sh.N * 4 if b == 8 else 0)
+                    del l
+                torch.cuda.empty_cache()
+            row = {"shape": f"layer.c{c}.prefill", "fp16_library_gemm_us": round(tot["fp16"] * 1e3, 1),
+                   "w8a8_linear_us": round(tot["w8a8"] * 1e3, 1), "w4a8_linear_us": round(tot["w4a8"] * 1e3, 1),
+                   "w8a8_speedup_over_fp16": round(tot["fp16"] / tot["w8a8"], 2),
+                   "w4a8_speedup_over_fp16": round(tot["fp16"] / tot["w4a8"], 2),
+                   "weight_mb": {k: round(v / 1e6, 1) for k, v in mem.items()}}
+            log("[detail]", json.dumps(row))
+            detail.append(row)
         # the activation quantizer alone and with the paper's two operand transforms fused in front of it
         # (SmoothQuant per-channel multiply, block Hadamard rotation), graph-replayed; 3 B per element
         for M, K in ((2048, 1536), (4096, 4096), (4096, 11008)):
