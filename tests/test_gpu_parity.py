@@ -147,6 +147,28 @@ def test_decode_variants_bit_exact_and_within_tolerance(G, variant, bits, M, K, 
     assert G.norm_err(G.gpu_linear(x, g, b), ref["y64"]) <= TOL
 
 
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M", [2, 40])
+def test_largest_k_decode_and_prefill(G, bits, M):
+    """K = 131072, the largest the interface accepts (no int32 accumulator can overflow below 133144)."""
+    K, N = 131072, 40
+    rng = np.random.default_rng(K + M + bits)
+    xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    xq[0] = 127                                            # one token at the extreme
+    w = synth.weights(N, K, 0, "single")
+    w[1] = np.abs(w[1]).max()                              # one channel whose codes are all +127 / +7
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
+    if bits == 8:
+        acc, _ = G.gpu_acc(xq, g)
+        ref = oracle.igemm(xq, g["canon"])
+        assert int(ref[0, 1]) == 127 * 127 * K             # the largest accumulator value there is
+        assert (acc == ref).all()
+    else:
+        _, total, _ = oracle.igemm_grouped(xq, oracle.unpack_int4(g["canon"]), g["scales"], 128)
+        acc, _ = G.gpu_acc(xq, g)
+        assert (acc == total).all()
+
+
 def test_w8a8_accumulator_extremes(G):
     K = 11008
     xq = np.full((2, K), 127, dtype=np.int8)
