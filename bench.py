@@ -72,9 +72,9 @@ class Layer:
         sh, ql = self.sh, self.ql
         k, y = self.kernels[i % len(self.kernels)], self.ys[i % len(self.ys)]
         if sh.bits == 8:
-            ql.ql_w8a8_gemm(self.xq, self.sx, sh.M, sh.K, k, self.sw, self.bias, sh.N, y)
+            ql.ql_w8a8_gemm(self.xq, self.sx, sh.M, sh.K, k, self.sw, self.bias, sh.N, y, self.ws)
         else:
-            ql.ql_w4a8_gemm(self.xq, self.sx, sh.M, sh.K, k, sh.group, self.bias, sh.N, y)
+            ql.ql_w4a8_gemm(self.xq, self.sx, sh.M, sh.K, k, sh.group, self.bias, sh.N, y, self.ws)
 
     # algorithmic bytes of one GEMM launch: int8 activations + their scales, weights (+ scales), fp16 output (+ bias)
     def gemm_bytes(self):

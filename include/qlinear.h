@@ -82,8 +82,10 @@ int ql_weight_bytes(int N, int K, int bits, int group,
 /* Bytes of the kernel-layout copy of xq for M tokens: ceil32(M) * K. */
 int ql_act_kernel_bytes(int M, int K, size_t *bytes /* host */);
 
-/* Workspace needed by ql_w8a8_linear / ql_w4a8_linear / the *_gemm calls for these sizes
- * (quantized activations in kernel layout, their scales, split-K scratch). */
+/* Workspace for ql_w8a8_linear / ql_w4a8_linear for these sizes: the quantized activations in kernel layout
+ * and their scales (required), followed by scratch for split-K partial sums (offered when the output has too
+ * few tiles to occupy the GPU: more than 32 tokens, long K; up to 64 MiB).  The *_gemm calls take scratch only:
+ * their ws may be NULL or smaller, then K is not split. */
 int ql_workspace_bytes(int M, int N, int K, int bits, size_t *bytes /* host */);
 
 /* Per-token dynamic int8 activation quantization (Eq. 1-2 with n = 8, one scale per token).

@@ -73,6 +73,17 @@ WsLayout ws_layout(int M, int K)
     return l;
 }
 
+// Split-K scratch worth offering for this shape: room for 8 partial copies of the (128-padded) output when the
+// output has too few 128x128 tiles to occupy the GPU, nothing otherwise; at most 64 MiB.  The GEMMs use what
+// they are given and fall back to unsplit kernels when it is less.
+size_t splitk_scratch(int M, int N)
+{
+    const size_t mp = round_up(M, 128), np = round_up(N, 128);
+    if (M <= DECODE_MAX_M || (mp / 128) * (np / 128) >= 192) return 0;
+    const size_t want = 8 * mp * np * 4;
+    return want < ((size_t)64 << 20) ? want : ((size_t)64 << 20);
+}
+
 int check_out(const void *y, int64_t ldy, int N)
 {
     if (!y) return fail(QL_ERR_NULL, "y is NULL");
@@ -86,7 +97,7 @@ int run_gemm(GemmArgs &a, hipStream_t st)
     if (a.M == 0) return QL_OK;
     int variant = g_variant;
     if (variant == 0 && a.M <= DECODE_MAX_M) variant = 100;
-    if (variant >= 100) {
+    if (variant >= 100 && variant < 200) {
         if (a.M > DECODE_MAX_M)
             return fail(QL_ERR_UNSUPPORTED, "decode kernels take at most %d tokens (M=%d)", DECODE_MAX_M, a.M);
         return launch_gemm_decode(a, variant, st);
@@ -106,8 +117,7 @@ int gemm_common(const int8_t *xq, const float *sx, int M, int K, const void *wq,
         (bias && !aligned(bias, 16)))
         return fail(QL_ERR_ALIGN, "xq/wq need 256-byte, sx/sw/bias 16-byte alignment");
     QL_TRY(check_out(y, ldy, N));
-    (void)ws;
-    (void)ws_bytes;
+    if (!ws || !aligned(ws, 16)) ws = nullptr, ws_bytes = 0;   // optional scratch (split-K partial sums)
     GemmArgs a = {};
     a.xq = xq;
     a.sx = sx;
@@ -147,7 +157,7 @@ int linear_common(const void *x, int64_t ldx, int M, int K, const void *wq, cons
     if (!aligned(wq, 256) || (sw && !aligned(sw, 16)) || (bias && !aligned(bias, 16)))
         return fail(QL_ERR_ALIGN, "wq needs 256-byte, sw/bias 16-byte alignment");
     QL_TRY(check_out(y, ldy, N));
-    if (M <= DECODE_MAX_M && (g_variant == 0 || g_variant >= 100) && decode_fuses_quant(M, K, g_variant)) {
+    if (M <= DECODE_MAX_M && (g_variant == 0 || (g_variant >= 100 && g_variant < 200)) && decode_fuses_quant(M, K, g_variant)) {
         // one or two tokens: the decode GEMM quantizes them itself, one launch instead of two
         GemmArgs a = {};
         a.x = static_cast<const __half *>(x);
@@ -165,7 +175,9 @@ int linear_common(const void *x, int64_t ldx, int M, int K, const void *wq, cons
         return launch_gemm_decode(a, g_variant == 0 ? 100 : g_variant, st);
     }
     QL_TRY(launch_act_quant(static_cast<const __half *>(x), ldx, M, K, nullptr, xq, sx, st));
-    return gemm_common(xq, sx, M, K, wq, sw, bits, group, bias, N, y, ldy, ws, ws_bytes, st);
+    // what lies behind the quantized activations is scratch for the GEMM (split-K partial sums)
+    return gemm_common(xq, sx, M, K, wq, sw, bits, group, bias, N, y, ldy, static_cast<char *>(ws) + l.total,
+                       ws_bytes - l.total, st);
 }
 
 }  // namespace
@@ -182,7 +194,9 @@ const char *ql_last_error(void) { return g_err; }
 
 int ql_set_kernel_variant(int variant)
 {
-    if (variant < 0 || (variant > 19 && variant < 100) || (variant > 104 && variant != 111 && variant != 121 && variant != 130))
+    if (variant < 0 || (variant > 19 && variant < 100) ||
+        (variant > 104 && variant != 111 && variant != 121 && variant != 130 && !(variant >= 202 && variant <= 232) &&
+         !(variant >= 302 && variant <= 332)))
         return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);
     g_variant = variant;
     return QL_OK;
@@ -235,7 +249,7 @@ int ql_workspace_bytes(int M, int N, int K, int bits, size_t *bytes)
     QL_TRY(check_mk(M, K));
     QL_TRY(check_nk(N, K, bits));
     if (!bytes) return fail(QL_ERR_NULL, "bytes is NULL");
-    *bytes = ws_layout(M, K).total;
+    *bytes = ws_layout(M, K).total + splitk_scratch(M, N);
     return QL_OK;
 }
 
@@ -436,8 +450,7 @@ static int acc_common(const int8_t *xq, int M, int K, const void *wq, int bits, 
     a.K = K;
     a.bits = bits;
     a.group = group;
-    a.ws = ws;
-    a.ws_bytes = ws_bytes;
+    if (ws && aligned(ws, 16)) a.ws = ws, a.ws_bytes = ws_bytes;
     return run_gemm(a, st);
 }
 

@@ -32,7 +32,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 
-enum { EPI_F16 = 0, EPI_ACC = 1 };
+enum { EPI_F16 = 0, EPI_ACC = 1, EPI_PART = 2 };   // EPI_PART: split-K, raw partial sums to the workspace
 
 struct PrefillParams {
     const int8_t *xq;
@@ -49,6 +49,8 @@ struct PrefillParams {
     int M, N, K, Npad;
     int tiles_m, tiles_n;
     unsigned x_bytes, w_bytes;
+    void *part;              // split-K: partial sums [split][workgroup][wavefront][block][quad][64 lanes x 16 B]
+    int stages_per_split;    // split-K: blockIdx.y takes stages [y * stages_per_split, ...); otherwise all of them
 };
 
 #define LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
@@ -135,7 +137,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     }   // made visible by the barriers of the main loop / the one in front of the epilogue
 
     const int KB = p.K / 32;                             // k-blocks
-    const int nstages = KB / KBS;
+    // split-K: this workgroup multiplies stages [stage0, stage0 + nstages) only (never an empty range)
+    const int stage0 = blockIdx.y * p.stages_per_split;
+    const int nstages = min(p.stages_per_split, KB / KBS - stage0);
     const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, p.x_bytes);
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.w_bytes);
     const __amdgpu_buffer_rsrc_t sr = make_rsrc(p.wscales, W4 ? (unsigned)(p.K / 128) * p.Npad * 2u : 0u);
@@ -152,13 +156,13 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
             const bool is_x = (XFR % NW == 0) ? (i < XFR / NW) : (f < XFR);
             if (is_x) {
                 const int mb = f / KBS, kb = f % KBS;
-                unsigned off = ((unsigned)(tm * TMB + mb) * KB + s * KBS + kb) * 1024u;
+                unsigned off = ((unsigned)(tm * TMB + mb) * KB + (stage0 + s) * KBS + kb) * 1024u;
                 if (!live) off = 0xFFFFF000u;            // beyond the buffer: the load returns nothing
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(buf + f * 1024), 16, voff, off, 0, 0);
             } else {
                 const int g = f - XFR;
                 const int nb = g / WKB, kb = g % WKB;
-                unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + s * WKB + kb) * 1024u;
+                unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + (stage0 + s) * WKB + kb) * 1024u;
                 if (!live) off = 0xFFFFF000u;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + f * 1024), 16, voff, off, 0, 0);
             }
@@ -167,7 +171,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
         for (int i = 0; i < FR / NW; ++i) load_fragment(i);
         if (NHI != 0 && wave < NHI) load_fragment(FR / NW);
         if (SCALE_DMA) {   // stage s = scale group s: 4 bytes per lane, the first WN*16 lanes carry the wavefront's channels
-            unsigned off = ((unsigned)s * p.Npad + (tn * TNB + wn * WN) * 32) * 2u;
+            unsigned off = ((unsigned)(stage0 + s) * p.Npad + (tn * TNB + wn * WN) * 32) * 2u;
             if (!live) off = 0xFFFFF000u;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(sr, LDS_PTR(scale_slots + ((s % STAGES) * NW + wave) * 256), 4,
                                                      lane * 4, off, 0, 0);
@@ -328,7 +332,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                 for (int j = 0; j < WM; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        if (EPI == EPI_F16) {
+                        if (EPI != EPI_ACC) {
                             accf[i][j][r] = __builtin_fmaf((float)acc[i][j][r], (float)sg[i][r / 4][r % 4], accf[i][j][r]);
                         } else {
                             tot[i][j][r] += acc[i][j][r];
@@ -444,6 +448,24 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     auto my_block = [&](int j) { return WK == 1 || j / (HB > 0 ? HB : 1) == wk; };   // token blocks this wavefront finishes
 
     // ---------------------------------------------------------------- epilogue
+    if constexpr (EPI == EPI_PART) {   // split-K: the wavefront's registers as they are, 1 KiB per store instruction
+        static_assert(WK == 1, "split-K across workgroups and inside one are not combined");
+        char *dst = static_cast<char *>(p.part) +
+                    (((size_t)blockIdx.y * gridDim.x + blockIdx.x) * NW + wave) * (size_t)(WN * WM * 4096);
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int j = 0; j < WM; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v4i v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = W4 ? __float_as_int(accf[i][j][4 * q + e]) : acc[i][j][4 * q + e];
+                    *reinterpret_cast<v4i *>(dst + ((i * WM + j) * 4 + q) * 1024 + lane * 16) = v;
+                }
+        return;
+    }
     if (EPI == EPI_ACC) {   // test hook: raw integer accumulators, element by element
 #pragma unroll
         for (int j = 0; j < WM; ++j) {
@@ -521,10 +543,73 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     }
 }
 
+// Split-K, second kernel: adds the partial sums of the splits in a fixed order (int32: exact; int4 path: fp32,
+// split 0 first), then the same dequantization as the fused epilogue.  One lane per 4 consecutive channels of
+// one token, in the order the first kernel stored them.
+struct FinishParams {
+    const void *part;
+    const float *sx;
+    const float *sw;
+    const __half *bias;
+    __half *y;
+    int64_t ldy;
+    int32_t *acc;            // test hook (int8 weights): raw sums instead of y
+    int M, N;
+    int tiles_m, tiles_n, splits;
+    int waves_m, waves_n, wm, wn;
+    int w4;
+};
+
+__global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
+{
+    const int nw = f.waves_m * f.waves_n, blocks = f.wn * f.wm, ntiles = f.tiles_m * f.tiles_n;
+    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = (int)(t % 64);
+    size_t u = t / 64;
+    const int q = (int)(u % 4);
+    u /= 4;
+    const int j = (int)(u % f.wm);
+    u /= f.wm;
+    const int i = (int)(u % f.wn);
+    u /= f.wn;
+    const int wave = (int)(u % nw);
+    const size_t tile = u / nw;
+    if (tile >= (size_t)ntiles) return;
+    int tm, tn;
+    tile_coords((int)tile, f.tiles_m, f.tiles_n, tm, tn);
+    const int wm = wave % f.waves_m, wn = wave / f.waves_m;
+    const int m = ((tm * f.waves_m + wm) * f.wm + j) * 32 + (lane & 31);
+    const int n0 = ((tn * f.waves_n + wn) * f.wn + i) * 32 + 8 * q + 4 * (lane >> 5);
+    if (m >= f.M || n0 >= f.N) return;
+    const char *src = static_cast<const char *>(f.part) + ((tile * nw + wave) * blocks + (i * f.wm + j)) * 4096 + q * 1024 +
+                      lane * 16;
+    const size_t split_stride = (size_t)ntiles * nw * blocks * 4096;
+    int si[4] = {0, 0, 0, 0};
+    float sf[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < f.splits; ++s) {
+        const v4i v = *reinterpret_cast<const v4i *>(src + (size_t)s * split_stride);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (f.w4) sf[e] += __int_as_float(v[e]);
+            else si[e] += v[e];
+        }
+    }
+    if (f.acc) {
+        for (int e = 0; e < 4 && n0 + e < f.N; ++e) f.acc[(size_t)m * f.N + n0 + e] = si[e];
+        return;
+    }
+    const float sxm = f.sx[m] * (f.w4 ? 0.0625f : 1.0f);
+    for (int e = 0; e < 4 && n0 + e < f.N; ++e) {
+        const float b = f.bias ? __half2float(f.bias[n0 + e]) : 0.0f;
+        const float v = f.w4 ? __builtin_fmaf(sf[e], sxm, b) : __builtin_fmaf((float)si[e] * sxm, f.sw[n0 + e], b);
+        f.y[(size_t)m * f.ldy + n0 + e] = __float2half_rn(v);
+    }
+}
+
 // OCC: wavefronts per SIMD the register allocation must leave room for (workgroups per CU x waves / 4)
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false,
           int WK = 1>
-int launch_one(const GemmArgs &a, hipStream_t st)
+int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
 {
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
     constexpr int XFR = WAVES_M * WM * KBS;
@@ -564,38 +649,120 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     p.wscales = W4 ? reinterpret_cast<const __half *>(static_cast<const char *>(a.wq) + w4_scales_offset(a.N, a.K))
                    : nullptr;
     const int grid = p.tiles_m * p.tiles_n;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * WK * 64), LDS, st, p);
-    return check_hip(hipGetLastError(), "gemm_prefill launch");
+    const int nstages = a.K / (32 * KBS);
+    p.stages_per_split = ceil_div(nstages, splits);
+    splits = ceil_div(nstages, p.stages_per_split);   // no empty split
+    p.part = a.ws;
+    hipLaunchKernelGGL(kern, dim3(grid, splits), dim3(WAVES_M * WAVES_N * WK * 64), LDS, st, p);
+    QL_TRY(check_hip(hipGetLastError(), "gemm_prefill launch"));
+    if (EPI != EPI_PART) return QL_OK;
+    FinishParams f;
+    f.part = a.ws;
+    f.sx = a.sx;
+    f.sw = a.sw;
+    f.bias = a.bias;
+    f.y = a.y;
+    f.ldy = a.ldy;
+    f.acc = a.acc;
+    f.M = a.M;
+    f.N = a.N;
+    f.tiles_m = p.tiles_m;
+    f.tiles_n = p.tiles_n;
+    f.splits = splits;
+    f.waves_m = WAVES_M;
+    f.waves_n = WAVES_N;
+    f.wm = WM;
+    f.wn = WN;
+    f.w4 = W4;
+    const size_t lanes = (size_t)grid * WAVES_M * WAVES_N * WN * WM * 4 * 64;
+    hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, st, f);
+    return check_hip(hipGetLastError(), "splitk_finish launch");
+}
+
+// Split-K plan for shapes whose tiles leave most CUs idle: bytes of partial sums per split and the number of
+// splits that minimises  rounds x tile time + partial-sum traffic + second launch  (times in us; rates measured).
+struct SplitPlan {
+    int splits;
+    double us;
+};
+
+inline SplitPlan plan_split(long tiles, int TM, int TN, int K, int stage_k, double tops_per_cu, size_t ws_bytes)
+{
+    SplitPlan best = {1, 4.0 + (double)((tiles + 255) / 256) * (2.0 * TM * TN * K) / (tops_per_cu * 1e6)};
+    const int nstages = K / stage_k;
+    for (int s = 2; s <= 32; ++s) {
+        if (nstages / s < 4) break;
+        const size_t bytes = (size_t)s * tiles * TM * TN * 4;
+        if (bytes > ws_bytes) break;
+        const double kk = (double)((nstages + s - 1) / s) * stage_k;
+        const double us = 4.0 + (double)((tiles * s + 255) / 256) * (2.0 * TM * TN * kk) / (tops_per_cu * 1e6) + 3.0 +
+                          2.0 * bytes / 4.0e6;
+        if (us < best.us * 0.9) best = {s, us};
+    }
+    return best;
 }
 
 // variant 0 = automatic choice; 1..5 pick one tile configuration (tests and tuning)
 template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
 {
+    // split-K scratch: whatever the caller's workspace offers behind the quantized activations
+    const size_t scratch = a.ws ? a.ws_bytes : 0;
+    const bool dump_partials = a.partials != nullptr;
     if (W4) {
         // 128 tokens x 256 channels (equal bytes of both operands per stage), 8 wavefronts of 64x64 in two
         // ping-pong groups, 4 stages of one 128-k scale group each
+        const long tiles = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
+        int splits = 1;
+        if (variant >= 202 && variant <= 232) splits = variant - 200;
+        else if (variant == 0 && tiles < 192) splits = plan_split(tiles, 128, 256, a.K, 128, 7.0, scratch).splits;
+        if (splits > 1 && EPI == EPI_F16 && !dump_partials) {
+            if ((size_t)splits * tiles * 128 * 256 * 4 > scratch)
+                return fail(QL_ERR_WORKSPACE, "split-K needs %zu bytes of workspace", (size_t)splits * tiles * 128 * 256 * 4);
+            return launch_one<2, 4, 2, 2, 4, 4, true, EPI_PART, 1, true>(a, st, splits);
+        }
         return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
     }
+    int splits = 1;
     if (variant == 0) {
-        // Relative time of a tile shape = rounds over the 256 CUs x tile area / rate of a busy CU (measured:
-        // the big ping-pong tiles sustain ~10.2 TOPS per CU, three resident 128x128 workgroups ~9.2 together,
-        // a lone 128x128 workgroup 8.7, or 10 with the k-split ping-pong once K is long enough to amortise its
-        // exchange).  256x256 wins ties: fewer rounds, fewer pipeline fills and epilogues.
+        // Estimated time of a tile shape = 4 us (launch, pipeline fill, epilogue) + rounds over the 256 CUs x tile
+        // operations / rate of a busy CU (measured: the big ping-pong tiles sustain ~10.2 TOPS per CU, three
+        // resident 128x128 workgroups ~9.2 together, a lone 128x128 workgroup 8.7, or 10 with the k-split
+        // ping-pong once K is long enough to amortise its exchange).  256x256 wins ties: fewer rounds, fewer
+        // pipeline fills and epilogues.  When even the best shape leaves most CUs idle (few tokens, long K), K is
+        // split over several workgroups per tile and a second kernel adds their partial sums (plan_split).
         auto rounds = [](long tiles, long slots) { return (tiles + slots - 1) / slots; };
+        auto us_of = [&](double area_over_rate) { return 4.0 + area_over_rate * 2.0 * a.K / 1e6; };
         const long m256 = ceil_div(a.M, 256), m128 = ceil_div(a.M, 128);
         const long t256 = m256 * ceil_div(a.N, 256), t192 = m256 * ceil_div(a.N, 192), t128 = m128 * ceil_div(a.N, 128);
-        double best = rounds(t256, 256) * (256.0 * 256.0) / 10.2;
+        double best = us_of(rounds(t256, 256) * (256.0 * 256.0) / 10.2);
         variant = 6;
-        const double c192 = rounds(t192, 256) * (256.0 * 192.0) / 10.2;
+        const double c192 = us_of(rounds(t192, 256) * (256.0 * 192.0) / 10.2);
         if (c192 < best * 0.97) best = c192, variant = 15;
         int v128;
         double c128;
-        if (t128 > 512) v128 = 11, c128 = rounds(t128, 768) * 3 * (128.0 * 128.0) / 9.2;
-        else if (t128 > 256) v128 = 4, c128 = 2 * (128.0 * 128.0) / 9.0;
-        else if (a.K % 128 == 0 && a.K >= 3072) v128 = 19, c128 = (128.0 * 128.0) / 10.0;
-        else v128 = 13, c128 = (128.0 * 128.0) / 8.7;
-        if (c128 < best * 0.97) variant = v128;
+        if (t128 > 512) v128 = 11, c128 = us_of(rounds(t128, 768) * 3 * (128.0 * 128.0) / 9.2);
+        else if (t128 > 256) v128 = 4, c128 = us_of(2 * (128.0 * 128.0) / 9.0);
+        else if (a.K % 128 == 0 && a.K >= 3072) v128 = 19, c128 = us_of((128.0 * 128.0) / 10.0);
+        else v128 = 13, c128 = us_of((128.0 * 128.0) / 8.7);
+        if (c128 < best * 0.97) best = c128, variant = v128;
+        if (scratch && !dump_partials) {
+            const SplitPlan pa = plan_split(t128, 128, 128, a.K, 64, 8.7, scratch);
+            const SplitPlan pb = plan_split(t256, 256, 256, a.K, 64, 10.2, scratch);
+            if (pa.splits > 1 && pa.us < best * 0.9) best = pa.us, variant = 200, splits = pa.splits;
+            if (pb.splits > 1 && pb.us < best * 0.9) best = pb.us, variant = 300, splits = pb.splits;
+        }
+    } else if (variant >= 202 && variant <= 232) {
+        splits = variant - 200, variant = 200;
+    } else if (variant >= 302 && variant <= 332) {
+        splits = variant - 300, variant = 300;
+    }
+    if (variant == 200 || variant == 300) {   // split-K: 128x128 tiles of 8 wavefronts, or 256x256 ping-pong tiles
+        const int T = variant == 200 ? 128 : 256;
+        const size_t need = (size_t)splits * ceil_div(a.M, T) * ceil_div(a.N, T) * T * T * 4;
+        if (need > scratch) return fail(QL_ERR_WORKSPACE, "split-K needs %zu bytes of workspace", need);
+        if (variant == 200) return launch_one<4, 2, 1, 2, 2, 4, false, EPI_PART>(a, st, splits);
+        return launch_one<2, 4, 4, 2, 2, 4, false, EPI_PART, 1, true>(a, st, splits);
     }
     if ((variant == 5 || variant == 12) && a.K % 128) variant = variant == 5 ? 1 : 4;
     if (variant == 19 && a.K % 128) variant = 13;   // 128-k stages need K % 128 == 0

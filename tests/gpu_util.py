@@ -70,7 +70,7 @@ def repack_act(xq: np.ndarray) -> torch.Tensor:
     return xk
 
 
-def gpu_acc(xq: np.ndarray, wq, want_partials=False):
+def gpu_acc(xq: np.ndarray, wq, want_partials=False, ws=None):
     """Raw integer accumulators of the GEMM main loop for host codes xq and a gpu_quant_weight dict."""
     M, K = xq.shape
     N = wq["N"]
@@ -78,7 +78,7 @@ def gpu_acc(xq: np.ndarray, wq, want_partials=False):
     acc = torch.full((M, N), -12345, dtype=torch.int32, device=DEV)
     part = None
     if wq["bits"] == 8:
-        ql.ql_w8a8_gemm_acc_i32(xk, M, K, wq["kernel"], N, acc)
+        ql.ql_w8a8_gemm_acc_i32(xk, M, K, wq["kernel"], N, acc, ws)
     else:
         G = K // wq["group"]
         part = torch.full((M, G, N), -12345, dtype=torch.int32, device=DEV) if want_partials else None
@@ -87,7 +87,7 @@ def gpu_acc(xq: np.ndarray, wq, want_partials=False):
     return acc.cpu().numpy(), (part.cpu().numpy() if part is not None else None)
 
 
-def gpu_linear(x16: np.ndarray, wq, bias16=None, ldy=None, ldx=None) -> np.ndarray:
+def gpu_linear(x16: np.ndarray, wq, bias16=None, ldy=None, ldx=None, extra_ws=0) -> np.ndarray:
     M, K = x16.shape
     N = wq["N"]
     if ldx is None:
@@ -99,7 +99,7 @@ def gpu_linear(x16: np.ndarray, wq, bias16=None, ldy=None, ldx=None) -> np.ndarr
     ld = ldy or ((N + 7) // 8 * 8)
     ybuf = torch.full((M, ld), float("nan"), dtype=torch.float16, device=DEV)
     y = ybuf[:, :N]
-    ws = empty_bytes(ql.ql_workspace_bytes(M, N, K, wq["bits"]))
+    ws = empty_bytes(ql.ql_workspace_bytes(M, N, K, wq["bits"]) + extra_ws)
     b = dev(bias16) if bias16 is not None else None
     if wq["bits"] == 8:
         ql.ql_w8a8_linear(xd, wq["kernel"], wq["scales_dev"].view(torch.float32), b, N, y, ws)

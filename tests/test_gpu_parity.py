@@ -169,6 +169,52 @@ def test_largest_k_decode_and_prefill(G, bits, M):
         assert (acc == total).all()
 
 
+# ------------------------------------------------------------------ split-K (few tokens, long K)
+@pytest.mark.parametrize("variant", [202, 203, 208, 302, 305])
+@pytest.mark.parametrize("M,K,N", [(64, 4096, 200), (100, 1536, 264), (300, 2048, 520), (33, 11008, 48)])
+def test_w8a8_split_k_accumulators_bit_exact(G, variant, M, K, N):
+    """K split over several workgroups per tile + second kernel adding the int32 partial sums: still exact."""
+    splits, T = variant % 100, 128 if variant < 300 else 256
+    if K // 64 // splits < 1:
+        pytest.skip("more splits than 64-k stages")
+    rng = np.random.default_rng(M + K + N)
+    xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
+    g = G.gpu_quant_weight(synth.weights(N, K, 0, "single"), 8, 0)
+    ws = G.empty_bytes(splits * -(-M // T) * -(-N // T) * T * T * 4)
+    ql.ql_set_kernel_variant(variant)
+    acc, _ = G.gpu_acc(xq, g, ws=ws)
+    assert (acc == oracle.igemm(xq, g["canon"])).all()
+    with pytest.raises(ql.QlError):                        # the same call without the scratch it needs
+        G.gpu_acc(xq, g)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N,variant", [(64, 4096, 200, 204), (100, 1536, 264, 203), (200, 11008, 136, 0),
+                                           (48, 4096, 520, 0), (300, 2048, 520, 302)])
+def test_split_k_linear_within_tolerance_and_deterministic(G, bits, M, K, N, variant):
+    x = synth.activations(M, K, 0, "single")
+    w = synth.weights(N, K, 0, "single")
+    b = synth.bias(N, 0, "single")
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
+    ref = (oracle.linear_w8a8(x, g["canon"], g["scales"], b) if bits == 8
+           else oracle.linear_w4a8(x, g["canon"], g["scales"], 128, b))
+    if bits == 4 and variant >= 300:
+        variant = 203                                      # the int4 kernel has one tile shape
+    ql.ql_set_kernel_variant(variant)
+    y1 = G.gpu_linear(x, g, b, extra_ws=64 << 20)
+    y2 = G.gpu_linear(x, g, b, extra_ws=64 << 20)
+    assert np.isfinite(y1).all()
+    assert G.norm_err(y1, ref["y64"]) <= TOL
+    assert (y1.view(np.uint16) == y2.view(np.uint16)).all()
+    # and the unsplit kernels agree to rounding (int8: same integer sums, so the same fp16 values)
+    ql.ql_set_kernel_variant(13 if bits == 8 else 1)
+    y0 = G.gpu_linear(x, g, b)
+    if bits == 8:
+        assert (y1.view(np.uint16) == y0.view(np.uint16)).all()
+    else:
+        assert G.norm_err(y1, y0.astype(np.float64)) <= 2e-3
+
+
 def test_w8a8_accumulator_extremes(G):
     K = 11008
     xq = np.full((2, K), 127, dtype=np.int8)
