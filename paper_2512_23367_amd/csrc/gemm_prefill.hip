@@ -545,7 +545,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
 
 // Split-K, second kernel: adds the partial sums of the splits in a fixed order (int32: exact; int4 path: fp32,
 // split 0 first), then the same dequantization as the fused epilogue.  One lane per 4 consecutive channels of
-// one token, in the order the first kernel stored them.
+// one token, in the order the first kernel stored them (32-bit index arithmetic only: this kernel is short).
 struct FinishParams {
     const void *part;
     const float *sx;
@@ -556,53 +556,74 @@ struct FinishParams {
     int32_t *acc;            // test hook (int8 weights): raw sums instead of y
     int M, N;
     int tiles_m, tiles_n, splits;
-    int waves_m, waves_n, wm, wn;
-    int w4;
 };
 
+template <int WAVES_M, int WAVES_N, int WM, int WN, bool W4>
 __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
 {
-    const int nw = f.waves_m * f.waves_n, blocks = f.wn * f.wm, ntiles = f.tiles_m * f.tiles_n;
-    const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = (int)(t % 64);
-    size_t u = t / 64;
-    const int q = (int)(u % 4);
-    u /= 4;
-    const int j = (int)(u % f.wm);
-    u /= f.wm;
-    const int i = (int)(u % f.wn);
-    u /= f.wn;
-    const int wave = (int)(u % nw);
-    const size_t tile = u / nw;
-    if (tile >= (size_t)ntiles) return;
+    // one workgroup per (tile, wavefront of the first kernel): its 4 wavefronts take the 4 quads of every block.
+    // All loads of a lane are issued before the first is used (the kernel is one memory round trip long).
+    constexpr int NW = WAVES_M * WAVES_N, BLOCKS = WN * WM;
+    const int ntiles = f.tiles_m * f.tiles_n;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int tile = blockIdx.x / NW, wave = blockIdx.x % NW;
     int tm, tn;
-    tile_coords((int)tile, f.tiles_m, f.tiles_n, tm, tn);
-    const int wm = wave % f.waves_m, wn = wave / f.waves_m;
-    const int m = ((tm * f.waves_m + wm) * f.wm + j) * 32 + (lane & 31);
-    const int n0 = ((tn * f.waves_n + wn) * f.wn + i) * 32 + 8 * q + 4 * (lane >> 5);
-    if (m >= f.M || n0 >= f.N) return;
-    const char *src = static_cast<const char *>(f.part) + ((tile * nw + wave) * blocks + (i * f.wm + j)) * 4096 + q * 1024 +
-                      lane * 16;
-    const size_t split_stride = (size_t)ntiles * nw * blocks * 4096;
-    int si[4] = {0, 0, 0, 0};
-    float sf[4] = {0.f, 0.f, 0.f, 0.f};
+    tile_coords(tile, f.tiles_m, f.tiles_n, tm, tn);
+    const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+    const size_t split_stride = (size_t)ntiles * NW * BLOCKS * 4096;
+    const char *src0 = static_cast<const char *>(f.part) + (size_t)blockIdx.x * BLOCKS * 4096 + q * 1024 + lane * 16;
+    int si[BLOCKS][4];
+    float sf[BLOCKS][4];
+#pragma unroll
+    for (int b = 0; b < BLOCKS; ++b)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) si[b][e] = 0, sf[b][e] = 0.0f;
     for (int s = 0; s < f.splits; ++s) {
-        const v4i v = *reinterpret_cast<const v4i *>(src + (size_t)s * split_stride);
+        v4i v[BLOCKS];
+#pragma unroll
+        for (int b = 0; b < BLOCKS; ++b) v[b] = *reinterpret_cast<const v4i *>(src0 + (size_t)s * split_stride + b * 4096);
+#pragma unroll
+        for (int b = 0; b < BLOCKS; ++b)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (W4) sf[b][e] += __int_as_float(v[b][e]);
+                else si[b][e] += v[b][e];
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < WN; ++i) {
+        const int n0 = ((tn * WAVES_N + wn) * WN + i) * 32 + 8 * q + 4 * (lane >> 5);
+        if (n0 >= f.N) continue;
+        float sw4[4], b4[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (f.w4) sf[e] += __int_as_float(v[e]);
-            else si[e] += v[e];
+            const int n = n0 + e < f.N ? n0 + e : n0;
+            sw4[e] = (!W4 && f.sw) ? f.sw[n] : 0.0f;
+            b4[e] = f.bias ? __half2float(f.bias[n]) : 0.0f;
         }
-    }
-    if (f.acc) {
-        for (int e = 0; e < 4 && n0 + e < f.N; ++e) f.acc[(size_t)m * f.N + n0 + e] = si[e];
-        return;
-    }
-    const float sxm = f.sx[m] * (f.w4 ? 0.0625f : 1.0f);
-    for (int e = 0; e < 4 && n0 + e < f.N; ++e) {
-        const float b = f.bias ? __half2float(f.bias[n0 + e]) : 0.0f;
-        const float v = f.w4 ? __builtin_fmaf(sf[e], sxm, b) : __builtin_fmaf((float)si[e] * sxm, f.sw[n0 + e], b);
-        f.y[(size_t)m * f.ldy + n0 + e] = __float2half_rn(v);
+#pragma unroll
+        for (int j = 0; j < WM; ++j) {
+            const int m = ((tm * WAVES_M + wm) * WM + j) * 32 + (lane & 31);
+            if (m >= f.M) continue;
+            const int b = i * WM + j;
+            if (f.acc) {
+                for (int e = 0; e < 4 && n0 + e < f.N; ++e) f.acc[(size_t)m * f.N + n0 + e] = si[b][e];
+                continue;
+            }
+            const float sxm = f.sx[m] * (W4 ? 0.0625f : 1.0f);
+            h4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = W4 ? __builtin_fmaf(sf[b][e], sxm, b4[e]) : __builtin_fmaf((float)si[b][e] * sxm, sw4[e], b4[e]);
+                o[e] = (_Float16)v;
+            }
+            __half *dst = f.y + (size_t)m * f.ldy + n0;
+            if (n0 + 3 < f.N) {
+                *reinterpret_cast<h4 *>(dst) = o;         // 8 bytes: row starts are 16-byte aligned, n0 % 4 == 0
+            } else {
+                for (int e = 0; e < 4 && n0 + e < f.N; ++e) reinterpret_cast<_Float16 *>(dst)[e] = o[e];
+            }
+        }
     }
 }
 
@@ -669,13 +690,8 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     f.tiles_m = p.tiles_m;
     f.tiles_n = p.tiles_n;
     f.splits = splits;
-    f.waves_m = WAVES_M;
-    f.waves_n = WAVES_N;
-    f.wm = WM;
-    f.wn = WN;
-    f.w4 = W4;
-    const size_t lanes = (size_t)grid * WAVES_M * WAVES_N * WN * WM * 4 * 64;
-    hipLaunchKernelGGL(splitk_finish_kernel, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, st, f);
+    hipLaunchKernelGGL((splitk_finish_kernel<WAVES_M, WAVES_N, WM, WN, W4>), dim3(grid * WAVES_M * WAVES_N), dim3(256), 0, st,
+                       f);
     return check_hip(hipGetLastError(), "splitk_finish launch");
 }
 
