@@ -194,7 +194,7 @@ const char *ql_last_error(void) { return g_err; }
 
 int ql_set_kernel_variant(int variant)
 {
-    if (variant < 0 || (variant > 19 && variant < 100) ||
+    if (variant < 0 || (variant > 20 && variant < 100) ||
         (variant > 104 && variant != 111 && variant != 121 && variant != 130 && !(variant >= 202 && variant <= 232) &&
          !(variant >= 302 && variant <= 332)))
         return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);

@@ -23,6 +23,7 @@
 // between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
 // an fp32 accumulator with the group's scale.
 #include "common.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace ql {
@@ -768,6 +769,13 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
             if (pa.splits > 1 && pa.us < best * 0.9) best = pa.us, variant = 200, splits = pa.splits;
             if (pb.splits > 1 && pb.us < best * 0.9) best = pb.us, variant = 300, splits = pb.splits;
         }
+        if (a.M <= 128) {
+            // at most two 64-token tiles high: 64x64 tiles put four times as many (small) workgroups on the GPU
+            // as 128x128.  Such a workgroup streams K at ~0.14 us per 64 k whatever its size (latency bound), and
+            // the weights cannot arrive faster than HBM delivers them.
+            const double us64 = std::max(4.0 + 0.14 * (a.K / 64), 2.2 + 1.5 * ((double)a.N * a.K) / 6.8e6);
+            if (us64 < best * 0.9) best = us64, variant = 20, splits = 1;
+        }
     } else if (variant >= 202 && variant <= 232) {
         splits = variant - 200, variant = 200;
     } else if (variant >= 302 && variant <= 332) {
@@ -813,6 +821,8 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 4, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
     case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU)
         return launch_one<4, 2, 1, 2, 2, 4, false, EPI>(a, st);
+    case 20:  // 64 tokens x 64 channels, 4 wavefronts of 32x32, up to four workgroups per CU: few-token shapes
+        return launch_one<2, 2, 1, 1, 2, 4, false, EPI, 4>(a, st);
     case 14:  // 128x128, 8 wavefronts of 64 tokens x 32 channels
         return launch_one<2, 4, 2, 1, 2, 4, false, EPI>(a, st);
     case 10:  // 256x256, 4 wavefronts of 128x128, 128 k per stage, 2 stages

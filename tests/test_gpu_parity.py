@@ -93,7 +93,7 @@ def test_weight_quant_int4_bit_exact_and_export(G, N, K):
 
 
 # --------------------------------------------------------------- accumulators
-PREFILL_VARIANTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19]
+PREFILL_VARIANTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20]
 SHAPES_ACC = [(64, 512, 512), (100, 192, 200), (300, 1024, 520), (257, 256, 33)]
 
 
