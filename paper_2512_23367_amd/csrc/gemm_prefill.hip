@@ -742,39 +742,56 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
     }
     int splits = 1;
     if (variant == 0) {
-        // Estimated time of a tile shape = 4 us (launch, pipeline fill, epilogue) + rounds over the 256 CUs x tile
-        // operations / rate of a busy CU (measured: the big ping-pong tiles sustain ~10.2 TOPS per CU, three
-        // resident 128x128 workgroups ~9.2 together, a lone 128x128 workgroup 8.7, or 10 with the k-split
-        // ping-pong once K is long enough to amortise its exchange).  256x256 wins ties: fewer rounds, fewer
-        // pipeline fills and epilogues.  When even the best shape leaves most CUs idle (few tokens, long K), K is
-        // split over several workgroups per tile and a second kernel adds their partial sums (plan_split).
-        auto rounds = [](long tiles, long slots) { return (tiles + slots - 1) / slots; };
-        auto us_of = [&](double area_over_rate) { return 4.0 + area_over_rate * 2.0 * a.K / 1e6; };
-        const long m256 = ceil_div(a.M, 256), m128 = ceil_div(a.M, 128);
-        const long t256 = m256 * ceil_div(a.N, 256), t192 = m256 * ceil_div(a.N, 192), t128 = m128 * ceil_div(a.N, 128);
-        double best = us_of(rounds(t256, 256) * (256.0 * 256.0) / 10.2);
-        variant = 6;
-        const double c192 = us_of(rounds(t192, 256) * (256.0 * 192.0) / 10.2);
-        if (c192 < best * 0.97) best = c192, variant = 15;
-        int v128;
-        double c128;
-        if (t128 > 512) v128 = 11, c128 = us_of(rounds(t128, 768) * 3 * (128.0 * 128.0) / 9.2);
-        else if (t128 > 256) v128 = 4, c128 = us_of(2 * (128.0 * 128.0) / 9.0);
-        else if (a.K % 128 == 0 && a.K >= 3072) v128 = 19, c128 = us_of((128.0 * 128.0) / 10.0);
-        else v128 = 13, c128 = us_of((128.0 * 128.0) / 8.7);
-        if (c128 < best * 0.97) best = c128, variant = v128;
+        // Estimated time of a tile configuration, fitted to measurements over a grid of shapes (512..16384 tokens,
+        // N 1536..22016, K 1536..11008):
+        //   2.4 us launch + fp16 output at 6.9 TB/s + rounds x (o + tile operations / r),
+        // rounds = passes over the 256 CUs (configurations with several workgroups per CU advance in fractions of
+        // a pass once every CU is full), o = what a pass costs beyond its matrix work (pipeline fill, the
+        // epilogue's latency; hidden behind the neighbour when workgroups share a CU), r = TOPS of a busy CU.
+        // The fitted r of the large tiles is above what a CU sustains alone because their o absorbs part of it;
+        // only the sum is meaningful.  When even the best configuration leaves most CUs idle (few tokens, long
+        // K), K is split over several workgroups per tile and a second kernel adds the partial sums (plan_split).
+        struct Candidate { int variant, tm, tn, slots; double o, r; };
+        static const Candidate cands[] = {
+            {6, 256, 256, 1, 3.72, 14.14},    // 256x256 ping-pong
+            {15, 256, 192, 1, 3.55, 12.78},   // 256x192 ping-pong
+            {17, 128, 256, 2, 0.63, 11.12},   // 128x256 ping-pong, two workgroups per CU
+            {19, 128, 128, 1, 1.76, 11.13},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
+            {13, 128, 128, 1, 0.83, 10.02},   // 128x128, 8 wavefronts (at most one pass)
+            {4, 128, 128, 2, 0.53, 8.87},     // 128x128, 4 wavefronts, two per CU (more than one pass)
+            {11, 128, 128, 3, 0.26, 9.33},    // 128x128, 4 wavefronts, three per CU (more than two passes)
+        };
+        const long t128 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 128), t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
+        double best = 1e30;
+        for (const Candidate &c : cands) {
+            if (c.variant == 19 && (a.K % 128 != 0 || t128 > 256)) continue;
+            if (c.variant == 13 && t128 > 256) continue;
+            if (c.variant == 4 && t128 <= 256) continue;
+            if (c.variant == 11 && t128 <= 512) continue;
+            const long tiles = (long)ceil_div(a.M, c.tm) * ceil_div(a.N, c.tn);
+            double rounds;
+            if (c.slots == 1 || tiles <= 256L * c.slots) rounds = (double)((tiles + 255) / 256);
+            else rounds = (double)((tiles * c.slots + 255) / 256) / c.slots;
+            const double us = 2.4 + (double)a.M * a.N * 2.0 / 6.9e6 +
+                              rounds * (c.o + (double)c.tm * c.tn * 2.0 * a.K / (c.r * 1e6));
+            if (us < best * 0.99) best = us, variant = c.variant;   // earlier (larger) configurations win ties
+        }
         if (scratch && !dump_partials) {
             const SplitPlan pa = plan_split(t128, 128, 128, a.K, 64, 8.7, scratch);
             const SplitPlan pb = plan_split(t256, 256, 256, a.K, 64, 10.2, scratch);
             if (pa.splits > 1 && pa.us < best * 0.9) best = pa.us, variant = 200, splits = pa.splits;
             if (pb.splits > 1 && pb.us < best * 0.9) best = pb.us, variant = 300, splits = pb.splits;
         }
-        if (a.M <= 128) {
-            // at most two 64-token tiles high: 64x64 tiles put four times as many (small) workgroups on the GPU
-            // as 128x128.  Such a workgroup streams K at ~0.14 us per 64 k whatever its size (latency bound), and
-            // the weights cannot arrive faster than HBM delivers them.
-            const double us64 = std::max(4.0 + 0.14 * (a.K / 64), 2.2 + 1.5 * ((double)a.N * a.K) / 6.8e6);
-            if (us64 < best * 0.9) best = us64, variant = 20, splits = 1;
+        {
+            // 64x64 tiles: four (small) workgroups per CU, so few-token shapes put four times as many workgroups on
+            // the GPU as 128x128.  Alone, such a workgroup streams K at ~0.14 us per 64 k whatever its size
+            // (latency bound); when a CU holds several, each costs 0.8 us + its operations at 6.5 TOPS; and
+            // the weights cannot arrive faster than HBM delivers them (measured: 1.5x the plain stream time).
+            const long t64 = (long)ceil_div(a.M, 64) * ceil_div(a.N, 64);
+            const double per_cu = (double)((t64 + 255) / 256) * (0.8 + 8192.0 * a.K / 6.5e6);
+            const double us64 = std::max(2.4 + (double)a.M * a.N * 2.0 / 6.9e6 + std::max(1.6 + 0.14 * (a.K / 64), per_cu),
+                                         2.2 + 1.5 * ((double)a.N * a.K) / 6.8e6);
+            if (t64 <= 1024 && us64 < best * 0.95) best = us64, variant = 20, splits = 1;
         }
     } else if (variant >= 202 && variant <= 232) {
         splits = variant - 200, variant = 200;
