@@ -4,7 +4,9 @@ A plain, slow, obviously-correct implementation of what the hot path computes,
 written from the paper's definitions (its Eq. 1-2 quantizer, the per-token /
 per-channel / group-wise granularities of its Preliminary section, the
 symmetric setting of its Experimental Setup, and Y = XW of its Eq. 3), plus the
-two operand transforms of its W4A8 variants (SmoothQuant, Eq. 3; Hadamard rotation, Eq. 4).
+two operand transforms of its W4A8 variants (SmoothQuant, Eq. 3; Hadamard rotation, Eq. 4)
+and the other quantizer forms of its Preliminary section (Eq. 2 as printed, per-tensor
+granularity, a calibrated static activation scale).
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may use this
 package.  It shares no code with the HIP path and imports nothing from it.
@@ -21,6 +23,15 @@ from .quantizers import (  # noqa: F401
     pack_int4,
     unpack_int4,
     quant_eq2_literal,
+    quant_act_opt,
+    quant_weight_opt,
+    act_scale_calibrate,
+    scale_from_amax,
+    RANGE_SYMMETRIC,
+    RANGE_EQ2,
+    SCOPE_FINE,
+    SCOPE_TENSOR,
+    SCOPE_STATIC,
 )
 from .linear import igemm, igemm_grouped, linear_w8a8, linear_w4a8  # noqa: F401
 from .transforms import (  # noqa: F401

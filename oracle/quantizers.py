@@ -129,3 +129,90 @@ def quant_eq2_literal(x16: np.ndarray, n_bits: int):
     lo, hi = F32(-(2 ** (n_bits - 1))), F32(2 ** (n_bits - 1) - 1)
     r = np.minimum(np.maximum(r, lo), hi)
     return r.astype(np.int8), s
+
+
+# ---------------------------------------------------------------------------------------------
+# The other quantizer forms of the paper's Preliminary section: Eq. 2 as printed, per-tensor
+# granularity, and a calibrated (static) activation scale (Experimental Setup: scales derived from
+# calibration data).  All of them use the literal Eq. 1 form  code = round(X / s)  with the stored
+# fp32 scale s (one IEEE fp32 division per element), then the clamp of Eq. 2.
+
+RANGE_SYMMETRIC = 0      # s = amax / (2^(n-1) - 1), codes in +-(2^(n-1) - 1)
+RANGE_EQ2 = 1            # s = 2 amax / (2^n - 1),   codes in [-2^(n-1), 2^(n-1) - 1]   (Eq. 2 as printed)
+SCOPE_FINE = 0           # per token (activations), per output channel / per group (weights)
+SCOPE_TENSOR = 1         # one scale for the whole tensor, from its own abs-max
+SCOPE_STATIC = 2         # activations only: one calibrated scale supplied by the caller
+
+
+def scale_from_amax(amax, n_bits: int, rng: int):
+    """fp32 scale(s) of Eq. 2 from abs-max value(s); 0 stays 0 (callers replace it by 1 on use)."""
+    amax = np.asarray(amax, dtype=F32)
+    if rng == RANGE_SYMMETRIC:
+        return (amax / F32(2 ** (n_bits - 1) - 1)).astype(F32)        # one fp32 division
+    if rng == RANGE_EQ2:
+        return ((F32(2) * amax) / F32(2 ** n_bits - 1)).astype(F32)   # exact doubling, one fp32 division
+    raise ValueError("unknown range")
+
+
+def _limits(n_bits: int, rng: int):
+    hi = 2 ** (n_bits - 1) - 1
+    return (F32(-hi), F32(hi)) if rng == RANGE_SYMMETRIC else (F32(-hi - 1), F32(hi))
+
+
+def _codes(x: np.ndarray, s: np.ndarray, n_bits: int, rng: int) -> np.ndarray:
+    lo, hi = _limits(n_bits, rng)
+    r = np.rint(x / s)                                                # Eq. 1: fp32 division, half to even
+    return np.minimum(np.maximum(r, lo), hi).astype(np.int8)          # clamp of Eq. 2
+
+
+def act_scale_calibrate(batches, rng: int = RANGE_SYMMETRIC) -> np.float32:
+    """Calibrated per-tensor activation scale: Eq. 2's s from the largest |x| seen over the batches."""
+    amax = F32(0)
+    for b in batches:
+        amax = max(amax, np.abs(_as_f32(b)).max(initial=F32(0)))
+    return F32(scale_from_amax(amax, 8, rng))
+
+
+def quant_act_opt(x16: np.ndarray, rng: int = RANGE_SYMMETRIC, scope: int = SCOPE_FINE, static_scale=None):
+    """int8 activation quantization with the given range / granularity.  Returns (xq int8 [M,K],
+    sx float32 [M]): one entry per token whatever the granularity, so the GEMM epilogue is unchanged."""
+    x = _as_f32(x16)
+    M = x.shape[0]
+    if scope == SCOPE_FINE:
+        s = scale_from_amax(np.abs(x).max(axis=1), 8, rng)
+    elif scope == SCOPE_TENSOR:
+        s = np.full(M, scale_from_amax(np.abs(x).max(initial=F32(0)), 8, rng), dtype=F32)
+    elif scope == SCOPE_STATIC:
+        if static_scale is None or not np.isfinite(static_scale) or static_scale < 0:
+            raise ValueError("static scope takes a finite non-negative scale")
+        s = np.full(M, F32(static_scale), dtype=F32)
+    else:
+        raise ValueError("unknown scope")
+    s = np.where(s == 0, F32(1), s).astype(F32)
+    return _codes(x, s[:, None], 8, rng), s
+
+
+def quant_weight_opt(w16: np.ndarray, n_bits: int, group: int = 0, rng: int = RANGE_SYMMETRIC,
+                     scope: int = SCOPE_FINE):
+    """Weight quantization with the given range / granularity.
+    n_bits 8: returns (wq int8 [N,K], sw float32 [N]);
+    n_bits 4: returns (packed uint8 [N,K/2], q int8 [N,K], sw float16 [N,K/group]) -- the scale is
+    rounded to fp16 before the codes are computed, as in quant_weight_int4."""
+    w = _as_f32(w16)
+    N, K = w.shape
+    if scope not in (SCOPE_FINE, SCOPE_TENSOR):
+        raise ValueError("weights take fine or per-tensor scope")
+    if n_bits == 8:
+        amax = np.abs(w).max(axis=1) if scope == SCOPE_FINE else np.full(N, np.abs(w).max(initial=F32(0)), dtype=F32)
+        s = scale_from_amax(amax, 8, rng)
+        s = np.where(s == 0, F32(1), s).astype(F32)
+        return _codes(w, s[:, None], 8, rng), s
+    if n_bits != 4 or group <= 0 or K % group or group % 2:
+        raise ValueError("4-bit weights take an even group length that divides K")
+    wg = w.reshape(N, K // group, group)
+    amax = np.abs(wg).max(axis=2) if scope == SCOPE_FINE else \
+        np.full((N, K // group), np.abs(w).max(initial=F32(0)), dtype=F32)
+    s16 = scale_from_amax(amax, 4, rng).astype(np.float16)            # round to nearest even
+    s16 = np.where(s16 == 0, np.float16(1), s16).astype(np.float16)
+    q = _codes(wg, s16.astype(F32)[:, :, None], 4, rng).reshape(N, K)
+    return pack_int4(q), q, s16
