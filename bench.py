@@ -418,10 +418,19 @@ def main():
             sxv = torch.empty(M, dtype=torch.float32, device="cuda:0")
             inv = torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5
             B = ql.ql_hadamard_block(K)
+            scratch = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+            static = torch.full((1,), 0.05, dtype=torch.float32, device="cuda:0")
             row = {"shape": f"act_quant.M{M}.K{K}", "hadamard_block": B}
             for name, fn in (("plain", lambda i: ql.ql_quant_act_per_token(x, None, kl, sxv)),
                              ("smoothquant", lambda i: ql.ql_quant_act_per_token_transformed(x, inv, 0, None, kl, sxv)),
-                             ("hadamard", lambda i: ql.ql_quant_act_per_token_transformed(x, None, B, None, kl, sxv))):
+                             ("hadamard", lambda i: ql.ql_quant_act_per_token_transformed(x, None, B, None, kl, sxv)),
+                             # the other quantizer forms: Eq. 2 as printed, per-tensor dynamic, calibrated static scale
+                             ("eq2_per_token", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_EQ2, ql.QL_SCOPE_FINE, None,
+                                                                             None, kl, sxv, None)),
+                             ("per_tensor", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_SYMMETRIC, ql.QL_SCOPE_TENSOR,
+                                                                          None, None, kl, sxv, scratch)),
+                             ("static_scale", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_SYMMETRIC, ql.QL_SCOPE_STATIC,
+                                                                            static, None, kl, sxv, None))):
                 t = graph_time_ms(torch, fn, 50)
                 row[name + "_us"] = round(t * 1e3, 2)
                 row[name + "_gbs"] = round(3 * M * K / (t * 1e-3) / 1e9, 1)

@@ -184,6 +184,36 @@ int ql_quant_weight_transformed(const void *w, int N, int K, int bits, int group
                                 int hadamard_block, float *w32, void *wq_canonical, void *scales,
                                 void *wq_kernel, void *stream);
 
+/* ---- The other quantizer forms of the paper's Preliminary section -------------------------------------------
+ * range: QL_RANGE_SYMMETRIC  s = max|X| / (2^(n-1) - 1), codes in +-(2^(n-1) - 1)   (what every call above uses)
+ *        QL_RANGE_EQ2        Eq. 2 as printed: s = 2 max|X| / (2^n - 1), codes in [-2^(n-1), 2^(n-1) - 1]
+ * scope: QL_SCOPE_FINE       per token (activations), per output channel / per group (weights)
+ *        QL_SCOPE_TENSOR     per-tensor granularity: one scale from the whole tensor's own maximum
+ *        QL_SCOPE_STATIC     activations only: one calibrated scale supplied by the caller (Experimental
+ *                            Setup: scales derived from calibration data); values beyond its range are clamped
+ * Arithmetic: Eq. 1 as printed, code = round-half-even(X / s) with the stored fp32 scale (IEEE division; for
+ * 4-bit weights s is first rounded to fp16), then the clamp; a zero scale is stored as 1.  Exception:
+ * activations with (QL_RANGE_SYMMETRIC, QL_SCOPE_FINE) are ql_quant_act_per_token itself.  The outputs have
+ * the layouts of ql_quant_act_per_token / ql_quant_weight -- sx holds one (possibly repeated) entry per token,
+ * per-tensor weight scales are stored per channel / per group -- so the GEMM entry points take them unchanged.
+ * With QL_RANGE_EQ2 both operands can hold -2^(n-1): K is limited to 131040 so that int32 sums cannot overflow.
+ * scratch: 4 bytes of device memory, 4-byte aligned, required for QL_SCOPE_TENSOR only (else may be NULL). */
+typedef enum ql_range { QL_RANGE_SYMMETRIC = 0, QL_RANGE_EQ2 = 1 } ql_range;
+typedef enum ql_scope { QL_SCOPE_FINE = 0, QL_SCOPE_TENSOR = 1, QL_SCOPE_STATIC = 2 } ql_scope;
+
+/* Calibration of a static activation scale: *scale = max(*scale, s(max|x|)) for the given range, so that
+ * calling it on every calibration batch leaves the scale of the largest value seen.  scale: device fp32
+ * that holds 0 (or an earlier result) on entry. */
+int ql_act_scale_calibrate(const void *x, int64_t ldx, int M, int K, int range, float *scale, void *stream);
+
+/* static_scale: device fp32 (QL_SCOPE_STATIC only). */
+int ql_quant_act_opt(const void *x, int64_t ldx, int M, int K, int range, int scope, const float *static_scale,
+                     int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx, void *scratch, void *stream);
+
+/* scope: QL_SCOPE_FINE or QL_SCOPE_TENSOR. */
+int ql_quant_weight_opt(const void *w, int N, int K, int bits, int group, int range, int scope,
+                        void *wq_canonical, void *scales, void *wq_kernel, void *scratch, void *stream);
+
 /* Ceiling probes for benchmarks (nothing of the method): what the GPU sustains on the two resources the
  * layer is bound by, to be timed by the caller with events on `stream`.
  *   ql_probe_mfma_int8: `workgroups` workgroups of 8 wavefronts each issue 4*iters register-resident

@@ -26,7 +26,11 @@ EXPORTS = [
     "ql_probe_mfma_int8", "ql_probe_hbm_read",
     "ql_hadamard_block", "ql_smooth_calibrate", "ql_smooth_scales",
     "ql_quant_act_per_token_transformed", "ql_quant_weight_transformed",
+    "ql_act_scale_calibrate", "ql_quant_act_opt", "ql_quant_weight_opt",
 ]
+
+QL_RANGE_SYMMETRIC, QL_RANGE_EQ2 = 0, 1
+QL_SCOPE_FINE, QL_SCOPE_TENSOR, QL_SCOPE_STATIC = 0, 1, 2
 
 
 class QlError(RuntimeError):
@@ -76,6 +80,9 @@ def lib() -> ctypes.CDLL:
             "ql_smooth_scales": [vp, vp, i, i, c.c_float, vp, vp, vp],
             "ql_quant_act_per_token_transformed": [vp, i64, i, i, vp, i, vp, vp, vp, vp],
             "ql_quant_weight_transformed": [vp, i, i, i, i, vp, i, vp, vp, vp, vp, vp],
+            "ql_act_scale_calibrate": [vp, i64, i, i, i, vp, vp],
+            "ql_quant_act_opt": [vp, i64, i, i, i, i, vp, vp, vp, vp, vp, vp],
+            "ql_quant_weight_opt": [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(l, name)
@@ -163,6 +170,26 @@ def ql_quant_weight_transformed(w, bits, group, smooth, hadamard_block, w32, wq_
     N, K = w.shape
     _check(lib().ql_quant_weight_transformed(_p(w), N, K, bits, group, _p(smooth), hadamard_block, _p(w32),
                                              _p(wq_canonical), _p(scales), _p(wq_kernel), _stream()))
+
+
+def ql_act_scale_calibrate(x, rng, scale):
+    _want(x, torch.float16, "x"), _want(scale, torch.float32, "scale")
+    M, K = x.shape
+    _check(lib().ql_act_scale_calibrate(_p(x), _ld(x) if M else K, M, K, rng, _p(scale), _stream()))
+
+
+def ql_quant_act_opt(x, rng, scope, static_scale, xq_rowmajor, xq_kernel, sx, scratch):
+    _want(x, torch.float16, "x")
+    M, K = x.shape
+    _check(lib().ql_quant_act_opt(_p(x), _ld(x) if M else K, M, K, rng, scope, _p(static_scale), _p(xq_rowmajor),
+                                  _p(xq_kernel), _p(sx), _p(scratch), _stream()))
+
+
+def ql_quant_weight_opt(w, bits, group, rng, scope, wq_canonical, scales, wq_kernel, scratch):
+    _want(w, torch.float16, "w")
+    N, K = w.shape
+    _check(lib().ql_quant_weight_opt(_p(w), N, K, bits, group, rng, scope, _p(wq_canonical), _p(scales),
+                                     _p(wq_kernel), _p(scratch), _stream()))
 
 
 def ql_weight_bytes(N, K, bits, group):

@@ -123,6 +123,87 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     }
 }
 
+// The other quantizer forms of the Preliminary section (not the hot path; one workgroup per token, the row is
+// read twice).  Eq. 1 as printed: code = rne(x / s) with the stored fp32 scale s (IEEE division), then Eq. 2's
+// clamp.  range 1 = Eq. 2 as printed (s = 2 amax / 255, codes in [-128, 127]); scope: the token's own maximum,
+// the whole tensor's (tensor_amax: its bit pattern, found by a kernel before this one) or a calibrated scale
+// supplied by the caller (static_scale).  sx still gets one entry per token, so the GEMM epilogue is unchanged.
+__device__ inline float act_scale_of(float amax, int range)
+{
+    return range == QL_RANGE_EQ2 ? (2.0f * amax) / 255.0f : amax / 127.0f;   // one IEEE fp32 division
+}
+
+__global__ __launch_bounds__(256) void act_quant_opt_kernel(const __half *__restrict__ x, int64_t ldx, int M, int K,
+                                                            int range, const unsigned *__restrict__ tensor_amax,
+                                                            const float *__restrict__ static_scale,
+                                                            int8_t *__restrict__ xq_rm, int8_t *__restrict__ xq_kl,
+                                                            float *__restrict__ sx)
+{
+    __shared__ unsigned red[4];
+    const int m = blockIdx.x;
+    const int nchunks = K / CHUNK;
+    const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)m * ldx);
+    float s;
+    if (static_scale) {
+        s = *static_scale;
+    } else if (tensor_amax) {
+        s = act_scale_of(__uint_as_float(*tensor_amax), range);
+    } else {
+        unsigned mx = 0;
+        for (int c = threadIdx.x; c < nchunks; c += 256) mx = abs_max_bits(row[c], mx);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+        __syncthreads();
+        mx = max(max(red[0], red[1]), max(red[2], red[3]));
+        s = act_scale_of(half_bits_to_float(mx), range);
+    }
+    if (s == 0.0f) s = 1.0f;
+    if (threadIdx.x == 0) sx[m] = s;
+    const float lo = range == QL_RANGE_EQ2 ? -128.0f : -127.0f;
+    for (int c = threadIdx.x; c < nchunks; c += 256) {
+        const Half16 h = row[c];
+        const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
+        unsigned q[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float v = half_bits_to_float((w[i / 2] >> (16 * (i % 2))) & 0xffffu);
+            const float r = fminf(fmaxf(rintf(v / s), lo), 127.0f);   // IEEE fp32 division, ties to even, clamp
+            q[i / 4] |= (unsigned)((int)r & 0xff) << (8 * (i % 4));
+        }
+        const uint4 o = make_uint4(q[0], q[1], q[2], q[3]);
+        if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK) = o;
+        if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = o;
+    }
+}
+
+// max |x| over all tokens, as a bit pattern (accumulates into *out) or, with `as_scale`, as Eq. 2's scale for
+// the given range (the scale is a non-decreasing function of the maximum, so the largest scale any workgroup
+// derives is the scale of the largest value): a calibrated scale is the running maximum over batches
+__global__ __launch_bounds__(256) void act_absmax_kernel(const __half *__restrict__ x, int64_t ldx, int M, int K,
+                                                         int range, bool as_scale, unsigned *__restrict__ out)
+{
+    __shared__ unsigned red[4];
+    const int nchunks = K / CHUNK;
+    unsigned mx = 0;
+    for (int m = blockIdx.x; m < M; m += gridDim.x) {
+        const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)m * ldx);
+        for (int c = threadIdx.x; c < nchunks; c += 256) mx = abs_max_bits(row[c], mx);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mx = max(max(red[0], red[1]), max(red[2], red[3]));
+        const float amax = half_bits_to_float(mx);
+        const float v = as_scale ? act_scale_of(amax, range) : amax;
+        if (v > 0.0f) atomicMax(out, __float_as_uint(v));
+    }
+}
+
+__global__ void fill_word_kernel(unsigned *p, unsigned v) { *p = v; }
+
 __global__ void act_repack_kernel(const int8_t *__restrict__ xq_rm, int M, int K,
                                   int8_t *__restrict__ xq_kl)
 {
@@ -174,6 +255,32 @@ int launch_act_quant_smooth(const __half *x, int64_t ldx, int M, int K, const fl
     if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, true>(x, ldx, M, K, inv_smooth, xq_rm, xq_kl, sx, st);
     else launch_aq<8, true>(x, ldx, M, K, inv_smooth, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant (smooth) launch");
+}
+
+int launch_act_quant_opt(const __half *x, int64_t ldx, int M, int K, int range, int scope,
+                         const float *static_scale, unsigned *amax_scratch, int8_t *xq_rm, int8_t *xq_kl, float *sx,
+                         hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    const unsigned *ta = nullptr;
+    if (scope == QL_SCOPE_TENSOR) {
+        hipLaunchKernelGGL(fill_word_kernel, dim3(1), dim3(1), 0, st, amax_scratch, 0u);
+        hipLaunchKernelGGL(act_absmax_kernel, dim3(M < 1024 ? M : 1024), dim3(256), 0, st, x, ldx, M, K, range, false,
+                           amax_scratch);
+        QL_TRY(check_hip(hipGetLastError(), "act_absmax launch"));
+        ta = amax_scratch;
+    }
+    hipLaunchKernelGGL(act_quant_opt_kernel, dim3(M), dim3(256), 0, st, x, ldx, M, K, range, ta,
+                       scope == QL_SCOPE_STATIC ? static_scale : nullptr, xq_rm, xq_kl, sx);
+    return check_hip(hipGetLastError(), "act_quant (options) launch");
+}
+
+int launch_act_calibrate(const __half *x, int64_t ldx, int M, int K, int range, float *scale, hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    hipLaunchKernelGGL(act_absmax_kernel, dim3(M < 1024 ? M : 1024), dim3(256), 0, st, x, ldx, M, K, range, true,
+                       reinterpret_cast<unsigned *>(scale));
+    return check_hip(hipGetLastError(), "act_calibrate launch");
 }
 
 int launch_act_repack(const int8_t *xq_rm, int M, int K, int8_t *xq_kl, hipStream_t st)

@@ -296,6 +296,67 @@ int ql_quant_weight(const void *w, int N, int K, int bits, int group, void *wq_c
                                 static_cast<__half *>(scales), static_cast<uint8_t *>(wq_kernel), st);
 }
 
+// ---- the other quantizer forms of the Preliminary section (Eq. 2 as printed, per-tensor, static scale)
+static int check_options(int range, int scope, int K, bool weights)
+{
+    if (range != QL_RANGE_SYMMETRIC && range != QL_RANGE_EQ2) return fail(QL_ERR_UNSUPPORTED, "unknown range %d", range);
+    if (scope != QL_SCOPE_FINE && scope != QL_SCOPE_TENSOR && !(scope == QL_SCOPE_STATIC && !weights))
+        return fail(QL_ERR_UNSUPPORTED, "scope %d is not available for %s", scope, weights ? "weights" : "activations");
+    if (range == QL_RANGE_EQ2 && K > 131040)
+        return fail(QL_ERR_UNSUPPORTED, "K=%d: with codes of -128 on both sides int32 sums are safe up to K = 131040", K);
+    return QL_OK;
+}
+
+int ql_act_scale_calibrate(const void *x, int64_t ldx, int M, int K, int range, float *scale, void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_options(range, QL_SCOPE_STATIC, K, false));
+    if (M == 0) return QL_OK;
+    if (!x || !scale) return fail(QL_ERR_NULL, "x and scale are required");
+    if (!aligned(x, 16) || ldx < K || ldx % 8 || !aligned(scale, 4))
+        return fail(QL_ERR_ALIGN, "x must be 16-byte aligned, ldx >= K and a multiple of 8 (ldx=%lld)", (long long)ldx);
+    return launch_act_calibrate(static_cast<const __half *>(x), ldx, M, K, range, scale, static_cast<hipStream_t>(stream));
+}
+
+int ql_quant_act_opt(const void *x, int64_t ldx, int M, int K, int range, int scope, const float *static_scale,
+                     int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx, void *scratch, void *stream)
+{
+    QL_TRY(check_options(range, scope, K, false));
+    if (range == QL_RANGE_SYMMETRIC && scope == QL_SCOPE_FINE)
+        return ql_quant_act_per_token(x, ldx, M, K, xq_rowmajor, xq_kernel, sx, stream);
+    QL_TRY(check_mk(M, K));
+    if (M == 0) return QL_OK;
+    if (!x || !sx || (!xq_rowmajor && !xq_kernel)) return fail(QL_ERR_NULL, "x, sx and one of the outputs are required");
+    if (scope == QL_SCOPE_STATIC && !static_scale) return fail(QL_ERR_NULL, "static_scale is required for QL_SCOPE_STATIC");
+    if (scope == QL_SCOPE_TENSOR && !scratch) return fail(QL_ERR_NULL, "scratch is required for QL_SCOPE_TENSOR");
+    if (!aligned(x, 16) || ldx < K || ldx % 8)
+        return fail(QL_ERR_ALIGN, "x must be 16-byte aligned, ldx >= K and a multiple of 8 (ldx=%lld)", (long long)ldx);
+    if ((xq_rowmajor && !aligned(xq_rowmajor, 16)) || (xq_kernel && !aligned(xq_kernel, 256)) || !aligned(sx, 4) ||
+        (static_scale && !aligned(static_scale, 4)) || (scratch && !aligned(scratch, 4)))
+        return fail(QL_ERR_ALIGN, "xq_rowmajor needs 16-byte, xq_kernel 256-byte, sx/static_scale/scratch 4-byte alignment");
+    return launch_act_quant_opt(static_cast<const __half *>(x), ldx, M, K, range, scope, static_scale,
+                                static_cast<unsigned *>(scratch), xq_rowmajor, xq_kernel, sx,
+                                static_cast<hipStream_t>(stream));
+}
+
+int ql_quant_weight_opt(const void *w, int N, int K, int bits, int group, int range, int scope, void *wq_canonical,
+                        void *scales, void *wq_kernel, void *scratch, void *stream)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_nk(N, K, bits));
+    QL_TRY(check_options(range, scope, K, true));
+    if (!w) return fail(QL_ERR_NULL, "w is NULL");
+    if (bits == 8 && !scales) return fail(QL_ERR_NULL, "scales is required for int8 weights");
+    if (!wq_canonical && !wq_kernel && !scales) return fail(QL_ERR_NULL, "no output requested");
+    if (scope == QL_SCOPE_TENSOR && !scratch) return fail(QL_ERR_NULL, "scratch is required for QL_SCOPE_TENSOR");
+    if (!aligned(w, 16) || (wq_canonical && !aligned(wq_canonical, 16)) || (scales && !aligned(scales, 16)) ||
+        (wq_kernel && !aligned(wq_kernel, 256)) || (scratch && !aligned(scratch, 4)))
+        return fail(QL_ERR_ALIGN, "w/wq_canonical/scales need 16-byte, wq_kernel 256-byte, scratch 4-byte alignment");
+    return launch_weight_quant_opt(static_cast<const __half *>(w), N, K, bits, group, range, scope == QL_SCOPE_TENSOR,
+                                   static_cast<unsigned *>(scratch), wq_canonical, scales, wq_kernel,
+                                   static_cast<hipStream_t>(stream));
+}
+
 // ---- SmoothQuant / Hadamard variants (Eq. 3-4)
 static int check_transform(int K, int hadamard_block)
 {

@@ -88,6 +88,12 @@ int launch_weight_quant8_f32(const float *w, int N, int K, int8_t *canon, float 
                              hipStream_t st);
 int launch_weight_quant4_f32(const float *w, int N, int K, int group, uint8_t *canon, __half *scales,
                              uint8_t *kl, hipStream_t st);
+int launch_act_quant_opt(const __half *x, int64_t ldx, int M, int K, int range, int scope,
+                         const float *static_scale, unsigned *amax_scratch, int8_t *xq_rm, int8_t *xq_kl, float *sx,
+                         hipStream_t st);
+int launch_act_calibrate(const __half *x, int64_t ldx, int M, int K, int range, float *scale, hipStream_t st);
+int launch_weight_quant_opt(const __half *w, int N, int K, int bits, int group, int range, bool per_tensor,
+                            unsigned *amax_scratch, void *canon, void *scales, void *kl, hipStream_t st);
 int hadamard_block_of(int K);
 int launch_act_quant_transform(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, int hblock,
                                int8_t *xq_rm, int8_t *xq_kl, float *sx, hipStream_t st);
