@@ -72,3 +72,36 @@ def test_null_and_alignment_validation_without_launch():
     # unknown kernel variant
     assert lib.ql_set_kernel_variant(77) == 4
     assert lib.ql_set_kernel_variant(0) == 0
+
+
+def test_header_is_plain_c_and_a_c_program_links(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99 and a C program that calls the host-only
+    entry points links against the library and runs (no GPU needed for these calls)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    lib_path = os.path.join(ROOT, "paper_2512_23367_amd", "libqlinear.so")
+    if not os.path.exists(lib_path):
+        pytest.skip("library not built")
+    src = tmp_path / "use_abi.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "qlinear.h"\n'
+        "int main(void) {\n"
+        "    size_t canon = 0, scales = 0, kernel = 0, ws = 0;\n"
+        "    int block = 0;\n"
+        "    if (ql_version() < 100) return 1;\n"
+        "    if (ql_weight_bytes(4096, 4096, 4, 128, &canon, &scales, &kernel) != QL_OK) return 2;\n"
+        "    if (canon != (size_t)4096 * 2048 || scales != (size_t)4096 * 32 * 2 || kernel < canon + 2 * scales) return 3;\n"
+        "    if (ql_workspace_bytes(64, 512, 512, 8, &ws) != QL_OK || ws < (size_t)64 * 512) return 4;\n"
+        "    if (ql_hadamard_block(11008, &block) != QL_OK || block != 256) return 5;\n"
+        "    if (ql_weight_bytes(10, 100, 8, 0, &canon, &scales, &kernel) != QL_ERR_SHAPE) return 6;\n"
+        '    if (ql_last_error()[0] == 0) return 7;\n'
+        '    printf("ok %d\\n", ql_version());\n'
+        "    return 0;\n}\n")
+    exe = tmp_path / "use_abi"
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, str(src), "-o", str(exe), lib_path,
+                    "-Wl,-rpath," + os.path.dirname(lib_path)], check=True, capture_output=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0 and out.stdout.startswith("ok"), (out.returncode, out.stdout, out.stderr)
