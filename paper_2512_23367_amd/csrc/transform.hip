@@ -11,7 +11,7 @@
 // stages h = 1, 2, ..., B/2 in that order, every output one addition or subtraction, then one multiply by
 // fp32(1/sqrt(B)): a fixed sequence of single fp32 operations per element, whatever lane does them.
 // A lane holds chunks of 16 consecutive elements: stages h <= 8 in registers, the next six across the lanes
-// of a wavefront, the last two (B > 1024) across wavefronts through LDS.
+// of a wavefront (four of them as vector-ALU lane permutes), the last two (B > 1024) across wavefronts through LDS.
 #include "common.h"
 #include "quant_math.h"
 #include <cmath>
@@ -41,9 +41,44 @@ __device__ inline void scale_chunk(const float *__restrict__ s, int c, float (&v
     }
 }
 
+// Value of the same register in lane (lane ^ bit).  Inside a row of 16 lanes the data-parallel-primitive
+// modifiers do it on the vector ALU (quad permutes for 1 and 2; 4 = reverse each half-row of 8, then reverse
+// each quad; 8 = rotate the row by 8); 16 and 32 go through the LDS crossbar.
+template <int CTRL>
+__device__ inline float dpp_move(float v)
+{
+    // all rows and banks enabled and every source lane exists: the 'old' operand is never read
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+template <int BIT>
+__device__ inline float lane_xor(float v)
+{
+    if constexpr (BIT == 1) return dpp_move<0xB1>(v);                        // quad_perm [1,0,3,2]
+    else if constexpr (BIT == 2) return dpp_move<0x4E>(v);                   // quad_perm [2,3,0,1]
+    else if constexpr (BIT == 4) return dpp_move<0x1B>(dpp_move<0x141>(v));  // row_half_mirror (i ^ 7), then quad_perm [3,2,1,0] (i ^ 3)
+    else if constexpr (BIT == 8) return dpp_move<0x128>(v);                  // row_ror:8
+    else return __shfl_xor(v, BIT, 64);
+}
+
+// one butterfly stage between lanes BIT apart: the lower lane keeps a + b, the upper one a - b (a = the lower lane's value)
+template <int BIT, int NIT>
+__device__ inline void lane_stage(float (&v)[NIT][16])
+{
+    // a + b below, b' - a' above: one fused multiply-add by +-1 (exact product, so the single rounding is that of
+    // the addition or subtraction itself)
+    const float sgn = (threadIdx.x & BIT) != 0 ? -1.0f : 1.0f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[it][i] = __builtin_fmaf(sgn, v[it][i], lane_xor<BIT>(v[it][i]));
+}
+
 // Block-diagonal Hadamard transform of the row whose chunk (it * TW + tid) sits in v[it]; lanes per block
 // = hblock / 16 (a power of two that divides TW and the number of chunks, so a block never straddles an `it`).
-template <int NIT>
+// LB: log2(hblock) when it is known at compile time (every stage's presence is then resolved at compile time,
+// which saves the register copies that merge the skipped and the executed path of each stage), -1 otherwise.
+template <int NIT, int LB = -1>
 __device__ inline void fwht_row(float (&v)[NIT][16], int hblock, float norm, float *xchg /* [TW][16] */)
 {
     const int tid = threadIdx.x;
@@ -59,25 +94,26 @@ __device__ inline void fwht_row(float (&v)[NIT][16], int hblock, float norm, flo
                     v[it][i | h] = a - b;
                 }
     }
-    const int lanes = hblock / 16;
-    for (int bit = 1; bit < lanes; bit <<= 1) {
-        const bool upper = (tid & bit) != 0;
+    const int lanes = LB >= 0 ? (1 << (LB >= 0 ? LB : 0)) / 16 : hblock / 16;
+    if (lanes > 1) lane_stage<1>(v);
+    if (lanes > 2) lane_stage<2>(v);
+    if (lanes > 4) lane_stage<4>(v);
+    if (lanes > 8) lane_stage<8>(v);
+    if (lanes > 16) lane_stage<16>(v);
+    if (lanes > 32) lane_stage<32>(v);
+    for (int bit = 64; bit < lanes; bit <<= 1) {   // across wavefronts
+        const float sgn = (tid & bit) != 0 ? -1.0f : 1.0f;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             float o[16];
-            if (bit < 64) {
+            __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[i] = __shfl_xor(v[it][i], bit, 64);
-            } else {
-                __syncthreads();
+            for (int i = 0; i < 16; ++i) xchg[i * TW + tid] = v[it][i];
+            __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 16; ++i) xchg[i * TW + tid] = v[it][i];
-                __syncthreads();
+            for (int i = 0; i < 16; ++i) o[i] = xchg[i * TW + (tid ^ bit)];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[i] = xchg[i * TW + (tid ^ bit)];
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) v[it][i] = upper ? o[i] - v[it][i] : v[it][i] + o[i];
+            for (int i = 0; i < 16; ++i) v[it][i] = __builtin_fmaf(sgn, v[it][i], o[i]);
         }
     }
 #pragma unroll
@@ -90,7 +126,7 @@ __device__ inline void fwht_row(float (&v)[NIT][16], int hblock, float norm, flo
 // (Collecting 8 tokens per workgroup for whole-line writes of the tile order, as the plain quantizer does at
 // large M, was measured and is slower here: a workgroup transforms its tokens one after the other, and that
 // serial latency costs more than the 16-byte writes save -- 37 us against 27 us for 4096 x 4096.)
-template <int NIT>
+template <int NIT, int LB>
 __global__ __launch_bounds__(TW) void act_quant_transform_kernel(const __half *__restrict__ x, int64_t ldx, int K,
                                                                  const float *__restrict__ inv_smooth, int hblock,
                                                                  float norm, int8_t *__restrict__ xq_rm,
@@ -113,7 +149,7 @@ __global__ __launch_bounds__(TW) void act_quant_transform_kernel(const __half *_
             for (int i = 0; i < 16; ++i) v[it][i] = 0.0f;
         }
     }
-    if (hblock > 1) fwht_row<NIT>(v, hblock, norm, xchg);
+    if (LB > 0) fwht_row<NIT, LB>(v, hblock, norm, xchg);
 
     float amax = 0.0f;
 #pragma unroll
@@ -217,13 +253,30 @@ int launch_act_quant_transform(const __half *x, int64_t ldx, int M, int K, const
     if (M == 0) return QL_OK;
     const int nit = ceil_div(K / 16, TW);
     const float norm = block_norm(hblock > 1 ? hblock : 1);
-#define QL_LAUNCH(NIT)                                                                                              \
-    hipLaunchKernelGGL((act_quant_transform_kernel<NIT>), dim3(M), dim3(TW), 0, st, x, ldx, K, inv_smooth, hblock, \
-                       norm, xq_rm, xq_kl, sx)
-    if (nit == 1) QL_LAUNCH(1);
-    else if (nit == 2) QL_LAUNCH(2);
-    else if (nit == 3) QL_LAUNCH(3);
-    else QL_LAUNCH(4);
+    int lb = 0;
+    while (hblock > 1 && (1 << lb) < hblock) ++lb;
+#define QL_LAUNCH(NIT, LB)                                                                                        \
+    hipLaunchKernelGGL((act_quant_transform_kernel<NIT, LB>), dim3(M), dim3(TW), 0, st, x, ldx, K, inv_smooth,    \
+                       hblock, norm, xq_rm, xq_kl, sx)
+#define QL_BY_BLOCK(NIT)                                                                                          \
+    switch (lb) {                                                                                                 \
+    case 0: QL_LAUNCH(NIT, 0); break;                                                                             \
+    case 4: QL_LAUNCH(NIT, 4); break;                                                                             \
+    case 5: QL_LAUNCH(NIT, 5); break;                                                                             \
+    case 6: QL_LAUNCH(NIT, 6); break;                                                                             \
+    case 7: QL_LAUNCH(NIT, 7); break;                                                                             \
+    case 8: QL_LAUNCH(NIT, 8); break;                                                                             \
+    case 9: QL_LAUNCH(NIT, 9); break;                                                                             \
+    case 10: QL_LAUNCH(NIT, 10); break;                                                                           \
+    case 11: QL_LAUNCH(NIT, 11); break;                                                                           \
+    case 12: QL_LAUNCH(NIT, 12); break;                                                                           \
+    default: return fail(QL_ERR_UNSUPPORTED, "hadamard_block=%d", hblock);                                        \
+    }
+    if (nit == 1) { QL_BY_BLOCK(1) }
+    else if (nit == 2) { QL_BY_BLOCK(2) }
+    else if (nit == 3) { QL_BY_BLOCK(3) }
+    else { QL_BY_BLOCK(4) }
+#undef QL_BY_BLOCK
 #undef QL_LAUNCH
     return check_hip(hipGetLastError(), "act_quant_transform launch");
 }
