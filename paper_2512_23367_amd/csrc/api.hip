@@ -158,7 +158,7 @@ int linear_common(const void *x, int64_t ldx, int M, int K, const void *wq, cons
         return fail(QL_ERR_ALIGN, "wq needs 256-byte, sw/bias 16-byte alignment");
     QL_TRY(check_out(y, ldy, N));
     if (M <= DECODE_MAX_M && (g_variant == 0 || (g_variant >= 100 && g_variant < 200)) && decode_fuses_quant(M, K, g_variant)) {
-        // one or two tokens: the decode GEMM quantizes them itself, one launch instead of two
+        // few tokens: the decode GEMM quantizes them itself, one launch instead of two
         GemmArgs a = {};
         a.x = static_cast<const __half *>(x);
         a.ldx = ldx;

@@ -7,7 +7,7 @@
 //     per wavefront, straight into the 16x16x64 int8 matrix instruction (int4: after a shift/mask
 //     unpack); nothing is reused, so nothing is staged in LDS;
 //   * the (at most 32) quantized tokens are re-read from L2 in the same tile order, or staged in LDS when
-//     they are few; for one or two tokens the linear-layer entry points skip the separate quantization
+//     they are few; for up to four tokens the linear-layer entry points skip the separate quantization
 //     kernel and every workgroup quantizes the fp16 tokens itself on the way into LDS (paper Eq. 1-2,
 //     same arithmetic as the stand-alone quantizer), while its first weight fragments are in flight.
 #include "common.h"
@@ -42,9 +42,14 @@ struct DecodeParams {
 // C: groups of 16 output channels per workgroup (they share every token fragment that is loaded).
 // XL: the (few) quantized tokens are staged once per workgroup in LDS, [k-tile half][token] with one extra
 // all-zero token row that the lanes of absent tokens read; the ring then holds weights only.
-// FQ: the tokens arrive as fp16 and are quantized here (XL staging with the quantizer in front of it).
-constexpr int FQ_MAX_M = 2;
-template <bool W4, int MH, int C, int EPI, int WAVES, bool XL, bool FQ>
+// FQ > 0: the tokens arrive as fp16 and are quantized here (XL staging with the quantizer in front of it); a lane
+// keeps FQ (= 2) pieces of 16 k in registers.
+// Measured: up to 4 tokens and K <= 4096 (8192 for two, 12288 for one) the fused form wins 0.7-2.4 us per
+// linear; at 8 tokens, or with twice the pieces per lane, every workgroup re-quantizing all tokens costs more
+// than the separate launch.
+constexpr int FQ_MAX_M = 4;
+constexpr size_t FQ_MAX_LDS = 24576;   // staged tokens (M + 1) * K bytes: four workgroups per CU still fit
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL, int FQ>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 {
     static_assert(!FQ || (XL && EPI == EPI_F16), "fused quantization stages the tokens in LDS");
@@ -145,49 +150,42 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     // registers (loads return in order: behind the weight stream they would arrive an HBM latency late);
     // the row maxima of the wavefronts' k-ranges meet in LDS (one workgroup barrier, reached by every
     // wavefront), then the codes are produced from the registers while the weights are still in flight.
-    // A lane keeps FQ_SLOTS pieces: two rounds of one token or one round of two.
-    constexpr int FQ_SLOTS = 2;
-    Half16 keep[FQ ? FQ_SLOTS : 1];
+    // With Mp = M rounded up to a power of two, lane l works on token l % Mp (always the same one: a token's
+    // maximum needs no bookkeeping) and, in slot sl, on piece th0 + sl * (64 / Mp) + l / Mp; the host makes sure
+    // that FQ slots cover the wavefront's pieces.
+    constexpr int FQ_SLOTS = FQ > 0 ? FQ : 1;
+    Half16 keep[FQ_SLOTS];
+    const int fq_lg = p.M <= 1 ? 0 : p.M <= 2 ? 1 : 2;   // log2(Mp)
+    const int fq_m = lane & ((1 << fq_lg) - 1);        // this lane's token (absent when >= M)
+    const int fq_ppr = 64 >> fq_lg;                     // pieces per slot
     auto load_tokens = [&](int th0, int th1) {
 #pragma unroll
         for (int sl = 0; sl < FQ_SLOTS; ++sl) {
-            const int it = sl / p.M, m = sl % p.M;        // M = 1: (0,0) (1,0);  M = 2: (0,0) (0,1)
-            const int i = th0 + it * 64 + lane;
+            const int i = th0 + sl * fq_ppr + (lane >> fq_lg);
             keep[sl] = Half16{uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
-            if (i < th1) keep[sl] = *reinterpret_cast<const Half16 *>(p.x + (size_t)m * p.ldx + (size_t)i * 16);
+            if (i < th1 && fq_m < p.M) keep[sl] = *reinterpret_cast<const Half16 *>(p.x + (size_t)fq_m * p.ldx + (size_t)i * 16);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
     auto quantize_tokens = [&](int th0, int th1) {
-        unsigned mx[FQ_MAX_M] = {0, 0};
+        unsigned mx = 0;
 #pragma unroll
-        for (int sl = 0; sl < FQ_SLOTS; ++sl) {
-            const unsigned v = abs_max_bits(keep[sl], 0);   // pieces beyond the range hold zeros
-            if (sl % p.M == 0) mx[0] = max(mx[0], v); else mx[1] = max(mx[1], v);
-        }
-#pragma unroll
-        for (int m = 0; m < FQ_MAX_M; ++m) {
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) mx[m] = max(mx[m], (unsigned)__shfl_xor((int)mx[m], off, 64));
-            if (lane == 0) amax_red[wave][m] = mx[m];
-        }
+        for (int sl = 0; sl < FQ_SLOTS; ++sl) mx = abs_max_bits(keep[sl], mx);   // pieces beyond the range hold zeros
+        for (int off = 32; off >= (1 << fq_lg); off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
+        if (lane < (1 << fq_lg)) amax_red[wave][lane] = mx;
         __syncthreads();
-        float inv[FQ_MAX_M];
-#pragma unroll
-        for (int m = 0; m < FQ_MAX_M; ++m) {
-            unsigned a = 0;
-            for (int w = 0; w < WAVES; ++w) a = max(a, amax_red[w][m]);
-            float scale;
-            token_scales(a, scale, inv[m]);
-            if (r == m) e_sx[0] = scale * (W4 ? 0.0625f : 1.0f);
-        }
+        unsigned a = 0;
+        for (int w = 0; w < WAVES; ++w) a = max(a, amax_red[w][fq_m]);
+        float scale, inv;
+        token_scales(a, scale, inv);
+        // the finishing lanes want the scale of token r: for r < M that is this lane's own token (Mp divides 16)
+        e_sx[0] = (r < p.M) ? scale * (W4 ? 0.0625f : 1.0f) : 0.0f;
 #pragma unroll
         for (int sl = 0; sl < FQ_SLOTS; ++sl) {
-            const int it = sl / p.M, m = sl % p.M;
-            const int i = th0 + it * 64 + lane;
-            if (i < th1) {
-                *reinterpret_cast<uint4 *>(xs + ((size_t)i * xrows + m) * 16) = quant_chunk(keep[sl], m == 0 ? inv[0] : inv[1]);
-                if (m == 0) *reinterpret_cast<uint4 *>(xs + ((size_t)i * xrows + p.M) * 16) = uint4{0, 0, 0, 0};
+            const int i = th0 + sl * fq_ppr + (lane >> fq_lg);
+            if (i < th1 && fq_m < p.M) {
+                *reinterpret_cast<uint4 *>(xs + ((size_t)i * xrows + fq_m) * 16) = quant_chunk(keep[sl], inv);
+                if (fq_m == 0) *reinterpret_cast<uint4 *>(xs + ((size_t)i * xrows + p.M) * 16) = uint4{0, 0, 0, 0};
             }
         }
         asm volatile("" ::: "memory");
@@ -390,7 +388,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     }
 }
 
-template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false, bool FQ = false>
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false, int FQ = 0>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     DecodeParams p;
@@ -456,12 +454,18 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     // few tokens: stage them in LDS (ring slots then hold weights only, more bytes in flight per register)
     const bool xl = (size_t)(a.M + 1) * a.K <= 24576 && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
     if (a.x) {   // fp16 tokens: quantize in the prologue (the caller checked decode_fuses_quant)
-        if (EPI != EPI_F16 || !xl || a.M > FQ_MAX_M) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
+        const bool xl_fq = a.M <= FQ_MAX_M && (size_t)(a.M + 1) * a.K <= FQ_MAX_LDS && variant != 121;
+        if (EPI != EPI_F16 || !xl_fq) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
+        // 16-k pieces of a wavefront's k-range x tokens (rounded up to a power of two) <= 64 lanes x 2 slots
+        const int waves = wide ? 16 : 8;
+        const int pieces = W4 ? 8 * ceil_div(a.K / 128, waves) : 4 * ceil_div(a.K / 64, waves);
+        const int mp = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
+        if (pieces * mp > 128) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
         if constexpr (EPI == EPI_F16) {
-            if (wide) return launch_one<W4, 1, 1, EPI, 16, true, true>(a, st);
-            if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, true>(a, st);
-            if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, true>(a, st);
-            return launch_one<W4, 1, 4, EPI, 8, true, true>(a, st);
+            if (wide) return launch_one<W4, 1, 1, EPI, 16, true, 2>(a, st);
+            if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, 2>(a, st);
+            if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, 2>(a, st);
+            return launch_one<W4, 1, 4, EPI, 8, true, 2>(a, st);
         }
     }
     if (xl) {
@@ -490,9 +494,11 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
 // re-quantizing all of them costs less than a kernel launch).
 bool decode_fuses_quant(int M, int K, int variant)
 {
-    // a wavefront (of at least 8) keeps its k-range in registers: 2 x 64 pieces of 16 k for one token, 64 for two
-    const int pieces = ceil_div(ceil_div(K, 128), 8) * 8;   // int4 splits whole 128-k groups, int8 64-k chunks: bound both
-    return M >= 1 && M <= FQ_MAX_M && (size_t)(M + 1) * K <= 24576 && pieces * M <= 128 && variant != 121 &&
+    // a wavefront (of at least 8) keeps its k-range in registers: at most 2 x 64 pieces of 16 k, tokens rounded up
+    // to a power of two (int4 splits whole 128-k groups, int8 64-k chunks: bound both)
+    const int pieces = ceil_div(ceil_div(K, 128), 8) * 8;
+    const int mp = M <= 1 ? 1 : M <= 2 ? 2 : 4;
+    return M >= 1 && M <= FQ_MAX_M && (size_t)(M + 1) * K <= FQ_MAX_LDS && pieces * mp <= 128 && variant != 121 &&
            variant != 130;
 }
 

@@ -270,13 +270,18 @@ def test_linear_fp16_within_tolerance(G, bits, M, K, N, bias):
 
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("M,K,N,ldx", [(1, 4096, 520, None), (2, 4096, 200, 4104), (1, 11008, 72, None), (2, 512, 33, None),
-                                       (1, 128, 16, 136), (2, 8192, 48, None)])
+                                       (1, 128, 16, 136), (2, 8192, 48, None),
+                                       (3, 4096, 200, None), (5, 4096, 520, 4104), (8, 4096, 10240, None),
+                                       (8, 4096, 4608, None), (6, 4096, 72, None), (16, 1536, 4608, None),
+                                       (12, 2048, 136, 2056), (7, 512, 33, None), (4, 8192, 264, None),
+                                       (9, 4096, 200, None), (3, 11008, 72, None), (16, 2560, 48, None)])
 def test_decode_linear_with_fused_quantization_matches_two_kernel_path(G, bits, M, K, N, ldx):
-    """One or two tokens: the decode GEMM quantizes the fp16 tokens in its prologue.  Same codes, same integer
-    sums, same epilogue arithmetic as quantization kernel + GEMM, so the fp16 outputs must agree bit for bit
-    (variant 130 forces the two-kernel path), and both must be within tolerance of the oracle."""
+    """Few tokens (up to 16 when they fit the kernel's registers and LDS): the decode GEMM quantizes the fp16
+    tokens in its prologue.  Same codes, same integer sums, same epilogue arithmetic as quantization kernel +
+    GEMM, so the fp16 outputs must agree bit for bit (variant 130 forces the two-kernel path; shapes beyond the
+    limits take it anyway), and both must be within tolerance of the oracle."""
     x = synth.activations(M, K, 0, "single")
-    if M == 2:
+    if M >= 2:
         x[1] = 0          # an all-zero token: scale 1, codes 0
     w = synth.weights(N, K, 0, "single")
     b = synth.bias(N, 0, "single")
