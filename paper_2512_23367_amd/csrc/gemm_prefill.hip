@@ -23,6 +23,7 @@
 // between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
 // an fp32 accumulator with the group's scale.
 #include "common.h"
+#include <cmath>
 #include <algorithm>
 #include <type_traits>
 
@@ -48,7 +49,7 @@ struct PrefillParams {
     int32_t *partials;
     int row0, nrows;
     int M, N, K, Npad;
-    int tiles_m, tiles_n;
+    int tiles_m, tiles_n, group_m;   // group_m: token tiles per strip of the tile order (see tile_coords)
     unsigned x_bytes, w_bytes;
     void *part;              // split-K: partial sums [split][workgroup][wavefront][block][quad][64 lanes x 16 B]
     int stages_per_split;    // split-K: blockIdx.y takes stages [y * stages_per_split, ...); otherwise all of them
@@ -68,21 +69,38 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes
 }
 
 // Hardware hands consecutive workgroup ids to the 8 XCDs in turn; give every XCD one contiguous
-// range of logical tiles, ordered so that tiles running together share activation and weight
-// strips in that XCD's L2.
-__device__ inline void tile_coords(int bid, int tiles_m, int tiles_n, int &tm, int &tn)
+// range of logical tiles, ordered (strips of `group` token tiles, channel tile by channel tile) so that the
+// tiles an XCD runs together form a block that shares activation and weight strips in that XCD's L2.
+__device__ inline void tile_coords(int bid, int tiles_m, int tiles_n, int group, int &tm, int &tn)
 {
     const int nt = tiles_m * tiles_n;
     const int xcd = bid % 8, idx = bid / 8;
     const int per = nt / 8, rem = nt % 8;
     const int logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
-    constexpr int GROUP = 8;
-    const int per_group = GROUP * tiles_n;
+    const int per_group = group * tiles_n;
     const int g = logical / per_group, in_g = logical % per_group;
-    const int first_m = g * GROUP;
-    const int gsize = (tiles_m - first_m) < GROUP ? (tiles_m - first_m) : GROUP;
+    const int first_m = g * group;
+    const int gsize = (tiles_m - first_m) < group ? (tiles_m - first_m) : group;
     tm = first_m + in_g % gsize;
     tn = in_g / gsize;
+}
+
+// Strip height: the tiles resident on one XCD together (32 CUs x occupancy, or all of its tiles if fewer) should
+// form the block that fetches the fewest operand bytes -- a x b tiles cost a*TM + b*TN rows of K bytes.  Only
+// divisors of tiles_m are considered (equal strips; a ragged last strip costs more than it saves), ties go to
+// the shorter strip (measured: fewer bytes fetched when the block does not fit the 4 MB L2 anyway).
+inline int strip_height(int tiles_m, int tiles_n, int TM, int TN, int occupancy)
+{
+    const long per_xcd = ((long)tiles_m * tiles_n + 7) / 8;
+    const long together = per_xcd < 32L * occupancy ? per_xcd : 32L * occupancy;
+    int best = 1;
+    long best_cost = -1;
+    for (int d = 1; d <= tiles_m; ++d) {
+        if (tiles_m % d) continue;
+        const long cost = (long)d * TM + ((together + d - 1) / d) * TN;
+        if (best_cost < 0 || cost < best_cost) best = d, best_cost = cost;
+    }
+    return best;
 }
 
 // WK = 2: the k-blocks of every stage are split between two sets of WAVES_M x WAVES_N wavefronts (the two
@@ -123,7 +141,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     const int wm = wave % WAVES_M, wn = (wave / WAVES_M) % WAVES_N, wk = wave / (WAVES_M * WAVES_N);
 
     int tm, tn;
-    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
 
     if (EPI == EPI_F16) {
         for (int t = threadIdx.x; t < TMB * 32; t += NW * 64) {
@@ -556,7 +574,7 @@ struct FinishParams {
     int64_t ldy;
     int32_t *acc;            // test hook (int8 weights): raw sums instead of y
     int M, N;
-    int tiles_m, tiles_n, splits;
+    int tiles_m, tiles_n, group_m, splits;
 };
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, bool W4>
@@ -569,7 +587,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
     const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
     const int tile = blockIdx.x / NW, wave = blockIdx.x % NW;
     int tm, tn;
-    tile_coords(tile, f.tiles_m, f.tiles_n, tm, tn);
+    tile_coords(tile, f.tiles_m, f.tiles_n, f.group_m, tm, tn);
     const int wm = wave % WAVES_M, wn = wave / WAVES_M;
     const size_t split_stride = (size_t)ntiles * NW * BLOCKS * 4096;
     const char *src0 = static_cast<const char *>(f.part) + (size_t)blockIdx.x * BLOCKS * 4096 + q * 1024 + lane * 16;
@@ -666,6 +684,7 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     p.Npad = round_up(a.N, TILE_ROWS);
     p.tiles_m = ceil_div(a.M, TM);
     p.tiles_n = ceil_div(a.N, TN);
+    p.group_m = strip_height(p.tiles_m, p.tiles_n, TM, TN, OCC);
     p.x_bytes = (unsigned)act_kernel_bytes(a.M, a.K);
     p.w_bytes = (unsigned)(W4 ? w4_codes_bytes(a.N, a.K) : w8_kernel_bytes(a.N, a.K));
     p.wscales = W4 ? reinterpret_cast<const __half *>(static_cast<const char *>(a.wq) + w4_scales_offset(a.N, a.K))
@@ -690,6 +709,7 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     f.N = a.N;
     f.tiles_m = p.tiles_m;
     f.tiles_n = p.tiles_n;
+    f.group_m = p.group_m;
     f.splits = splits;
     hipLaunchKernelGGL((splitk_finish_kernel<WAVES_M, WAVES_N, WM, WN, W4>), dim3(grid * WAVES_M * WAVES_N), dim3(256), 0, st,
                        f);
