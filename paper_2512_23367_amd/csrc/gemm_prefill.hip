@@ -739,7 +739,7 @@ inline SplitPlan plan_split(long tiles, int TM, int TN, int K, int stage_k, doub
     return best;
 }
 
-// variant 0 = automatic choice; 1..5 pick one tile configuration (tests and tuning)
+// variant 0 = automatic choice; other values pick one of the configurations below (tests and tuning)
 template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
 {
@@ -825,49 +825,24 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         if (variant == 200) return launch_one<4, 2, 1, 2, 2, 4, false, EPI_PART>(a, st, splits);
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI_PART, 1, true>(a, st, splits);
     }
-    if ((variant == 5 || variant == 12) && a.K % 128) variant = variant == 5 ? 1 : 4;
     if (variant == 19 && a.K % 128) variant = 13;   // 128-k stages need K % 128 == 0
     switch (variant) {
-    case 1:   // 256x256, 8 wavefronts of 128 tokens x 64 channels, 64 k per stage, 4 stages
-        return launch_one<2, 4, 4, 2, 2, 4, false, EPI>(a, st);
-    case 2:   // 256x256, 8 wavefronts of 64 tokens x 128 channels
-        return launch_one<4, 2, 2, 4, 2, 4, false, EPI>(a, st);
-    case 3:   // 256x256, 4 wavefronts of 128x128
-        return launch_one<2, 2, 4, 4, 2, 4, false, EPI>(a, st);
-    case 4:   // 128x128, 4 wavefronts of 64x64 (two workgroups per CU)
-        return launch_one<2, 2, 2, 2, 2, 4, false, EPI>(a, st);
-    case 5:   // 256x256, 8 wavefronts, 128 k per stage, 2 stages
-        return launch_one<2, 4, 4, 2, 4, 2, false, EPI>(a, st);
-    case 7:   // 256x256, 8 wavefronts of 64 tokens x 128 channels, 128 k per stage, 2 stages
-        return launch_one<4, 2, 2, 4, 4, 2, false, EPI>(a, st);
-    case 11:  // 128x128, 4 wavefronts of 64x64, 3 stages of 64 k: three workgroups per CU
-        return launch_one<2, 2, 2, 2, 2, 3, false, EPI, 3>(a, st);
-    case 12:  // 128x128, 4 wavefronts of 64x64, 2 stages of 128 k: two workgroups per CU
-        return launch_one<2, 2, 2, 2, 4, 2, false, EPI, 2>(a, st);
-    case 6:   // 256x256, 8 wavefronts in two ping-pong groups (one computes while the other fetches), 64-k stages
+    case 6:   // 256x256, 8 wavefronts of 128 tokens x 64 channels in two ping-pong groups (one computes while the other fetches), 64-k stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI, 1, true>(a, st);
     case 15:  // 256 tokens x 192 channels, 8 wavefronts of 64x96 in two ping-pong groups
         return launch_one<4, 2, 2, 3, 2, 4, false, EPI, 1, true>(a, st);
+    case 17:  // 128 tokens x 256 channels, 8 wavefronts of 64x64, ping-pong, 3 stages: two workgroups per CU
+        return launch_one<2, 4, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
     case 19:  // 128x128, two ping-pong groups of 4 wavefronts (64x64 each) that split the k-blocks of every 128-k stage
         return launch_one<2, 2, 2, 2, 4, 3, false, EPI, 1, true, 2>(a, st);
-    case 18:  // 256x256, 16 wavefronts of 64x64 in two ping-pong groups (two wavefronts of each group per SIMD)
-        return launch_one<4, 4, 2, 2, 2, 4, false, EPI, 1, true>(a, st);
-    case 16:  // 256 tokens x 128 channels, 8 wavefronts of 64x64, ping-pong, 3 stages: two workgroups per CU
-        return launch_one<4, 2, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
-    case 17:  // 128 tokens x 256 channels, same
-        return launch_one<2, 4, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
-    case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU)
+    case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU), rotated single-phase loop
         return launch_one<4, 2, 1, 2, 2, 4, false, EPI>(a, st);
+    case 4:   // 128x128, 4 wavefronts of 64x64 (two workgroups per CU)
+        return launch_one<2, 2, 2, 2, 2, 4, false, EPI>(a, st);
+    case 11:  // 128x128, 4 wavefronts of 64x64, 3 stages of 64 k: three workgroups per CU
+        return launch_one<2, 2, 2, 2, 2, 3, false, EPI, 3>(a, st);
     case 20:  // 64 tokens x 64 channels, 4 wavefronts of 32x32, up to four workgroups per CU: few-token shapes
         return launch_one<2, 2, 1, 1, 2, 4, false, EPI, 4>(a, st);
-    case 14:  // 128x128, 8 wavefronts of 64 tokens x 32 channels
-        return launch_one<2, 4, 2, 1, 2, 4, false, EPI>(a, st);
-    case 10:  // 256x256, 4 wavefronts of 128x128, 128 k per stage, 2 stages
-        return launch_one<2, 2, 4, 4, 4, 2, false, EPI>(a, st);
-    case 8:   // 256 tokens x 128 channels, 4 wavefronts of 128x64, two workgroups per CU (independent barriers)
-        return launch_one<2, 2, 4, 2, 2, 3, false, EPI>(a, st);
-    case 9:   // 128 tokens x 256 channels, 4 wavefronts of 64x128, two workgroups per CU
-        return launch_one<2, 2, 2, 4, 2, 3, false, EPI>(a, st);
     default:
         return fail(QL_ERR_UNSUPPORTED, "unknown prefill kernel variant %d", variant);
     }

@@ -93,14 +93,14 @@ def test_weight_quant_int4_bit_exact_and_export(G, N, K):
 
 
 # --------------------------------------------------------------- accumulators
-PREFILL_VARIANTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20]
+PREFILL_VARIANTS = [4, 6, 11, 13, 15, 17, 19, 20]
 SHAPES_ACC = [(64, 512, 512), (100, 192, 200), (300, 1024, 520), (257, 256, 33)]
 
 
 @pytest.mark.parametrize("variant", PREFILL_VARIANTS)
 @pytest.mark.parametrize("M,K,N", SHAPES_ACC)
 def test_w8a8_accumulators_bit_exact_prefill(G, variant, M, K, N):
-    if variant in (5, 7, 10, 12, 19) and K % 128:
+    if variant == 19 and K % 128:
         pytest.skip("this variant stages 128 k at a time (the library falls back to a 64-k variant)")
     rng = np.random.default_rng(M + K + N)
     xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
@@ -208,7 +208,7 @@ def test_split_k_linear_within_tolerance_and_deterministic(G, bits, M, K, N, var
     assert (y1.view(np.uint16) == y2.view(np.uint16)).all()
     # and the unsplit kernels agree to rounding (int8: same integer sums -- tested above -- so at most the last
     # fp32 bit of the dequantized value differs, which moves an fp16 result across a rounding boundary rarely)
-    ql.ql_set_kernel_variant(13 if bits == 8 else 1)
+    ql.ql_set_kernel_variant(13 if bits == 8 else 6)   # int4: any unsplit value selects its one tile kernel
     y0 = G.gpu_linear(x, g, b)
     if bits == 8:
         diff = y1.view(np.uint16) != y0.view(np.uint16)
@@ -229,7 +229,7 @@ def test_w8a8_accumulator_extremes(G):
     assert (np.abs(g["canon"]) == 127).all()
     acc, _ = G.gpu_acc(xq, g)
     assert (acc == oracle.igemm(xq, g["canon"])).all() and abs(int(acc[0, 0])) == 177548032
-    ql.ql_set_kernel_variant(1)
+    ql.ql_set_kernel_variant(6)                            # the same through a prefill tile kernel
     acc, _ = G.gpu_acc(xq, g)
     assert (acc == oracle.igemm(xq, g["canon"])).all()
 
