@@ -295,6 +295,38 @@ def test_decode_linear_with_fused_quantization_matches_two_kernel_path(G, bits, 
     assert G.norm_err(y_fused, ref["y64"]) <= TOL
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        bits = int(rng.choice([8, 4]))
+        M = int(rng.choice([rng.integers(1, 33), rng.integers(33, 200), rng.integers(200, 700)]))
+        N = int(rng.integers(1, 900))
+        K = int(rng.integers(1, 33)) * 128 if bits == 4 else int(rng.integers(1, 65)) * 64   # the interface's K granularity
+        out.append((bits, M, K, N, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("bits,M,K,N,bias", _random_shapes(48, 20251223))
+def test_random_shapes_with_the_automatic_kernel_choice(G, bits, M, K, N, bias):
+    """Seeded random shapes (ragged in every dimension) through whatever the library picks by itself -- decode
+    kernels, every prefill tile configuration, 64x64 tiles, split-K with the workspace's scratch: integer sums
+    bit-exact, fp16 output within tolerance."""
+    x = synth.activations(M, K, 0, "single")
+    w = synth.weights(N, K, 0, "single")
+    b = synth.bias(N, 0, "single") if bias else None
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
+    xq, _ = oracle.quant_act_per_token(x)
+    acc, _ = G.gpu_acc(xq, g)
+    if bits == 8:
+        ref = oracle.linear_w8a8(x, g["canon"], g["scales"], b)
+    else:
+        ref = oracle.linear_w4a8(x, g["canon"], g["scales"], 128, b)
+    assert (acc == ref["acc"]).all()
+    y = G.gpu_linear(x, g, b)
+    assert G.norm_err(y, ref["y64"]) <= TOL
+
+
 def test_config0_end_to_end(G):
     sh = synth.workload(0)[0]
     x, w, _ = synth.tensors(sh)
