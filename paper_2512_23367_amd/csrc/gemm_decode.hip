@@ -451,23 +451,24 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
     // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
     const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101;
-    // few tokens: stage them in LDS (ring slots then hold weights only, more bytes in flight per register)
-    const bool xl = (size_t)(a.M + 1) * a.K <= 24576 && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
-    if (a.x) {   // fp16 tokens: quantize in the prologue (the caller checked decode_fuses_quant)
-        const bool xl_fq = a.M <= FQ_MAX_M && (size_t)(a.M + 1) * a.K <= FQ_MAX_LDS && variant != 121;
-        if (EPI != EPI_F16 || !xl_fq) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
+    // few tokens can be staged in LDS (ring slots then hold weights only).  Measured: it pays for int4 weights
+    // with 8 wavefronts (gate+up at up to 5 tokens 13.5 -> 11.4 us: the short int4 ring no longer shares its
+    // registers with token fragments), makes no difference for int8 weights, and costs 0.7-1.1 us with 16
+    // wavefronts -- so it is used there, and as the vehicle of the fused quantization below.
+    const bool fits = (size_t)(a.M + 1) * a.K <= FQ_MAX_LDS && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
+    if (a.x) {   // fp16 tokens: quantize in the prologue (the caller checked decode_fuses_quant); always 8 wavefronts
+        if (EPI != EPI_F16 || !fits || a.M > FQ_MAX_M) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
         // 16-k pieces of a wavefront's k-range x tokens (rounded up to a power of two) <= 64 lanes x 2 slots
-        const int waves = wide ? 16 : 8;
-        const int pieces = W4 ? 8 * ceil_div(a.K / 128, waves) : 4 * ceil_div(a.K / 64, waves);
+        const int pieces = W4 ? 8 * ceil_div(a.K / 128, 8) : 4 * ceil_div(a.K / 64, 8);
         const int mp = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
         if (pieces * mp > 128) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
         if constexpr (EPI == EPI_F16) {
-            if (wide) return launch_one<W4, 1, 1, EPI, 16, true, 2>(a, st);
             if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, 2>(a, st);
             if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, 2>(a, st);
             return launch_one<W4, 1, 4, EPI, 8, true, 2>(a, st);
         }
     }
+    const bool xl = fits && ((W4 && !wide) || variant == 111 || (variant >= 101 && variant <= 104));
     if (xl) {
         if (wide) return launch_one<W4, 1, 1, EPI, 16, true>(a, st);
         if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true>(a, st);
