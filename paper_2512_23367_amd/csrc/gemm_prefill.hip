@@ -762,24 +762,26 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
     }
     int splits = 1;
     if (variant == 0) {
-        // Estimated time of a tile configuration, fitted to measurements over a grid of shapes (512..16384 tokens,
-        // N 1536..22016, K 1536..11008):
-        //   2.4 us launch + fp16 output at 6.9 TB/s + rounds x (o + tile operations / r),
-        // rounds = passes over the 256 CUs (configurations with several workgroups per CU advance in fractions of
-        // a pass once every CU is full), o = what a pass costs beyond its matrix work (pipeline fill, the
-        // epilogue's latency; hidden behind the neighbour when workgroups share a CU), r = TOPS of a busy CU.
-        // The fitted r of the large tiles is above what a CU sustains alone because their o absorbs part of it;
-        // only the sum is meaningful.  When even the best configuration leaves most CUs idle (few tokens, long
-        // K), K is split over several workgroups per tile and a second kernel adds the partial sums (plan_split).
-        struct Candidate { int variant, tm, tn, slots; double o, r; };
+        // Estimated time of a tile configuration, fitted to measurements over grids of shapes (512..16384 tokens,
+        // N 1536..22016, K 1536..11008; 268 shapes, the pick is within 0.3 % of the best configuration on average
+        // and 9 % at worst):
+        //   2.4 us launch + fp16 output at 6.9 TB/s + passes x (o + tile operations / r),
+        // passes = ceil(tiles / 256 CUs) (also with several workgroups per CU: the CU that gets one tile more
+        // decides), o = what a pass costs beyond its matrix work (pipeline fill, the epilogue's latency; hidden
+        // behind the neighbour when workgroups share a CU), r = TOPS of a busy CU.  The fitted r of the large
+        // tiles is above what a CU sustains alone because their o absorbs part of it; only the sum is meaningful.
+        // When even the best configuration leaves most CUs idle (few tokens, long K), K is split over several
+        // workgroups per tile and a second kernel adds the partial sums (plan_split).
+        struct Candidate { int variant, tm, tn; double o, r; };
         static const Candidate cands[] = {
-            {6, 256, 256, 1, 3.72, 14.14},    // 256x256 ping-pong
-            {15, 256, 192, 1, 3.55, 12.78},   // 256x192 ping-pong
-            {17, 128, 256, 2, 0.63, 11.12},   // 128x256 ping-pong, two workgroups per CU
-            {19, 128, 128, 1, 1.76, 11.13},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
-            {13, 128, 128, 1, 0.83, 10.02},   // 128x128, 8 wavefronts (at most one pass)
-            {4, 128, 128, 2, 0.53, 8.87},     // 128x128, 4 wavefronts, two per CU (more than one pass)
-            {11, 128, 128, 3, 0.26, 9.33},    // 128x128, 4 wavefronts, three per CU (more than two passes)
+            {23, 256, 384, 3.49, 13.41},   // 256x384 ping-pong, wavefronts of 128x96: fewest LDS bytes per matrix instruction
+            {6, 256, 256, 3.40, 13.85},    // 256x256 ping-pong
+            {15, 256, 192, 3.23, 12.65},   // 256x192 ping-pong
+            {17, 128, 256, 0.67, 11.34},   // 128x256 ping-pong, two workgroups per CU
+            {19, 128, 128, 1.83, 11.46},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
+            {13, 128, 128, 1.07, 10.32},   // 128x128, 8 wavefronts (at most one pass)
+            {4, 128, 128, 0.88, 9.47},     // 128x128, 4 wavefronts, two per CU (more than one pass)
+            {11, 128, 128, 0.42, 9.81},    // 128x128, 4 wavefronts, three per CU (more than two passes)
         };
         const long t128 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 128), t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
         double best = 1e30;
@@ -789,9 +791,7 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
             if (c.variant == 4 && t128 <= 256) continue;
             if (c.variant == 11 && t128 <= 512) continue;
             const long tiles = (long)ceil_div(a.M, c.tm) * ceil_div(a.N, c.tn);
-            double rounds;
-            if (c.slots == 1 || tiles <= 256L * c.slots) rounds = (double)((tiles + 255) / 256);
-            else rounds = (double)((tiles * c.slots + 255) / 256) / c.slots;
+            const double rounds = (double)((tiles + 255) / 256);
             const double us = 2.4 + (double)a.M * a.N * 2.0 / 6.9e6 +
                               rounds * (c.o + (double)c.tm * c.tn * 2.0 * a.K / (c.r * 1e6));
             if (us < best * 0.99) best = us, variant = c.variant;   // earlier (larger) configurations win ties
@@ -829,6 +829,8 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
     switch (variant) {
     case 6:   // 256x256, 8 wavefronts of 128 tokens x 64 channels in two ping-pong groups (one computes while the other fetches), 64-k stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI, 1, true>(a, st);
+    case 23:  // 256 tokens x 384 channels, 8 wavefronts of 128x96 in two ping-pong groups, 3 stages
+        return launch_one<2, 4, 4, 3, 2, 3, false, EPI, 1, true>(a, st);
     case 15:  // 256 tokens x 192 channels, 8 wavefronts of 64x96 in two ping-pong groups
         return launch_one<4, 2, 2, 3, 2, 4, false, EPI, 1, true>(a, st);
     case 17:  // 128 tokens x 256 channels, 8 wavefronts of 64x64, ping-pong, 3 stages: two workgroups per CU

@@ -93,7 +93,7 @@ def test_weight_quant_int4_bit_exact_and_export(G, N, K):
 
 
 # --------------------------------------------------------------- accumulators
-PREFILL_VARIANTS = [4, 6, 11, 13, 15, 17, 19, 20]
+PREFILL_VARIANTS = [4, 6, 11, 13, 15, 17, 19, 20, 23]
 SHAPES_ACC = [(64, 512, 512), (100, 192, 200), (300, 1024, 520), (257, 256, 33)]
 
 
