@@ -646,6 +646,148 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Few tokens (33 .. 128), int8 weights: the whole token range is ONE tile high, so a weight byte is needed by
+// exactly one workgroup and the layer is bound by streaming the weights, not by the matrix pipes.  Here a
+// workgroup owns MB token blocks x 96 channels, and its 8 wavefronts split K: wavefront w multiplies k-blocks
+// w, w + 8, ... of the workgroup's k-range with a register tile of MB*32 tokens x 96 channels (MB + 3 KB of
+// operands per 3*MB matrix instructions).  Every wavefront runs its own global -> LDS -> register pipeline on
+// private LDS slots (DEPTH k-blocks deep), so the main loop has no workgroup barrier at all; the wavefronts'
+// exact integer sums meet in LDS at the end, 32 channels at a time, each wavefront finishing an eighth.
+// With fewer than ~200 channel tiles the k-range is also split over workgroups (blockIdx.y), partial sums going
+// through the workspace and the same second kernel as the tile kernels' split-K.
+struct StreamParams {
+    const int8_t *xq;
+    const void *wq;
+    const float *sx;
+    const float *sw;
+    const __half *bias;
+    __half *y;
+    int64_t ldy;
+    int32_t *acc;
+    void *part;
+    int M, N, K;
+    int tiles_n, kb_per_split;
+    unsigned x_bytes, w_bytes;
+};
+
+template <int MB, int WN, int DEPTH, int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_stream_kernel(StreamParams p)
+{
+    constexpr int NW = 8, FR = MB + WN;                  // fragments (1 KiB each) per k-block
+    constexpr int SLOT = FR * 1024;
+    constexpr int UNITS = MB * 4 / NW;                   // (token block, quad) pairs a wavefront finishes per channel block
+    static_assert(MB * 4 % NW == 0, "the reduction hands every wavefront the same number of 1 KiB units");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int tm, tn;
+    tile_coords(blockIdx.x, 1, p.tiles_n, 1, tm, tn);   // same order as the second kernel of split-K
+    const int KB = p.K / 32;
+    const int kb0 = blockIdx.y * p.kb_per_split;
+    const int kb1 = min(KB, kb0 + p.kb_per_split);
+    const int rounds = (kb1 - kb0 - wave + NW - 1) / NW;   // this wavefront's k-blocks: kb0 + wave + 8 r  (may be <= 0)
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, p.x_bytes);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.w_bytes);
+    const unsigned voff = lane * 16;
+    char *mine = smem + wave * (DEPTH * SLOT);
+
+    // token blocks beyond ceil32(M) and channel blocks beyond ceil32(N) lie behind the buffers: they load zeros
+    auto issue = [&](int r) {
+        const bool live = r < rounds;
+        const int kb = kb0 + wave + NW * r;
+        char *slot = mine + (r % DEPTH) * SLOT;
+#pragma unroll
+        for (int j = 0; j < MB; ++j) {
+            unsigned off = ((unsigned)j * KB + kb) * 1024u;
+            if (!live) off = 0xFFFFF000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(slot + j * 1024), 16, voff, off, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < WN; ++i) {
+            unsigned off = ((unsigned)(tn * WN + i) * KB + kb) * 1024u;
+            if (!live) off = 0xFFFFF000u;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(slot + (MB + i) * 1024), 16, voff, off, 0, 0);
+        }
+    };
+
+    v16i acc[WN][MB];
+#pragma unroll
+    for (int i = 0; i < WN; ++i)
+#pragma unroll
+        for (int j = 0; j < MB; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+#pragma unroll
+    for (int r = 0; r < DEPTH - 1; ++r) issue(r);
+    for (int r = 0; r < rounds; ++r) {
+        issue(r + DEPTH - 1);                             // into the slot whose fragments were read in round r - 1
+        wait_vmcnt<(DEPTH - 1) * FR>();                   // round r has landed
+        const char *slot = mine + (r % DEPTH) * SLOT;
+        v4i xf[MB], wf[WN];
+#pragma unroll
+        for (int j = 0; j < MB; ++j) xf[j] = *reinterpret_cast<const v4i *>(slot + j * 1024 + lane * 16);
+#pragma unroll
+        for (int i = 0; i < WN; ++i) wf[i] = *reinterpret_cast<const v4i *>(slot + (MB + i) * 1024 + lane * 16);
+        __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0): the slot may be refilled
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int j = 0; j < MB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
+    }
+    wait_vmcnt<0>();                                      // the dead tail loads
+    __syncthreads();                                      // every wavefront is done with its slots
+
+    // reduction + epilogue, one 32-channel block at a time: red[wavefront][unit][lane] (16 B each)
+    char *red = smem;
+#pragma unroll
+    for (int i = 0; i < WN; ++i) {
+#pragma unroll
+        for (int j = 0; j < MB; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<v4i *>(red + (size_t)((wave * MB + j) * 4 + q) * 1024 + lane * 16) =
+                    v4i{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+        __syncthreads();
+#pragma unroll
+        for (int uu = 0; uu < UNITS; ++uu) {
+            const int u = wave * UNITS + uu, j = u / 4, q = u % 4;
+            v4i sum = v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int v = 0; v < NW; ++v) sum += *reinterpret_cast<const v4i *>(red + (size_t)(v * MB * 4 + u) * 1024 + lane * 16);
+            const int m = j * 32 + (lane & 31);
+            const int n0 = (tn * WN + i) * 32 + 8 * q + 4 * (lane >> 5);
+            if (EPI == EPI_PART) {   // layout of a tile kernel with one wavefront per tile: [split][tile][block i*MB+j][quad][lane]
+                char *dst = static_cast<char *>(p.part) + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * (size_t)(WN * MB * 4096);
+                *reinterpret_cast<v4i *>(dst + ((i * MB + j) * 4 + q) * 1024 + lane * 16) = sum;
+                continue;
+            }
+            if (m >= p.M || n0 >= p.N) continue;
+            if (EPI == EPI_ACC) {
+                for (int e = 0; e < 4 && n0 + e < p.N; ++e) p.acc[(size_t)m * p.N + n0 + e] = sum[e];
+                continue;
+            }
+            const float sxm = p.sx[m];
+            h4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = n0 + e < p.N ? n0 + e : n0;
+                const float b = p.bias ? __half2float(p.bias[n]) : 0.0f;
+                o[e] = (_Float16)__builtin_fmaf((float)sum[e] * sxm, p.sw[n], b);
+            }
+            __half *dst = p.y + (size_t)m * p.ldy + n0;
+            if (n0 + 3 < p.N) {
+                *reinterpret_cast<h4 *>(dst) = o;         // 8 bytes: row starts are 16-byte aligned, n0 % 4 == 0
+            } else {
+                for (int e = 0; e < 4 && n0 + e < p.N; ++e) reinterpret_cast<_Float16 *>(dst)[e] = o[e];
+            }
+        }
+        __syncthreads();                                  // before the next channel block overwrites the area
+    }
+}
+
 // OCC: wavefronts per SIMD the register allocation must leave room for (workgroups per CU x waves / 4)
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false,
           int WK = 1>
@@ -716,6 +858,61 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     return check_hip(hipGetLastError(), "splitk_finish launch");
 }
 
+// Few-token streaming kernel: MB = 2 (up to 64 tokens, 3 k-blocks in flight per wavefront) or 4 (up to 128, 2 in flight)
+template <int MB, int WN, int DEPTH, int EPI>
+int launch_stream(const GemmArgs &a, hipStream_t st, int splits)
+{
+    constexpr int SLOT = (MB + WN) * 1024;
+    constexpr int LDS = 8 * DEPTH * SLOT > 8 * MB * 4096 ? 8 * DEPTH * SLOT : 8 * MB * 4096;
+    static_assert(LDS <= 160 * 1024, "LDS budget");
+    auto kern = gemm_stream_kernel<MB, WN, DEPTH, EPI>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS),
+                         "hipFuncSetAttribute(max dynamic LDS)"));
+        attr_set = true;
+    }
+    StreamParams p;
+    p.xq = a.xq;
+    p.wq = a.wq;
+    p.sx = a.sx;
+    p.sw = a.sw;
+    p.bias = a.bias;
+    p.y = a.y;
+    p.ldy = a.ldy;
+    p.acc = a.acc;
+    p.part = a.ws;
+    p.M = a.M;
+    p.N = a.N;
+    p.K = a.K;
+    p.tiles_n = ceil_div(a.N, WN * 32);
+    p.x_bytes = (unsigned)act_kernel_bytes(a.M, a.K);
+    p.w_bytes = (unsigned)w8_kernel_bytes(a.N, a.K);
+    const int KB = a.K / 32;
+    p.kb_per_split = ceil_div(KB, splits);
+    splits = ceil_div(KB, p.kb_per_split);   // no empty split
+    hipLaunchKernelGGL(kern, dim3(p.tiles_n, splits), dim3(512), LDS, st, p);
+    QL_TRY(check_hip(hipGetLastError(), "gemm_stream launch"));
+    if (EPI != EPI_PART) return QL_OK;
+    FinishParams f;
+    f.part = a.ws;
+    f.sx = a.sx;
+    f.sw = a.sw;
+    f.bias = a.bias;
+    f.y = a.y;
+    f.ldy = a.ldy;
+    f.acc = a.acc;
+    f.M = a.M;
+    f.N = a.N;
+    f.tiles_m = 1;
+    f.tiles_n = p.tiles_n;
+    f.group_m = 1;
+    f.splits = splits;
+    hipLaunchKernelGGL((splitk_finish_kernel<1, 1, MB, WN, false>), dim3(p.tiles_n), dim3(256), 0, st, f);
+    return check_hip(hipGetLastError(), "splitk_finish launch");
+}
+
 // Split-K plan for shapes whose tiles leave most CUs idle: bytes of partial sums per split and the number of
 // splits that minimises  rounds x tile time + partial-sum traffic + second launch  (times in us; rates measured).
 struct SplitPlan {
@@ -739,6 +936,15 @@ inline SplitPlan plan_split(long tiles, int TM, int TN, int K, int stage_k, doub
     return best;
 }
 
+template <int EPI>
+int run_stream(const GemmArgs &a, hipStream_t st, int splits, size_t scratch)
+{
+    const size_t need = splits > 1 ? (size_t)splits * ceil_div(a.N, 96) * 2 * 3 * 4096 : 0;
+    if (need > scratch) return fail(QL_ERR_WORKSPACE, "split-K needs %zu bytes of workspace", need);
+    if (splits > 1) return launch_stream<2, 3, 3, EPI_PART>(a, st, splits);
+    return launch_stream<2, 3, 3, EPI>(a, st, 1);
+}
+
 // variant 0 = automatic choice; other values pick one of the configurations below (tests and tuning)
 template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
@@ -759,6 +965,12 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
             return launch_one<2, 4, 2, 2, 4, 4, true, EPI_PART, 1, true>(a, st, splits);
         }
         return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
+    }
+    if (variant >= 401 && variant <= 432) {   // few-token streaming kernel with 1..32 splits of K over workgroups
+        if (a.M > 64) return fail(QL_ERR_UNSUPPORTED, "the streaming kernel takes at most 64 tokens");
+        int s = variant - 400;
+        if (s > a.K / 256) s = a.K / 256 > 0 ? a.K / 256 : 1;   // at least one k-block per wavefront and split
+        return run_stream<EPI>(a, st, s, scratch);
     }
     int splits = 1;
     if (variant == 0) {
@@ -812,6 +1024,23 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
             const double us64 = std::max(2.4 + (double)a.M * a.N * 2.0 / 6.9e6 + std::max(1.6 + 0.14 * (a.K / 64), per_cu),
                                          2.2 + 1.5 * ((double)a.N * a.K) / 6.8e6);
             if (t64 <= 1024 && us64 < best * 0.95) best = us64, variant = 20, splits = 1;
+        }
+        {
+            // At most 64 tokens, long K, at most one pass of 96-channel tiles: the streaming kernel.  Measured at
+            // K = 4096..11008, N = 1536..22016 it is 0-19 % faster than the best of the kernels above (and 26-43 %
+            // slower with two passes, N = 32000); the estimates above are too coarse for so few tokens, so this
+            // is a rule, not a comparison.  K is split over workgroups when there are few channel tiles and K is
+            // long enough to amortise the second kernel (best split counts measured: 16 tiles 4..8, 43 tiles 4,
+            // 64 tiles 2 from K = 8192, 128 tiles 2 at K = 11008, else 1).
+            const int tiles = ceil_div(a.N, 96);
+            if (a.M <= 64 && a.K >= 4096 && tiles >= 16 && tiles <= 256) {
+                int s = a.K < 6144 ? 1 : (int)(a.K / 2048.0 * 32.0 / tiles * 1.3 + 0.5);
+                if (s > 16) s = 16;
+                if (s > a.K / 1024) s = a.K / 1024;
+                while (s > 1 && ((size_t)s * tiles * 2 * 3 * 4096 > scratch || dump_partials)) --s;
+                if (s < 1) s = 1;
+                return run_stream<EPI>(a, st, s, scratch);
+            }
         }
     } else if (variant >= 202 && variant <= 232) {
         splits = variant - 200, variant = 200;

@@ -188,6 +188,40 @@ def test_w8a8_split_k_accumulators_bit_exact(G, variant, M, K, N):
         G.gpu_acc(xq, g)
 
 
+@pytest.mark.parametrize("variant", [401, 402, 403, 408, 416])
+@pytest.mark.parametrize("M,K,N,bias", [(33, 512, 96, False), (64, 4096, 200, True), (40, 11008, 136, True), (48, 1536, 1000, False),
+                                        (64, 64, 33, True), (57, 8192, 520, False)])
+def test_streaming_kernel_bit_exact_and_within_tolerance(G, variant, M, K, N, bias):
+    """The few-token streaming kernel (one workgroup per 96 channels, its 8 wavefronts splitting K on private
+    pipelines, with 1..16 further splits of K over workgroups): exact integer sums, fp16 output within tolerance
+    and, between split counts, equal up to the rounding of the last step."""
+    import torch
+    x = synth.activations(M, K, 0, "single")
+    w = synth.weights(N, K, 0, "single")
+    b = synth.bias(N, 0, "single") if bias else None
+    g = G.gpu_quant_weight(w, 8, 0)
+    xq, _ = oracle.quant_act_per_token(x)
+    ref = oracle.linear_w8a8(x, g["canon"], g["scales"], b)
+    ws = G.empty_bytes(32 << 20)
+    ql.ql_set_kernel_variant(variant)
+    acc, _ = G.gpu_acc(xq, g, ws=ws)
+    assert (acc == ref["acc"]).all()
+    y = G.gpu_linear(x, g, b, extra_ws=32 << 20)
+    assert G.norm_err(y, ref["y64"]) <= TOL
+    # against the unsplit run: same integer sums, so at most the rounding of the last step differs (the fused
+    # epilogue may round the dequantized value straight to fp16, the second kernel via fp32): rarely, by one ulp
+    ql.ql_set_kernel_variant(401)
+    y1 = G.gpu_linear(x, g, b, extra_ws=32 << 20)
+    diff = y.view(np.uint16) != y1.view(np.uint16)
+    assert diff.mean() < 1e-3
+    assert np.abs(y.astype(np.float64) - y1.astype(np.float64))[diff].max(initial=0) <= \
+        np.spacing(np.abs(y1[diff]).astype(np.float16)).astype(np.float64).max(initial=0)
+    with pytest.raises(ql.QlError):                         # more than 64 tokens: refused, nothing launched
+        ql.ql_set_kernel_variant(variant)
+        G.gpu_acc(np.zeros((65, K), dtype=np.int8), g, ws=ws)
+    ql.ql_set_kernel_variant(0)
+
+
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("M,K,N,variant", [(64, 4096, 200, 204), (100, 1536, 264, 203), (200, 11008, 136, 0),
                                            (48, 4096, 520, 0), (300, 2048, 520, 302)])
