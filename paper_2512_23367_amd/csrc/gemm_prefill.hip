@@ -15,9 +15,13 @@
 // main loop is a ping-pong: the 8 wavefronts form two groups (one wavefront of each per SIMD) that run
 // one phase apart, so that on every SIMD one wavefront issues matrix instructions while the other reads
 // fragments from LDS, issues global loads and (int4) does the vector-ALU work; every phase ends with the
-// workgroup barrier.  Other variants (256x192 tiles, 128x128 tiles with 4 wavefronts or with the two groups
-// splitting the k-blocks of every stage, a rotated single-phase loop) serve shapes whose 256x256 tile count
-// fills the 256 CUs badly, and the tests; the automatic choice compares rounds x tile area / measured rate.
+// workgroup barrier.  Other configurations (256x384, 256x192 and 128x256 tiles, 128x128 tiles with 4 wavefronts or
+// with the two groups splitting the k-blocks of every stage, a rotated single-phase loop) serve shapes whose
+// 256x256 tile count fills the 256 CUs badly or whose N suits wider tiles; the automatic choice compares
+// estimated times fitted to measurements.
+//
+// For 33..64 tokens and long K a different kernel streams the weights once through barrier-free per-wavefront
+// pipelines (gemm_stream_kernel below).
 //
 // W4A8: weight tiles hold nibbles; the unpack (shift + mask, giving 16 * code in each byte) sits
 // between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
