@@ -386,6 +386,31 @@ def main():
                     log("[detail]", json.dumps(row))
                 del base, l
                 torch.cuda.empty_cache()
+        # between decode and prefill: 64 and 256 tokens on the 7B-class shapes (weights rotated as for decode);
+        # these are weight-stream-bound, so the rate is weight bytes per second
+        for base_sh in [s_ for s_ in synth.workload(4) if s_.M == 1]:
+            wbytes = base_sh.N * base_sh.K * base_sh.bits // 8
+            copies = -(-3 * MALL_BYTES // wbytes)
+            base = None
+            for M in (64, 256):
+                sh = synth.Shape(base_sh.config, base_sh.layer, M, base_sh.K, base_sh.N, base_sh.bits, base_sh.group, base_sh.bias)
+                l = Layer(sh, torch, ql, synth, copies if base is None else 1)
+                if base is None:
+                    base = l
+                else:
+                    l.kernels, l.scales, l.sw = base.kernels, base.scales, base.sw
+                l.quant()
+                r = max(50, 2 * copies)
+                t_bb = graph_time_ms(torch, l.gemm, r)
+                t_lin = graph_time_ms(torch, l.linear, r)
+                row = {"shape": sh.name, "gemm_us": round(t_bb * 1e3, 2), "linear_us": round(t_lin * 1e3, 2),
+                       "weight_gbs": round(wbytes / (t_bb * 1e-3) / 1e9, 1),
+                       "frac_hbm_peak": round(wbytes / (t_bb * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                       "weight_copies_rotated": copies}
+                detail.append(row)
+                log("[detail]", json.dumps(row))
+            del base, l
+            torch.cuda.empty_cache()
         # context for the paper's Table 3 (INT8 against FP16 prefill latency, weight memory): the same linears
         # as FP16 GEMMs of the vendor library (torch.matmul -> hipBLASLt/rocBLAS), a comparison system, not
         # part of this library; W8A8 / W4A8 = quantize + GEMM + epilogue through ql_*_linear

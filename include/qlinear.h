@@ -146,7 +146,9 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
                          void *ws, size_t ws_bytes, void *stream);
 
 /* Kernel selection, for tests and tuning (process-wide, not thread-safe):
- *   0 = automatic (decode kernels for M <= 32, otherwise a prefill tile chosen from the shape)
+ *   0 = automatic (decode kernels for M <= 32; up to 1024 tokens whichever of the decode kernels, working on
+ *       blocks of 64 tokens, and the prefill tile kernels has the lower estimated time; prefill tiles beyond)
+ *   1 = automatic among the prefill tile kernels, 100 = automatic among the decode kernels (M <= 1024)
  *   other values pick one implementation; unknown values -> QL_ERR_UNSUPPORTED. */
 int ql_set_kernel_variant(int variant);
 

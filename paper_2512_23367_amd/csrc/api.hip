@@ -28,7 +28,8 @@ int check_hip(hipError_t e, const char *what)
 namespace {
 
 constexpr int MAX_K = 131072;          // 131072 * 127 * 127 < 2^31: no int32 accumulator can overflow
-constexpr int DECODE_MAX_M = 32;
+constexpr int DECODE_MAX_M = 32;           // the decode kernels are the automatic choice up to here,
+constexpr int DECODE_BLOCKED_MAX_M = 1024; // and up to here (in blocks of 64 tokens) when their estimated time is lower
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -96,13 +97,18 @@ int run_gemm(GemmArgs &a, hipStream_t st)
 {
     if (a.M == 0) return QL_OK;
     int variant = g_variant;
-    if (variant == 0 && a.M <= DECODE_MAX_M) variant = 100;
+    if (variant == 0 && (a.M <= DECODE_MAX_M || (a.M <= DECODE_BLOCKED_MAX_M && decode_estimate_us(a) < prefill_estimate_us(a))))
+        variant = 100;
+#ifdef QL_TRACE_DISPATCH
+    fprintf(stderr, "dispatch M=%d N=%d K=%d bits=%d: decode %.1f us, tiles %.1f us -> %d\n", a.M, a.N, a.K, a.bits,
+            decode_estimate_us(a), prefill_estimate_us(a), variant);
+#endif
     if (variant >= 100 && variant < 200) {
-        if (a.M > DECODE_MAX_M)
-            return fail(QL_ERR_UNSUPPORTED, "decode kernels take at most %d tokens (M=%d)", DECODE_MAX_M, a.M);
+        if (a.M > DECODE_BLOCKED_MAX_M)
+            return fail(QL_ERR_UNSUPPORTED, "decode kernels take at most %d tokens (M=%d)", DECODE_BLOCKED_MAX_M, a.M);
         return launch_gemm_decode(a, variant, st);
     }
-    return launch_gemm_prefill(a, variant, st);
+    return launch_gemm_prefill(a, variant == 1 ? 0 : variant, st);   // 1: automatic choice among the tile kernels
 }
 
 int gemm_common(const int8_t *xq, const float *sx, int M, int K, const void *wq, const float *sw, int bits,
@@ -194,10 +200,10 @@ const char *ql_last_error(void) { return g_err; }
 
 int ql_set_kernel_variant(int variant)
 {
-    // 0 automatic; prefill tile configurations; decode configurations; split-K with 2..32 splits on 128x128 / 256x256 tiles
+    // 0 automatic; 1 automatic among the tile kernels; prefill tile configurations; decode configurations; split-K with 2..32 splits on 128x128 / 256x256 tiles
     static const int prefill[] = {4, 6, 11, 13, 15, 17, 19, 20, 23};
-    bool known = variant == 0 || (variant >= 100 && variant <= 104) || variant == 111 || variant == 121 || variant == 130 ||
-                 (variant >= 202 && variant <= 232) || (variant >= 302 && variant <= 332) || (variant >= 401 && variant <= 432);
+    bool known = variant == 0 || variant == 1 || (variant >= 100 && variant <= 104) || variant == 106 || variant == 108 || variant == 111 || variant == 121 || variant == 130 ||
+                 (variant >= 202 && variant <= 232) || (variant >= 302 && variant <= 332);
     for (int v : prefill) known = known || variant == v;
     if (!known)
         return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);

@@ -128,6 +128,9 @@ int launch_probe_mfma(int workgroups, int iters, int random_operands, int *sink,
 int launch_probe_read(const void *buf, size_t bytes, int *sink, hipStream_t st);
 int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st);
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st);
+// estimated time (us) of the automatic choice of the tile kernels / of the decode kernels (33 tokens and more)
+double prefill_estimate_us(const GemmArgs &a);
+double decode_estimate_us(const GemmArgs &a);
 bool decode_fuses_quant(int M, int K, int variant);
 
 }  // namespace ql

@@ -53,7 +53,8 @@ template <bool W4, int MH, int C, int EPI, int WAVES, bool XL, int FQ>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 {
     static_assert(!FQ || (XL && EPI == EPI_F16), "fused quantization stages the tokens in LDS");
-    __shared__ int red[WAVES][C][MH][4][64];
+    constexpr int RH = MH < 2 ? MH : (C > 4 ? 1 : 2);     // token halves that meet in LDS at a time (at most 64 KiB)
+    __shared__ int red[WAVES][C][RH][4][64];
     __shared__ unsigned amax_red[FQ ? WAVES : 1][FQ_MAX_M];
     extern __shared__ __attribute__((aligned(16))) char dyn_lds[];
     // W4A8: the group scales of this workgroup's C*16 channels, [C][K/128][16] fp16, then
@@ -64,12 +65,21 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (MH == 4) {   // more than 64 tokens: blockIdx.y picks 64 of them (two row-blocks of the token tiles)
+        const int t0 = 64 * blockIdx.y;
+        p.xq += (size_t)t0 * p.K;
+        p.sx += t0;
+        p.y += (size_t)t0 * p.ldy;
+        if (p.acc) p.acc += (size_t)t0 * p.N;
+        p.row0 -= t0;
+        p.M = p.M - t0 < 64 ? p.M - t0 : 64;
+    }
     const int rg0 = blockIdx.x * C;               // first group of 16 output channels
     const int r = lane & 15, ch = lane >> 4;      // operand row and 16-k chunk of the 16x16x64 instruction
     const int KB = p.K / 32;
     const int ngroups = p.Npad / 16;
 
-    // token operand: rows 0..15 (and 16..31) of row-block 0; 64 k = two consecutive 32-k tiles.
+    // token operand: rows 0..15 (16..31, then the same of row-block 1); 64 k = two consecutive 32-k tiles.
     // Rows >= M hold nothing: their lanes load nothing, which keeps the L2 traffic at M/16 of the weights'.
     const char *xb = reinterpret_cast<const char *>(p.xq) + (ch / 2) * 1024 + (r + 32 * (ch % 2)) * 16;
     bool xlive[MH];
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const int nchunks = p.K / 64;
         const int per = (nchunks + WAVES - 1) / WAVES;
         const int c0 = wave * per, c1 = (c0 + per < nchunks) ? c0 + per : nchunks;
-        constexpr int U = 8 / C;
+        constexpr int U = C >= 8 ? 1 : 8 / C;
         v4i wv[U][C], xv[XL ? 1 : U][MH];
         auto fetch = [&](int u, int c) {
             if (c < c1) {
@@ -210,7 +220,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                 if (!XL) {
 #pragma unroll
                     for (int h = 0; h < MH; ++h)
-                        xv[u][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb + (size_t)c * 2048 + h * 256)
+                        xv[u][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb + (size_t)(h / 2) * KB * 1024 + (size_t)c * 2048 + (h % 2) * 256)
                                             : v4i{0, 0, 0, 0};
                 }
             }
@@ -260,7 +270,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                     for (int t = 0; t < 2; ++t)
 #pragma unroll
                         for (int h = 0; h < MH; ++h)
-                            xv[u][t][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb4 + ((size_t)4 * g + t) * 1024 + h * 256)
+                            xv[u][t][h] = xlive[h] ? *reinterpret_cast<const v4i *>(xb4 + (size_t)(h / 2) * KB * 1024 + ((size_t)4 * g + t) * 1024 + (h % 2) * 256)
                                                    : v4i{0, 0, 0, 0};
                 }
             }
@@ -339,51 +349,57 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         }
     }
 
-    // add the 8 wavefronts' partial sums (fixed order: the result does not depend on timing)
+    // add the wavefronts' partial sums (fixed order: the result does not depend on timing), RH token halves
+    // at a time; wavefront w finishes channel group w (C <= WAVES)
 #pragma unroll
-    for (int j = 0; j < C; ++j)
+    for (int hb = 0; hb < MH; hb += RH) {
+        if (hb) __syncthreads();                          // the previous halves have been read
 #pragma unroll
-        for (int h = 0; h < MH; ++h)
+        for (int j = 0; j < C; ++j)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                int v;
-                if (!W4) v = acc[j][h][e];
-                else if (EPI == EPI_F16) v = __float_as_int(accf[j][h][e]);
-                else v = tot[j][h][e];
-                red[wave][j][h][e][lane] = v;
+            for (int hh = 0; hh < RH; ++hh)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    int v;
+                    if (!W4) v = acc[j][hb + hh][e];
+                    else if (EPI == EPI_F16) v = __float_as_int(accf[j][hb + hh][e]);
+                    else v = tot[j][hb + hh][e];
+                    red[wave][j][hh][e][lane] = v;
+                }
+        __syncthreads();
+        if (wave < C) {
+            const int j = wave;
+            const int n0 = (rg0 + j) * 16 + 4 * ch;
+#pragma unroll
+            for (int hh = 0; hh < RH; ++hh) {
+                const int h = hb + hh;
+                const int m = r + 16 * h;
+                int si[4] = {0, 0, 0, 0};
+                float sf[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (W4 && EPI == EPI_F16) sf[e] += __int_as_float(red[w][j][hh][e][lane]);
+                        else si[e] += red[w][j][hh][e][lane];
+                    }
+                if (m >= p.M || n0 >= p.N) continue;
+                if (EPI == EPI_ACC) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n0 + e < p.N) p.acc[(size_t)m * p.N + n0 + e] = W4 ? (si[e] >> 4) : si[e];
+                    continue;
+                }
+                const float sxm = e_sx[h];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (n0 + e >= p.N) break;
+                    float v;
+                    if (W4) v = __builtin_fmaf(sf[e], sxm, e_b[e]);
+                    else v = __builtin_fmaf((float)si[e] * sxm, e_sw[e], e_b[e]);
+                    p.y[(size_t)m * p.ldy + n0 + e] = __float2half_rn(v);
+                }
             }
-    __syncthreads();
-    // wavefront w finishes channel group w (C <= WAVES)
-    if (wave >= C) return;
-    const int j = wave;
-    const int n0 = (rg0 + j) * 16 + 4 * ch;
-#pragma unroll
-    for (int h = 0; h < MH; ++h) {
-        const int m = r + 16 * h;
-        int si[4] = {0, 0, 0, 0};
-        float sf[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int w = 0; w < WAVES; ++w)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (W4 && EPI == EPI_F16) sf[e] += __int_as_float(red[w][j][h][e][lane]);
-                else si[e] += red[w][j][h][e][lane];
-            }
-        if (m >= p.M || n0 >= p.N) continue;
-        if (EPI == EPI_ACC) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (n0 + e < p.N) p.acc[(size_t)m * p.N + n0 + e] = W4 ? (si[e] >> 4) : si[e];
-            continue;
-        }
-        const float sxm = e_sx[h];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (n0 + e >= p.N) break;
-            float v;
-            if (W4) v = __builtin_fmaf(sf[e], sxm, e_b[e]);
-            else v = __builtin_fmaf((float)si[e] * sxm, e_sw[e], e_b[e]);
-            p.y[(size_t)m * p.ldy + n0 + e] = __float2half_rn(v);
         }
     }
 }
@@ -422,8 +438,36 @@ int launch_one(const GemmArgs &a, hipStream_t st)
             attr_set = true;
         }
     }
-    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid), dim3(WAVES * 64), xs_bytes, st, p);
+    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid, MH == 4 ? ceil_div(a.M, 64) : 1),
+                       dim3(WAVES * 64), xs_bytes, st, p);
     return check_hip(hipGetLastError(), "gemm_decode launch");
+}
+
+// From 33 tokens on the kernel works on blocks of 64 tokens (blockIdx.y).  Every workgroup pulls its 64 tokens
+// and its C*16 channels over the whole K through its CU's L1 -- measured ~50 GB/s per CU with a ring of at
+// least two fragments per channel group (C <= 4), ~40 GB/s with one (C = 6, 8).  Its registers allow one
+// workgroup per CU, so workgroups beyond 256 run in further passes, each paying its own first round trip to
+// HBM and its reduction (2.5 us): 1 us + passes x (2.5 us + bytes per workgroup / rate).  On 16 layer shapes of
+// 1.5B..70B models at 33..256 tokens the C this picks was the fastest measured one; the time is within ~20 % of
+// the measured one and is what the caller compares with the tile kernels' estimate.
+struct BlockedPlan {
+    int c;
+    double us;
+};
+
+inline BlockedPlan plan_blocked(int M, int N, int K, bool w4)
+{
+    const int groups = round_up(N, TILE_ROWS) / 16, blocks = ceil_div(M, 64);
+    const int tokens = M >= 64 ? 64 : round_up(M, 16);
+    static const int cs[] = {1, 2, 3, 4, 6, 8};
+    BlockedPlan best = {1, 1e30};
+    for (int c : cs) {
+        if (w4 && (c > 4 || (size_t)c * (K / 128) * 32 > 16384)) continue;   // int4: register budget, staged scales
+        const double passes = (double)ceil_div(ceil_div(groups, c) * blocks, 256);
+        const double us = 1.0 + passes * (2.5 + K * ((w4 ? 8.0 : 16.0) * c + tokens) / (c <= 4 ? 50e3 : 40e3));
+        if (us < best.us) best = {c, us};
+    }
+    return best;
 }
 
 // The token fragments are re-read from L2 by every workgroup; their traffic relative to the weight
@@ -441,6 +485,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         // 17..32 tokens: token fragments are 2/C of the bytes a wavefront pulls through its CU's L1, so
         // three channel groups per workgroup as soon as that still leaves one workgroup per CU
         c = groups >= 768 ? 3 : groups >= 512 ? 2 : 1;
+        if (a.M > 32) c = plan_blocked(a.M, a.N, a.K, W4).c;
     }
     if (W4) {   // the staged scales (C * K/128 * 32 bytes of LDS) must stay small
         while (c > 1 && (size_t)c * (a.K / 128) * 32 > 16384) --c;
@@ -449,6 +494,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     if (variant == 102 && (!W4 || (size_t)2 * (a.K / 128) * 32 <= 16384)) c = 2;
     if (variant == 103 && a.M > 16 && (!W4 || (size_t)3 * (a.K / 128) * 32 <= 16384)) c = 3;
     if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
+    if ((variant == 106 || variant == 108) && !W4 && a.M > 32) c = variant - 100;
     // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
     const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101;
     // few tokens can be staged in LDS (ring slots then hold weights only).  Measured: it pays for int4 weights
@@ -481,6 +527,16 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         if (c == 2) return launch_one<W4, 1, 2, EPI, 8>(a, st);
         return launch_one<W4, 1, 4, EPI, 8>(a, st);
     }
+    if (a.M > 32) {
+        if (c == 1) return launch_one<W4, 4, 1, EPI, 8>(a, st);
+        if (c == 2) return launch_one<W4, 4, 2, EPI, 8>(a, st);
+        if (c == 3) return launch_one<W4, 4, 3, EPI, 8>(a, st);
+        if constexpr (!W4) {
+            if (c == 6) return launch_one<W4, 4, 6, EPI, 8>(a, st);
+            if (c == 8) return launch_one<W4, 4, 8, EPI, 8>(a, st);
+        }
+        return launch_one<W4, 4, 4, EPI, 8>(a, st);
+    }
     if (wide) return launch_one<W4, 2, 1, EPI, 16>(a, st);
     if (c == 1) return launch_one<W4, 2, 1, EPI, 8>(a, st);
     if (c == 2) return launch_one<W4, 2, 2, EPI, 8>(a, st);
@@ -501,6 +557,11 @@ bool decode_fuses_quant(int M, int K, int variant)
     const int mp = M <= 1 ? 1 : M <= 2 ? 2 : 4;
     return M >= 1 && M <= FQ_MAX_M && (size_t)(M + 1) * K <= FQ_MAX_LDS && pieces * mp <= 128 && variant != 121 &&
            variant != 130;
+}
+
+double decode_estimate_us(const GemmArgs &a)
+{
+    return plan_blocked(a.M, a.N, a.K, a.bits == 4).us;
 }
 
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st)

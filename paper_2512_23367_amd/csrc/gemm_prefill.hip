@@ -20,8 +20,9 @@
 // 256x256 tile count fills the 256 CUs badly or whose N suits wider tiles; the automatic choice compares
 // estimated times fitted to measurements.
 //
-// For 33..64 tokens and long K a different kernel streams the weights once through barrier-free per-wavefront
-// pipelines (gemm_stream_kernel below).
+// Few tokens (a weight byte is needed by one workgroup only, the layer is bound by streaming the weights) go to
+// the decode kernels instead when their estimated time is lower (prefill_estimate_us below is this file's side
+// of that comparison).
 //
 // W4A8: weight tiles hold nibbles; the unpack (shift + mask, giving 16 * code in each byte) sits
 // between the LDS read and the matrix instruction, and every 128 k the int32 partial is folded into
@@ -650,149 +651,6 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
     }
 }
 
-// ---------------------------------------------------------------------------------------------------------
-// Few tokens (33 .. 128), int8 weights: the whole token range is ONE tile high, so a weight byte is needed by
-// exactly one workgroup and the layer is bound by streaming the weights, not by the matrix pipes.  Here a
-// workgroup owns MB token blocks x 96 channels, and its 8 wavefronts split K: wavefront w multiplies k-blocks
-// w, w + 8, ... of the workgroup's k-range with a register tile of MB*32 tokens x 96 channels (MB + 3 KB of
-// operands per 3*MB matrix instructions).  Every wavefront runs its own global -> LDS -> register pipeline on
-// private LDS slots (DEPTH k-blocks deep), so the main loop has no workgroup barrier at all; the wavefronts'
-// exact integer sums meet in LDS at the end, 32 channels at a time, each wavefront finishing an eighth.
-// With fewer than ~200 channel tiles the k-range is also split over workgroups (blockIdx.y), partial sums going
-// through the workspace and the same second kernel as the tile kernels' split-K.
-struct StreamParams {
-    const int8_t *xq;
-    const void *wq;
-    const float *sx;
-    const float *sw;
-    const __half *bias;
-    __half *y;
-    int64_t ldy;
-    int32_t *acc;
-    void *part;
-    int M, N, K;
-    int tiles_n, kb_per_split;
-    unsigned x_bytes, w_bytes;
-};
-
-template <int MB, int WN, int DEPTH, int EPI>
-__global__ __launch_bounds__(512, 1) void gemm_stream_kernel(StreamParams p)
-{
-    constexpr int NW = 8, FR = MB + WN;                  // fragments (1 KiB each) per k-block
-    constexpr int SLOT = FR * 1024;
-    constexpr int UNITS = MB * 4 / NW;                   // (token block, quad) pairs a wavefront finishes per channel block
-    static_assert(MB * 4 % NW == 0, "the reduction hands every wavefront the same number of 1 KiB units");
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int tm, tn;
-    tile_coords(blockIdx.x, 1, p.tiles_n, 1, tm, tn);   // same order as the second kernel of split-K
-    const int KB = p.K / 32;
-    const int kb0 = blockIdx.y * p.kb_per_split;
-    const int kb1 = min(KB, kb0 + p.kb_per_split);
-    const int rounds = (kb1 - kb0 - wave + NW - 1) / NW;   // this wavefront's k-blocks: kb0 + wave + 8 r  (may be <= 0)
-    const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, p.x_bytes);
-    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.w_bytes);
-    const unsigned voff = lane * 16;
-    char *mine = smem + wave * (DEPTH * SLOT);
-
-    // token blocks beyond ceil32(M) and channel blocks beyond ceil32(N) lie behind the buffers: they load zeros
-    auto issue = [&](int r) {
-        const bool live = r < rounds;
-        const int kb = kb0 + wave + NW * r;
-        char *slot = mine + (r % DEPTH) * SLOT;
-#pragma unroll
-        for (int j = 0; j < MB; ++j) {
-            unsigned off = ((unsigned)j * KB + kb) * 1024u;
-            if (!live) off = 0xFFFFF000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(slot + j * 1024), 16, voff, off, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < WN; ++i) {
-            unsigned off = ((unsigned)(tn * WN + i) * KB + kb) * 1024u;
-            if (!live) off = 0xFFFFF000u;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(slot + (MB + i) * 1024), 16, voff, off, 0, 0);
-        }
-    };
-
-    v16i acc[WN][MB];
-#pragma unroll
-    for (int i = 0; i < WN; ++i)
-#pragma unroll
-        for (int j = 0; j < MB; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
-
-#pragma unroll
-    for (int r = 0; r < DEPTH - 1; ++r) issue(r);
-    for (int r = 0; r < rounds; ++r) {
-        issue(r + DEPTH - 1);                             // into the slot whose fragments were read in round r - 1
-        wait_vmcnt<(DEPTH - 1) * FR>();                   // round r has landed
-        const char *slot = mine + (r % DEPTH) * SLOT;
-        v4i xf[MB], wf[WN];
-#pragma unroll
-        for (int j = 0; j < MB; ++j) xf[j] = *reinterpret_cast<const v4i *>(slot + j * 1024 + lane * 16);
-#pragma unroll
-        for (int i = 0; i < WN; ++i) wf[i] = *reinterpret_cast<const v4i *>(slot + (MB + i) * 1024 + lane * 16);
-        __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0): the slot may be refilled
-#pragma unroll
-        for (int i = 0; i < WN; ++i)
-#pragma unroll
-            for (int j = 0; j < MB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[i], xf[j], acc[i][j], 0, 0, 0);
-    }
-    wait_vmcnt<0>();                                      // the dead tail loads
-    __syncthreads();                                      // every wavefront is done with its slots
-
-    // reduction + epilogue, one 32-channel block at a time: red[wavefront][unit][lane] (16 B each)
-    char *red = smem;
-#pragma unroll
-    for (int i = 0; i < WN; ++i) {
-#pragma unroll
-        for (int j = 0; j < MB; ++j)
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<v4i *>(red + (size_t)((wave * MB + j) * 4 + q) * 1024 + lane * 16) =
-                    v4i{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-        __syncthreads();
-#pragma unroll
-        for (int uu = 0; uu < UNITS; ++uu) {
-            const int u = wave * UNITS + uu, j = u / 4, q = u % 4;
-            v4i sum = v4i{0, 0, 0, 0};
-#pragma unroll
-            for (int v = 0; v < NW; ++v) sum += *reinterpret_cast<const v4i *>(red + (size_t)(v * MB * 4 + u) * 1024 + lane * 16);
-            const int m = j * 32 + (lane & 31);
-            const int n0 = (tn * WN + i) * 32 + 8 * q + 4 * (lane >> 5);
-            if (EPI == EPI_PART) {   // layout of a tile kernel with one wavefront per tile: [split][tile][block i*MB+j][quad][lane]
-                char *dst = static_cast<char *>(p.part) + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * (size_t)(WN * MB * 4096);
-                *reinterpret_cast<v4i *>(dst + ((i * MB + j) * 4 + q) * 1024 + lane * 16) = sum;
-                continue;
-            }
-            if (m >= p.M || n0 >= p.N) continue;
-            if (EPI == EPI_ACC) {
-                for (int e = 0; e < 4 && n0 + e < p.N; ++e) p.acc[(size_t)m * p.N + n0 + e] = sum[e];
-                continue;
-            }
-            const float sxm = p.sx[m];
-            h4 o;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int n = n0 + e < p.N ? n0 + e : n0;
-                const float b = p.bias ? __half2float(p.bias[n]) : 0.0f;
-                o[e] = (_Float16)__builtin_fmaf((float)sum[e] * sxm, p.sw[n], b);
-            }
-            __half *dst = p.y + (size_t)m * p.ldy + n0;
-            if (n0 + 3 < p.N) {
-                *reinterpret_cast<h4 *>(dst) = o;         // 8 bytes: row starts are 16-byte aligned, n0 % 4 == 0
-            } else {
-                for (int e = 0; e < 4 && n0 + e < p.N; ++e) reinterpret_cast<_Float16 *>(dst)[e] = o[e];
-            }
-        }
-        __syncthreads();                                  // before the next channel block overwrites the area
-    }
-}
-
-// OCC: wavefronts per SIMD the register allocation must leave room for (workgroups per CU x waves / 4)
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false,
           int WK = 1>
 int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
@@ -862,91 +720,119 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     return check_hip(hipGetLastError(), "splitk_finish launch");
 }
 
-// Few-token streaming kernel: MB = 2 (up to 64 tokens, 3 k-blocks in flight per wavefront) or 4 (up to 128, 2 in flight)
-template <int MB, int WN, int DEPTH, int EPI>
-int launch_stream(const GemmArgs &a, hipStream_t st, int splits)
-{
-    constexpr int SLOT = (MB + WN) * 1024;
-    constexpr int LDS = 8 * DEPTH * SLOT > 8 * MB * 4096 ? 8 * DEPTH * SLOT : 8 * MB * 4096;
-    static_assert(LDS <= 160 * 1024, "LDS budget");
-    auto kern = gemm_stream_kernel<MB, WN, DEPTH, EPI>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS),
-                         "hipFuncSetAttribute(max dynamic LDS)"));
-        attr_set = true;
-    }
-    StreamParams p;
-    p.xq = a.xq;
-    p.wq = a.wq;
-    p.sx = a.sx;
-    p.sw = a.sw;
-    p.bias = a.bias;
-    p.y = a.y;
-    p.ldy = a.ldy;
-    p.acc = a.acc;
-    p.part = a.ws;
-    p.M = a.M;
-    p.N = a.N;
-    p.K = a.K;
-    p.tiles_n = ceil_div(a.N, WN * 32);
-    p.x_bytes = (unsigned)act_kernel_bytes(a.M, a.K);
-    p.w_bytes = (unsigned)w8_kernel_bytes(a.N, a.K);
-    const int KB = a.K / 32;
-    p.kb_per_split = ceil_div(KB, splits);
-    splits = ceil_div(KB, p.kb_per_split);   // no empty split
-    hipLaunchKernelGGL(kern, dim3(p.tiles_n, splits), dim3(512), LDS, st, p);
-    QL_TRY(check_hip(hipGetLastError(), "gemm_stream launch"));
-    if (EPI != EPI_PART) return QL_OK;
-    FinishParams f;
-    f.part = a.ws;
-    f.sx = a.sx;
-    f.sw = a.sw;
-    f.bias = a.bias;
-    f.y = a.y;
-    f.ldy = a.ldy;
-    f.acc = a.acc;
-    f.M = a.M;
-    f.N = a.N;
-    f.tiles_m = 1;
-    f.tiles_n = p.tiles_n;
-    f.group_m = 1;
-    f.splits = splits;
-    hipLaunchKernelGGL((splitk_finish_kernel<1, 1, MB, WN, false>), dim3(p.tiles_n), dim3(256), 0, st, f);
-    return check_hip(hipGetLastError(), "splitk_finish launch");
-}
-
 // Split-K plan for shapes whose tiles leave most CUs idle: bytes of partial sums per split and the number of
-// splits that minimises  rounds x tile time + partial-sum traffic + second launch  (times in us; rates measured).
+// splits that minimises  fixed + passes x (per_pass + tile time) + partial-sum traffic  (times in us; the
+// parameters are fitted to measurements, see choose_w8).
 struct SplitPlan {
     int splits;
     double us;
 };
 
-inline SplitPlan plan_split(long tiles, int TM, int TN, int K, int stage_k, double tops_per_cu, size_t ws_bytes)
+struct SplitModel {
+    double tops_per_cu, fixed, per_pass, partial_bw;   // partial_bw in TB/s (partial sums are written and read once)
+    bool vs_unsplit;                                   // compare with this model's own unsplit time first
+};
+
+inline SplitPlan plan_split(long tiles, int TM, int TN, int K, int stage_k, const SplitModel &m, size_t ws_bytes)
 {
-    SplitPlan best = {1, 4.0 + (double)((tiles + 255) / 256) * (2.0 * TM * TN * K) / (tops_per_cu * 1e6)};
+    SplitPlan best = {1, m.vs_unsplit ? 4.0 + (double)((tiles + 255) / 256) * (2.0 * TM * TN * K) / (m.tops_per_cu * 1e6) : 1e30};
     const int nstages = K / stage_k;
     for (int s = 2; s <= 32; ++s) {
         if (nstages / s < 4) break;
         const size_t bytes = (size_t)s * tiles * TM * TN * 4;
         if (bytes > ws_bytes) break;
         const double kk = (double)((nstages + s - 1) / s) * stage_k;
-        const double us = 4.0 + (double)((tiles * s + 255) / 256) * (2.0 * TM * TN * kk) / (tops_per_cu * 1e6) + 3.0 +
-                          2.0 * bytes / 4.0e6;
+        const double us = m.fixed + (double)((tiles * s + 255) / 256) * (m.per_pass + (2.0 * TM * TN * kk) / (m.tops_per_cu * 1e6)) +
+                          2.0 * bytes / (m.partial_bw * 1e6);
         if (us < best.us * 0.9) best = {s, us};
     }
     return best;
 }
 
-template <int EPI>
-int run_stream(const GemmArgs &a, hipStream_t st, int splits, size_t scratch)
+// The automatic choice: configuration, split count and the estimated time it was chosen by.
+struct Choice {
+    int variant, splits;
+    double us;
+};
+
+// W4A8 has one tile shape: 128 tokens x 256 channels (equal bytes of both operands per stage), 8 wavefronts of
+// 64x64 in two ping-pong groups, 4 stages of one 128-k scale group each; K is split when the tiles are few.
+inline Choice choose_w4(const GemmArgs &a, size_t scratch, bool dump_partials)
 {
-    const size_t need = splits > 1 ? (size_t)splits * ceil_div(a.N, 96) * 2 * 3 * 4096 : 0;
-    if (need > scratch) return fail(QL_ERR_WORKSPACE, "split-K needs %zu bytes of workspace", need);
-    if (splits > 1) return launch_stream<2, 3, 3, EPI_PART>(a, st, splits);
-    return launch_stream<2, 3, 3, EPI>(a, st, 1);
+    const long tiles = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
+    const SplitModel model = {7.0, 7.0, 0.0, 4.0, true};
+    const SplitPlan plan = plan_split(tiles, 128, 256, a.K, 128, model, tiles < 192 && !dump_partials ? scratch : 0);
+    return {0, plan.splits, plan.us};
+}
+
+// W8A8.  Estimated time of a tile configuration:
+//   2.4 us launch + fp16 output at 6.9 TB/s + passes x (o + tile operations / r),
+// passes = ceil(tiles / 256 CUs) (also with several workgroups per CU: the CU that gets one tile more
+// decides), o = what a pass costs beyond its matrix work (pipeline fill, the epilogue's latency; hidden
+// behind the neighbour when workgroups share a CU), r = TOPS of a busy CU.  The fitted r of the large
+// tiles is above what a CU sustains alone because their o absorbs part of it; only the sum is meaningful.
+// When even the best configuration leaves most CUs idle (few tokens, long K), K is split over several
+// workgroups per tile and a second kernel adds the partial sums (plan_split).
+// Two parameter sets, both fitted to measurements:
+//   * more than 1024 tokens: grids of shapes with 512..16384 tokens, N 1536..22016, K 1536..11008 (268 shapes;
+//     the pick is within 0.3 % of the best configuration on average, 9 % at worst);
+//   * up to 1024 tokens: the weights are read once, from HBM (in a model they are never in a cache when their
+//     layer runs), and the time of a pass is how fast one workgroup can pull its operands -- measured with the
+//     weights rotated through 768 MB on 16 layer shapes of 1.5B..70B models x 9 token counts (pick within
+//     2 % of the best on average, 28 % at worst; the warm-cache parameters gave 4.5 % / 35 % there).
+inline Choice choose_w8(const GemmArgs &a, size_t scratch, bool dump_partials)
+{
+    struct Candidate { int variant, tm, tn; double o, r; };
+    static const Candidate many[] = {
+        {23, 256, 384, 3.49, 13.41},   // 256x384 ping-pong, wavefronts of 128x96: fewest LDS bytes per matrix instruction
+        {6, 256, 256, 3.40, 13.85},    // 256x256 ping-pong
+        {15, 256, 192, 3.23, 12.65},   // 256x192 ping-pong
+        {17, 128, 256, 0.67, 11.34},   // 128x256 ping-pong, two workgroups per CU
+        {19, 128, 128, 1.83, 11.46},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
+        {13, 128, 128, 1.07, 10.32},   // 128x128, 8 wavefronts (at most one pass)
+        {4, 128, 128, 0.88, 9.47},     // 128x128, 4 wavefronts, two per CU (more than one pass)
+        {11, 128, 128, 0.42, 9.81},    // 128x128, 4 wavefronts, three per CU (more than two passes)
+    };
+    static const Candidate few[] = {
+        {23, 256, 384, 6.33, 17.86}, {6, 256, 256, 3.81, 16.38}, {15, 256, 192, 3.50, 14.69}, {17, 128, 256, 1.63, 9.15},
+        {19, 128, 128, 2.13, 7.89},  {13, 128, 128, 0.97, 8.08}, {4, 128, 128, 0.49, 7.71},   {11, 128, 128, 0.0, 7.97},
+    };
+    const bool cold = a.M <= 1024;
+    const Candidate *cands = cold ? few : many;
+    const long t128 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 128), t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
+    Choice best = {0, 1, 1e30};
+    for (int i = 0; i < 8; ++i) {
+        const Candidate &c = cands[i];
+        if (c.variant == 19 && (a.K % 128 != 0 || t128 > 256)) continue;
+        if (c.variant == 13 && t128 > 256) continue;
+        if (c.variant == 4 && t128 <= 256) continue;
+        if (c.variant == 11 && t128 <= 512) continue;
+        const long tiles = (long)ceil_div(a.M, c.tm) * ceil_div(a.N, c.tn);
+        const double rounds = (double)((tiles + 255) / 256);
+        const double us = 2.4 + (double)a.M * a.N * 2.0 / 6.9e6 +
+                          rounds * (c.o + (double)c.tm * c.tn * 2.0 * a.K / (c.r * 1e6));
+        if (us < best.us * 0.99) best = {c.variant, 1, us};   // earlier (larger) configurations win ties
+    }
+    if (scratch && !dump_partials) {
+        const SplitModel m128 = cold ? SplitModel{8.0, 8.0, 0.0, 6.0, false} : SplitModel{8.7, 7.0, 0.0, 4.0, true};
+        const SplitModel m256 = cold ? SplitModel{16.0, 9.0, 2.0, 6.0, false} : SplitModel{10.2, 7.0, 0.0, 4.0, true};
+        const SplitPlan pa = plan_split(t128, 128, 128, a.K, 64, m128, scratch);
+        const SplitPlan pb = plan_split(t256, 256, 256, a.K, 64, m256, scratch);
+        if (pa.splits > 1 && pa.us < best.us * 0.9) best = {200, pa.splits, pa.us};
+        if (pb.splits > 1 && pb.us < best.us * 0.9) best = {300, pb.splits, pb.us};
+    }
+    // 64x64 tiles: four (small) workgroups per CU, so few-token shapes put four times as many workgroups on
+    // the GPU as 128x128.  Alone, such a workgroup streams K at 0.14 us per 64 k whatever its size (latency
+    // bound; 0.2 us when the weights come from HBM); when a CU holds several, each costs 0.8 us + its operations
+    // at 6.5 (4.5) TOPS; and the weights cannot arrive faster than HBM delivers them (measured: 1.5x the plain
+    // stream time).
+    const long t64 = (long)ceil_div(a.M, 64) * ceil_div(a.N, 64);
+    const double per_cu = (double)((t64 + 255) / 256) * (0.8 + 8192.0 * a.K / (cold ? 4.5e6 : 6.5e6));
+    const double lone = cold ? 0.4 + 0.2 * (a.K / 64) : 1.6 + 0.14 * (a.K / 64);
+    const double us64 = std::max(2.4 + (double)a.M * a.N * 2.0 / 6.9e6 + std::max(lone, per_cu),
+                                 2.2 + 1.5 * ((double)a.N * a.K) / 6.8e6);
+    if (t64 <= 1024 && us64 < best.us * 0.95) best = {20, 1, us64};
+    return best;
 }
 
 // variant 0 = automatic choice; other values pick one of the configurations below (tests and tuning)
@@ -957,95 +843,21 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
     const size_t scratch = a.ws ? a.ws_bytes : 0;
     const bool dump_partials = a.partials != nullptr;
     if (W4) {
-        // 128 tokens x 256 channels (equal bytes of both operands per stage), 8 wavefronts of 64x64 in two
-        // ping-pong groups, 4 stages of one 128-k scale group each
-        const long tiles = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
         int splits = 1;
         if (variant >= 202 && variant <= 232) splits = variant - 200;
-        else if (variant == 0 && tiles < 192) splits = plan_split(tiles, 128, 256, a.K, 128, 7.0, scratch).splits;
+        else if (variant == 0) splits = choose_w4(a, scratch, dump_partials).splits;
         if (splits > 1 && EPI == EPI_F16 && !dump_partials) {
+            const long tiles = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
             if ((size_t)splits * tiles * 128 * 256 * 4 > scratch)
                 return fail(QL_ERR_WORKSPACE, "split-K needs %zu bytes of workspace", (size_t)splits * tiles * 128 * 256 * 4);
             return launch_one<2, 4, 2, 2, 4, 4, true, EPI_PART, 1, true>(a, st, splits);
         }
         return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
     }
-    if (variant >= 401 && variant <= 432) {   // few-token streaming kernel with 1..32 splits of K over workgroups
-        if (a.M > 64) return fail(QL_ERR_UNSUPPORTED, "the streaming kernel takes at most 64 tokens");
-        int s = variant - 400;
-        if (s > a.K / 256) s = a.K / 256 > 0 ? a.K / 256 : 1;   // at least one k-block per wavefront and split
-        return run_stream<EPI>(a, st, s, scratch);
-    }
     int splits = 1;
     if (variant == 0) {
-        // Estimated time of a tile configuration, fitted to measurements over grids of shapes (512..16384 tokens,
-        // N 1536..22016, K 1536..11008; 268 shapes, the pick is within 0.3 % of the best configuration on average
-        // and 9 % at worst):
-        //   2.4 us launch + fp16 output at 6.9 TB/s + passes x (o + tile operations / r),
-        // passes = ceil(tiles / 256 CUs) (also with several workgroups per CU: the CU that gets one tile more
-        // decides), o = what a pass costs beyond its matrix work (pipeline fill, the epilogue's latency; hidden
-        // behind the neighbour when workgroups share a CU), r = TOPS of a busy CU.  The fitted r of the large
-        // tiles is above what a CU sustains alone because their o absorbs part of it; only the sum is meaningful.
-        // When even the best configuration leaves most CUs idle (few tokens, long K), K is split over several
-        // workgroups per tile and a second kernel adds the partial sums (plan_split).
-        struct Candidate { int variant, tm, tn; double o, r; };
-        static const Candidate cands[] = {
-            {23, 256, 384, 3.49, 13.41},   // 256x384 ping-pong, wavefronts of 128x96: fewest LDS bytes per matrix instruction
-            {6, 256, 256, 3.40, 13.85},    // 256x256 ping-pong
-            {15, 256, 192, 3.23, 12.65},   // 256x192 ping-pong
-            {17, 128, 256, 0.67, 11.34},   // 128x256 ping-pong, two workgroups per CU
-            {19, 128, 128, 1.83, 11.46},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
-            {13, 128, 128, 1.07, 10.32},   // 128x128, 8 wavefronts (at most one pass)
-            {4, 128, 128, 0.88, 9.47},     // 128x128, 4 wavefronts, two per CU (more than one pass)
-            {11, 128, 128, 0.42, 9.81},    // 128x128, 4 wavefronts, three per CU (more than two passes)
-        };
-        const long t128 = (long)ceil_div(a.M, 128) * ceil_div(a.N, 128), t256 = (long)ceil_div(a.M, 256) * ceil_div(a.N, 256);
-        double best = 1e30;
-        for (const Candidate &c : cands) {
-            if (c.variant == 19 && (a.K % 128 != 0 || t128 > 256)) continue;
-            if (c.variant == 13 && t128 > 256) continue;
-            if (c.variant == 4 && t128 <= 256) continue;
-            if (c.variant == 11 && t128 <= 512) continue;
-            const long tiles = (long)ceil_div(a.M, c.tm) * ceil_div(a.N, c.tn);
-            const double rounds = (double)((tiles + 255) / 256);
-            const double us = 2.4 + (double)a.M * a.N * 2.0 / 6.9e6 +
-                              rounds * (c.o + (double)c.tm * c.tn * 2.0 * a.K / (c.r * 1e6));
-            if (us < best * 0.99) best = us, variant = c.variant;   // earlier (larger) configurations win ties
-        }
-        if (scratch && !dump_partials) {
-            const SplitPlan pa = plan_split(t128, 128, 128, a.K, 64, 8.7, scratch);
-            const SplitPlan pb = plan_split(t256, 256, 256, a.K, 64, 10.2, scratch);
-            if (pa.splits > 1 && pa.us < best * 0.9) best = pa.us, variant = 200, splits = pa.splits;
-            if (pb.splits > 1 && pb.us < best * 0.9) best = pb.us, variant = 300, splits = pb.splits;
-        }
-        {
-            // 64x64 tiles: four (small) workgroups per CU, so few-token shapes put four times as many workgroups on
-            // the GPU as 128x128.  Alone, such a workgroup streams K at ~0.14 us per 64 k whatever its size
-            // (latency bound); when a CU holds several, each costs 0.8 us + its operations at 6.5 TOPS; and
-            // the weights cannot arrive faster than HBM delivers them (measured: 1.5x the plain stream time).
-            const long t64 = (long)ceil_div(a.M, 64) * ceil_div(a.N, 64);
-            const double per_cu = (double)((t64 + 255) / 256) * (0.8 + 8192.0 * a.K / 6.5e6);
-            const double us64 = std::max(2.4 + (double)a.M * a.N * 2.0 / 6.9e6 + std::max(1.6 + 0.14 * (a.K / 64), per_cu),
-                                         2.2 + 1.5 * ((double)a.N * a.K) / 6.8e6);
-            if (t64 <= 1024 && us64 < best * 0.95) best = us64, variant = 20, splits = 1;
-        }
-        {
-            // At most 64 tokens, long K, at most one pass of 96-channel tiles: the streaming kernel.  Measured at
-            // K = 4096..11008, N = 1536..22016 it is 0-19 % faster than the best of the kernels above (and 26-43 %
-            // slower with two passes, N = 32000); the estimates above are too coarse for so few tokens, so this
-            // is a rule, not a comparison.  K is split over workgroups when there are few channel tiles and K is
-            // long enough to amortise the second kernel (best split counts measured: 16 tiles 4..8, 43 tiles 4,
-            // 64 tiles 2 from K = 8192, 128 tiles 2 at K = 11008, else 1).
-            const int tiles = ceil_div(a.N, 96);
-            if (a.M <= 64 && a.K >= 4096 && tiles >= 16 && tiles <= 256) {
-                int s = a.K < 6144 ? 1 : (int)(a.K / 2048.0 * 32.0 / tiles * 1.3 + 0.5);
-                if (s > 16) s = 16;
-                if (s > a.K / 1024) s = a.K / 1024;
-                while (s > 1 && ((size_t)s * tiles * 2 * 3 * 4096 > scratch || dump_partials)) --s;
-                if (s < 1) s = 1;
-                return run_stream<EPI>(a, st, s, scratch);
-            }
-        }
+        const Choice c = choose_w8(a, scratch, dump_partials);
+        variant = c.variant, splits = c.splits;
     } else if (variant >= 202 && variant <= 232) {
         splits = variant - 200, variant = 200;
     } else if (variant >= 302 && variant <= 332) {
@@ -1084,6 +896,14 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
 }
 
 }  // namespace
+
+double prefill_estimate_us(const GemmArgs &a)
+{
+    const size_t scratch = a.ws ? a.ws_bytes : 0;
+    // int4: the plan's times are ~15 % above the measured ones with the weights coming from HBM (16 layer shapes x 9
+    // token counts); they only rank split counts there, here they meet another kernel's estimate
+    return a.bits == 4 ? 0.85 * choose_w4(a, scratch, a.partials != nullptr).us : choose_w8(a, scratch, a.partials != nullptr).us;
+}
 
 int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st)
 {

@@ -70,8 +70,9 @@ def repack_act(xq: np.ndarray) -> torch.Tensor:
     return xk
 
 
-def gpu_acc(xq: np.ndarray, wq, want_partials=False, ws=None):
-    """Raw integer accumulators of the GEMM main loop for host codes xq and a gpu_quant_weight dict."""
+def gpu_acc(xq: np.ndarray, wq, want_partials=False, ws=None, row0=0, nrows=None):
+    """Raw integer accumulators of the GEMM main loop for host codes xq and a gpu_quant_weight dict
+    (int4 with want_partials: also the group partials of tokens row0 .. row0 + nrows - 1, default all)."""
     M, K = xq.shape
     N = wq["N"]
     xk = repack_act(xq)
@@ -81,8 +82,9 @@ def gpu_acc(xq: np.ndarray, wq, want_partials=False, ws=None):
         ql.ql_w8a8_gemm_acc_i32(xk, M, K, wq["kernel"], N, acc, ws)
     else:
         G = K // wq["group"]
-        part = torch.full((M, G, N), -12345, dtype=torch.int32, device=DEV) if want_partials else None
-        ql.ql_w4a8_gemm_acc_i32(xk, M, K, wq["kernel"], wq["group"], N, acc, part, 0, M if want_partials else 0)
+        nrows = M if nrows is None else nrows
+        part = torch.full((nrows, G, N), -12345, dtype=torch.int32, device=DEV) if want_partials else None
+        ql.ql_w4a8_gemm_acc_i32(xk, M, K, wq["kernel"], wq["group"], N, acc, part, row0, nrows if want_partials else 0)
     torch.cuda.synchronize()
     return acc.cpu().numpy(), (part.cpu().numpy() if part is not None else None)
 

@@ -121,12 +121,13 @@ def test_w8a8_accumulators_bit_exact_decode(G, M, K, N):
     assert (acc == oracle.igemm(xq, g["canon"])).all()
 
 
-DECODE_VARIANTS = [101, 102, 103, 104, 111, 121]   # 1/2/3/4 channel groups per workgroup, 16 wavefronts, tokens from L2
+DECODE_VARIANTS = [101, 102, 103, 104, 106, 108, 111, 121]   # 1..8 channel groups per workgroup, 16 wavefronts, tokens from L2
 
 
 @pytest.mark.parametrize("variant", DECODE_VARIANTS)
 @pytest.mark.parametrize("bits", [8, 4])
-@pytest.mark.parametrize("M,K,N", [(1, 1024, 200), (8, 4096, 136), (17, 512, 72), (32, 1536, 200)])
+@pytest.mark.parametrize("M,K,N", [(1, 1024, 200), (8, 4096, 136), (17, 512, 72), (32, 1536, 200), (33, 512, 72),
+                                   (50, 1536, 200), (64, 4096, 136), (130, 1024, 200)])
 def test_decode_variants_bit_exact_and_within_tolerance(G, variant, bits, M, K, N):
     rng = np.random.default_rng(M + K + N + bits)
     xq = rng.integers(-127, 128, (M, K), dtype=np.int8)
@@ -188,43 +189,58 @@ def test_w8a8_split_k_accumulators_bit_exact(G, variant, M, K, N):
         G.gpu_acc(xq, g)
 
 
-@pytest.mark.parametrize("variant", [401, 402, 403, 408, 416])
-@pytest.mark.parametrize("M,K,N,bias", [(33, 512, 96, False), (64, 4096, 200, True), (40, 11008, 136, True), (48, 1536, 1000, False),
-                                        (64, 64, 33, True), (57, 8192, 520, False)])
-def test_streaming_kernel_bit_exact_and_within_tolerance(G, variant, M, K, N, bias):
-    """The few-token streaming kernel (one workgroup per 96 channels, its 8 wavefronts splitting K on private
-    pipelines, with 1..16 further splits of K over workgroups): exact integer sums, fp16 output within tolerance
-    and, between split counts, equal up to the rounding of the last step."""
-    import torch
+@pytest.mark.parametrize("variant", [100, 101, 104, 108])
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M,K,N,bias", [(33, 512, 96, False), (64, 4096, 200, True), (65, 1024, 136, True), (100, 1536, 1000, False),
+                                        (128, 128, 33, True), (300, 2048, 520, False), (1024, 512, 72, True)])
+def test_decode_kernels_on_blocks_of_64_tokens(G, variant, bits, M, K, N, bias):
+    """From 33 tokens on the decode kernels work on blocks of 64 tokens (one grid row each, up to 1024 tokens): exact
+    integer sums (int4: group partials too, for a row window that straddles blocks), fp16 output within tolerance
+    and, for int8, equal to the tile kernels' up to the rounding of the last step."""
     x = synth.activations(M, K, 0, "single")
     w = synth.weights(N, K, 0, "single")
     b = synth.bias(N, 0, "single") if bias else None
-    g = G.gpu_quant_weight(w, 8, 0)
+    g = G.gpu_quant_weight(w, bits, 0 if bits == 8 else 128)
     xq, _ = oracle.quant_act_per_token(x)
-    ref = oracle.linear_w8a8(x, g["canon"], g["scales"], b)
-    ws = G.empty_bytes(32 << 20)
     ql.ql_set_kernel_variant(variant)
-    acc, _ = G.gpu_acc(xq, g, ws=ws)
-    assert (acc == ref["acc"]).all()
-    y = G.gpu_linear(x, g, b, extra_ws=32 << 20)
+    if bits == 8:
+        ref = oracle.linear_w8a8(x, g["canon"], g["scales"], b)
+        acc, _ = G.gpu_acc(xq, g)
+        assert (acc == ref["acc"]).all()
+    else:
+        ref = oracle.linear_w4a8(x, g["canon"], g["scales"], 128, b)
+        _, total, part = oracle.igemm_grouped(xq, oracle.unpack_int4(g["canon"]), g["scales"], 128, want_partials=True)
+        row0 = max(0, min(M - 8, 60))
+        acc, gpart = G.gpu_acc(xq, g, want_partials=True, row0=row0, nrows=min(8, M))
+        assert (acc == total).all() and (gpart == part[row0:row0 + min(8, M)]).all()
+    y = G.gpu_linear(x, g, b)
     assert G.norm_err(y, ref["y64"]) <= TOL
-    # against the unsplit run: same integer sums, so at most the rounding of the last step differs (the fused
-    # epilogue may round the dequantized value straight to fp16, the second kernel via fp32): rarely, by one ulp
-    ql.ql_set_kernel_variant(401)
+    ql.ql_set_kernel_variant(1)
     y1 = G.gpu_linear(x, g, b, extra_ws=32 << 20)
-    diff = y.view(np.uint16) != y1.view(np.uint16)
-    assert diff.mean() < 1e-3
-    assert np.abs(y.astype(np.float64) - y1.astype(np.float64))[diff].max(initial=0) <= \
-        np.spacing(np.abs(y1[diff]).astype(np.float16)).astype(np.float64).max(initial=0)
-    with pytest.raises(ql.QlError):                         # more than 64 tokens: refused, nothing launched
-        ql.ql_set_kernel_variant(variant)
-        G.gpu_acc(np.zeros((65, K), dtype=np.int8), g, ws=ws)
     ql.ql_set_kernel_variant(0)
+    if bits == 8:
+        # same integer sums; the fused epilogues may round the dequantized value differently in its last fp32 bit
+        diff = y.view(np.uint16) != y1.view(np.uint16)
+        assert diff.mean() < 1e-3
+        assert np.abs(y.astype(np.float64) - y1.astype(np.float64))[diff].max(initial=0) <= \
+            np.spacing(np.abs(y1[diff]).astype(np.float16)).astype(np.float64).max(initial=0)
+    else:
+        assert G.norm_err(y, y1.astype(np.float64)) <= 2e-3
+
+
+def test_decode_kernels_refuse_more_than_1024_tokens(G):
+    g = G.gpu_quant_weight(synth.weights(40, 128, 0, "single"), 8, 0)
+    ql.ql_set_kernel_variant(100)
+    try:
+        with pytest.raises(ql.QlError):
+            G.gpu_acc(np.zeros((1025, 128), dtype=np.int8), g)
+    finally:
+        ql.ql_set_kernel_variant(0)
 
 
 @pytest.mark.parametrize("bits", [8, 4])
-@pytest.mark.parametrize("M,K,N,variant", [(64, 4096, 200, 204), (100, 1536, 264, 203), (200, 11008, 136, 0),
-                                           (48, 4096, 520, 0), (300, 2048, 520, 302)])
+@pytest.mark.parametrize("M,K,N,variant", [(64, 4096, 200, 204), (100, 1536, 264, 203), (200, 11008, 136, 1),
+                                           (48, 4096, 520, 1), (300, 2048, 520, 302)])
 def test_split_k_linear_within_tolerance_and_deterministic(G, bits, M, K, N, variant):
     x = synth.activations(M, K, 0, "single")
     w = synth.weights(N, K, 0, "single")
