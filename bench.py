@@ -208,7 +208,7 @@ def main():
     ap.add_argument("--workload", default="config1",
                     help="config1 (default), config2, config3, config4 (long prefill), decode8, decode4 "
                          "(the 7B-class decode GEMMs of config 4, int8 / int4 weights)")
-    ap.add_argument("--decode-m", type=int, default=1, help="tokens of the decode workloads: 1 .. 32")
+    ap.add_argument("--decode-m", type=int, default=1, help="tokens of the decode workloads: 1 .. 1024 (automatic kernel choice: beyond 32 tokens the tile kernels where they are estimated faster)")
     ap.add_argument("--variant", type=int, default=0, help="kernel variant (0 = automatic)")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape table of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
@@ -243,8 +243,8 @@ def main():
     if decode:
         bits = int(args.workload.replace("decode", ""))
         cfg = 4
-        if not 1 <= args.decode_m <= 32:
-            sys.exit("bench.py: --decode-m must be between 1 and 32 (the decode kernels' range)")
+        if not 1 <= args.decode_m <= 1024:
+            sys.exit("bench.py: --decode-m must be between 1 and 1024 (the decode kernels' range)")
         shapes = [synth.Shape(s.config, s.layer, args.decode_m, s.K, s.N, s.bits, s.group, s.bias)
                   for s in synth.workload(4) if s.M == 1 and s.bits == bits]
     else:
