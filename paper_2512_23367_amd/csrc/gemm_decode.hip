@@ -65,14 +65,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    if (MH == 4) {   // more than 64 tokens: blockIdx.y picks 64 of them (two row-blocks of the token tiles)
-        const int t0 = 64 * blockIdx.y;
+    if (MH >= 2) {   // more tokens than the kernel's 16 * MH: blockIdx.y picks a block of them
+        const int t0 = 16 * MH * blockIdx.y;
         p.xq += (size_t)t0 * p.K;
         p.sx += t0;
         p.y += (size_t)t0 * p.ldy;
         if (p.acc) p.acc += (size_t)t0 * p.N;
         p.row0 -= t0;
-        p.M = p.M - t0 < 64 ? p.M - t0 : 64;
+        p.M = p.M - t0 < 16 * MH ? p.M - t0 : 16 * MH;
     }
     const int rg0 = blockIdx.x * C;               // first group of 16 output channels
     const int r = lane & 15, ch = lane >> 4;      // operand row and 16-k chunk of the 16x16x64 instruction
@@ -438,34 +438,41 @@ int launch_one(const GemmArgs &a, hipStream_t st)
             attr_set = true;
         }
     }
-    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid, MH == 4 ? ceil_div(a.M, 64) : 1),
+    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid, MH >= 2 ? ceil_div(a.M, 16 * MH) : 1),
                        dim3(WAVES * 64), xs_bytes, st, p);
     return check_hip(hipGetLastError(), "gemm_decode launch");
 }
 
-// From 33 tokens on the kernel works on blocks of 64 tokens (blockIdx.y).  Every workgroup pulls its 64 tokens
-// and its C*16 channels over the whole K through its CU's L1 -- measured ~50 GB/s per CU with a ring of at
-// least two fragments per channel group (C <= 4), ~40 GB/s with one (C = 6, 8).  Its registers allow one
+// From 33 tokens on the kernels work on blocks of 64 or 32 tokens (blockIdx.y).  Every workgroup pulls its token
+// block and its C*16 channels over the whole K through its CU's L1 -- measured ~50 GB/s per CU with a ring of
+// at least two fragments per channel group (C <= 4), ~40 GB/s with one (C = 6, 8).  Its registers allow one
 // workgroup per CU, so workgroups beyond 256 run in further passes, each paying its own first round trip to
-// HBM and its reduction (2.5 us): 1 us + passes x (2.5 us + bytes per workgroup / rate).  On 16 layer shapes of
-// 1.5B..70B models at 33..256 tokens the C this picks was the fastest measured one; the time is within ~20 % of
-// the measured one and is what the caller compares with the tile kernels' estimate.
+// HBM and its reduction (2.5 us): 1 us + passes x (2.5 us + bytes per workgroup / rate).  Blocks of 32 tokens
+// read the weights twice (the second time from L2) but halve the tokens a workgroup pulls: they win when N is
+// small (N = 4096, 64 tokens: 256 workgroups of 32 channels x 32 tokens instead of 16 x 64).  On 16 layer
+// shapes of 1.5B..70B models at 33..256 tokens the C this picks for blocks of 64 was the fastest measured one;
+// the time is within ~20 % of the measured one and is what the caller compares with the tile kernels' estimate.
 struct BlockedPlan {
-    int c;
+    int block, c;
     double us;
 };
 
-inline BlockedPlan plan_blocked(int M, int N, int K, bool w4)
+inline BlockedPlan plan_blocked(int M, int N, int K, bool w4, int force_block = 0)
 {
-    const int groups = round_up(N, TILE_ROWS) / 16, blocks = ceil_div(M, 64);
-    const int tokens = M >= 64 ? 64 : round_up(M, 16);
+    const int groups = round_up(N, TILE_ROWS) / 16;
     static const int cs[] = {1, 2, 3, 4, 6, 8};
-    BlockedPlan best = {1, 1e30};
-    for (int c : cs) {
-        if (w4 && (c > 4 || (size_t)c * (K / 128) * 32 > 16384)) continue;   // int4: register budget, staged scales
-        const double passes = (double)ceil_div(ceil_div(groups, c) * blocks, 256);
-        const double us = 1.0 + passes * (2.5 + K * ((w4 ? 8.0 : 16.0) * c + tokens) / (c <= 4 ? 50e3 : 40e3));
-        if (us < best.us) best = {c, us};
+    BlockedPlan best = {64, 1, 1e30};
+    for (int block = 64; block >= 32; block /= 2) {
+        if (force_block && block != force_block) continue;
+        const int blocks = ceil_div(M, block);
+        const int tokens = M >= block ? block : round_up(M, 16);
+        for (int c : cs) {
+            if (c > 4 && (w4 || block == 32)) continue;                        // register budget; 32-token kernels have C <= 4
+            if (w4 && (size_t)c * (K / 128) * 32 > 16384) continue;            // int4: staged scales
+            const double passes = (double)ceil_div(ceil_div(groups, c) * blocks, 256);
+            const double us = 1.0 + passes * (2.5 + K * ((w4 ? 8.0 : 16.0) * c + tokens) / (c <= 4 ? 50e3 : 40e3));
+            if (us < best.us) best = {block, c, us};
+        }
     }
     return best;
 }
@@ -485,7 +492,11 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         // 17..32 tokens: token fragments are 2/C of the bytes a wavefront pulls through its CU's L1, so
         // three channel groups per workgroup as soon as that still leaves one workgroup per CU
         c = groups >= 768 ? 3 : groups >= 512 ? 2 : 1;
-        if (a.M > 32) c = plan_blocked(a.M, a.N, a.K, W4).c;
+    }
+    int block = 64;
+    if (a.M > 32) {   // blocks of 64 or 32 tokens; variants 122 / 123 force 32 / 64
+        const BlockedPlan plan = plan_blocked(a.M, a.N, a.K, W4, variant == 122 ? 32 : variant == 123 ? 64 : 0);
+        c = plan.c, block = plan.block;
     }
     if (W4) {   // the staged scales (C * K/128 * 32 bytes of LDS) must stay small
         while (c > 1 && (size_t)c * (a.K / 128) * 32 > 16384) --c;
@@ -496,7 +507,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
     if ((variant == 106 || variant == 108) && !W4 && a.M > 32) c = variant - 100;
     // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
-    const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101;
+    const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101 && a.M <= 32;
     // few tokens can be staged in LDS (ring slots then hold weights only).  Measured: it pays for int4 weights
     // with 8 wavefronts (gate+up at up to 5 tokens 13.5 -> 11.4 us: the short int4 ring no longer shares its
     // registers with token fragments), makes no difference for int8 weights, and costs 0.7-1.1 us with 16
@@ -527,7 +538,8 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         if (c == 2) return launch_one<W4, 1, 2, EPI, 8>(a, st);
         return launch_one<W4, 1, 4, EPI, 8>(a, st);
     }
-    if (a.M > 32) {
+    if (a.M > 32 && block == 32 && c > 4) c = 4;
+    if (a.M > 32 && block == 64) {
         if (c == 1) return launch_one<W4, 4, 1, EPI, 8>(a, st);
         if (c == 2) return launch_one<W4, 4, 2, EPI, 8>(a, st);
         if (c == 3) return launch_one<W4, 4, 3, EPI, 8>(a, st);

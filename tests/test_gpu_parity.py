@@ -189,12 +189,12 @@ def test_w8a8_split_k_accumulators_bit_exact(G, variant, M, K, N):
         G.gpu_acc(xq, g)
 
 
-@pytest.mark.parametrize("variant", [100, 101, 104, 108])
+@pytest.mark.parametrize("variant", [100, 101, 104, 108, 122, 123])   # automatic; 1/4/8 channel groups; blocks of 32/64 tokens
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("M,K,N,bias", [(33, 512, 96, False), (64, 4096, 200, True), (65, 1024, 136, True), (100, 1536, 1000, False),
                                         (128, 128, 33, True), (300, 2048, 520, False), (1024, 512, 72, True)])
 def test_decode_kernels_on_blocks_of_64_tokens(G, variant, bits, M, K, N, bias):
-    """From 33 tokens on the decode kernels work on blocks of 64 tokens (one grid row each, up to 1024 tokens): exact
+    """From 33 tokens on the decode kernels work on blocks of 64 or 32 tokens (one grid row each, up to 1024 tokens): exact
     integer sums (int4: group partials too, for a row window that straddles blocks), fp16 output within tolerance
     and, for int8, equal to the tile kernels' up to the rounding of the last step."""
     x = synth.activations(M, K, 0, "single")
