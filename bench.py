@@ -210,6 +210,9 @@ def main():
                          "(the 7B-class decode GEMMs of config 4, int8 / int4 weights)")
     ap.add_argument("--decode-m", type=int, default=1, help="tokens of the decode workloads: 1 .. 1024 (automatic kernel choice: beyond 32 tokens the tile kernels where they are estimated faster)")
     ap.add_argument("--variant", type=int, default=0, help="kernel variant (0 = automatic)")
+    ap.add_argument("--weight-copies", type=int, default=0,
+                    help="copies of every weight matrix the launches rotate through (0 = enough that the copies of "
+                         "a matrix exceed three times the 256 MB Infinity Cache, i.e. weights come from HBM as in a model)")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-shape table of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--only-step", action="store_true", help="only the timed steps (for profiling)")
@@ -258,8 +261,10 @@ def main():
         descr = (f"config4 decode: {'W8A8' if bits == 8 else 'W4A8 (group 128)'} linears of a 7B-class decoder "
                  f"layer, M={args.decode_m} (qkv, o, gate_up, down), weights rotated over >768 MB of copies")
 
-    def copies_for(s):   # decode: enough copies that the weight stream cannot come from the Infinity Cache
-        return -(-3 * MALL_BYTES // (s.N * s.K // (1 if s.bits == 8 else 2))) if decode else 1
+    def copies_for(s):   # enough copies that the weights cannot come from the Infinity Cache, per matrix:
+        if args.weight_copies:   # the per-layer GEMM timings below rotate one matrix at a time
+            return args.weight_copies
+        return -(-3 * MALL_BYTES // (s.N * s.K // (1 if s.bits == 8 else 2)))
 
     layers = [Layer(s, torch, ql, synth, copies_for(s)) for s in shapes]
     total_ops = sum(s.ops for s in shapes)
@@ -300,7 +305,10 @@ def main():
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic; every launch takes the next of enough copies of its weight matrix that the weights come "
+                "from HBM, not from the 256 MB Infinity Cache" if not args.weight_copies else
+                f"synthetic; {args.weight_copies} cop{'y' if args.weight_copies == 1 else 'ies'} of every weight matrix",
         "launch": "hip graph replay" if decode else "stream launches",
         "config": {"workload": descr, "layers": [s.name for s in shapes],
                    "weights": "int8 per-channel" if shapes[0].bits == 8 else "int4 group-128",
@@ -319,8 +327,9 @@ def main():
         # one event pair around `reps` back-to-back launches: per-launch pairs add ~2-7 us of event
         # overhead to kernels this short and would not agree with the profiler's kernel durations
         timer = graph_time_ms if decode else best_time_ms
-        gemm_ms.append(timer(torch, l.gemm, reps))
-        gemm_ms_b2b.append(best_time_ms(torch, l.gemm, reps, per_launch=True, warm=0, rounds=1))
+        reps_l = max(reps, len(l.kernels))   # at least one cycle through the weight copies
+        gemm_ms.append(timer(torch, l.gemm, reps_l))
+        gemm_ms_b2b.append(best_time_ms(torch, l.gemm, reps_l, per_launch=True, warm=0, rounds=1))
         # the quantizer runs 2-10 us: replay it from a HIP graph, or the launch path is what gets timed
         quant_ms.append(graph_time_ms(torch, lambda i, l=l: l.quant(), reps))
     achieved = total_ops / (sum(gemm_ms) * 1e-3) / 1e12
@@ -363,14 +372,14 @@ def main():
             for (layer, K, N, bits, _), shs in groups.items():
                 wbytes = N * K // (1 if bits == 8 else 2)
                 decode = shs[0].M <= 32
-                copies = -(-3 * MALL_BYTES // wbytes) if decode else 1
+                copies = -(-3 * MALL_BYTES // wbytes)
                 base = Layer(shs[0], torch, ql, synth, copies)
                 for sh in shs:
                     l = base if sh is shs[0] else Layer(sh, torch, ql, synth, 1)
                     if l is not base:
                         l.kernels, l.scales, l.sw = base.kernels, base.scales, base.sw
                     l.quant()
-                    r = 20 if not decode else max(50, 2 * copies)
+                    r = max(20, copies) if not decode else max(50, 2 * copies)   # at least one cycle through the copies
                     timer = graph_time_ms if decode else best_time_ms
                     t_bb = timer(torch, l.gemm, r)
                     t_lin = timer(torch, l.linear, r, warm=3, rounds=2)
@@ -381,7 +390,7 @@ def main():
                     else:
                         row["gbs"] = round(l.gemm_bytes() / (t_bb * 1e-3) / 1e9, 1)
                         row["frac_hbm_peak"] = round(row["gbs"] / PEAK_HBM_GBS, 4)
-                        row["weight_copies_rotated"] = copies
+                    row["weight_copies_rotated"] = copies
                     detail.append(row)
                     log("[detail]", json.dumps(row))
                 del base, l
