@@ -880,8 +880,9 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<4, 2, 2, 3, 2, 4, false, EPI, 1, true>(a, st);
     case 17:  // 128 tokens x 256 channels, 8 wavefronts of 64x64, ping-pong, 3 stages: two workgroups per CU
         return launch_one<2, 4, 2, 2, 2, 3, false, EPI, 2, true>(a, st);
-    case 19:  // 128x128, two ping-pong groups of 4 wavefronts (64x64 each) that split the k-blocks of every 128-k stage
-        return launch_one<2, 2, 2, 2, 4, 3, false, EPI, 1, true, 2>(a, st);
+    case 19:  // 128x128, two ping-pong groups of 4 wavefronts (64x64 each) that split the k-blocks of every 128-k stage;
+              // 4 stages (96 KB in flight per workgroup: 3-5 % faster than 3 when the weights come from HBM)
+        return launch_one<2, 2, 2, 2, 4, 4, false, EPI, 1, true, 2>(a, st);
     case 13:  // 128x128, 8 wavefronts of 32 tokens x 64 channels (two per SIMD with one workgroup per CU), rotated single-phase loop
         return launch_one<4, 2, 1, 2, 2, 4, false, EPI>(a, st);
     case 4:   // 128x128, 4 wavefronts of 64x64 (two workgroups per CU)
