@@ -152,6 +152,24 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
  *   other values pick one implementation; unknown values -> QL_ERR_UNSUPPORTED. */
 int ql_set_kernel_variant(int variant);
 
+/* What the automatic choice launches for a GEMM of this shape, and the time estimate it goes by (host
+ * arithmetic only: no GPU call, no allocation; usable for scheduling and for tests of the choice).
+ *   scratch_bytes  the split-K scratch the GEMM would get: the ws_bytes of ql_*_gemm, or the part of the
+ *                  workspace of ql_*_linear that lies behind ql_act_kernel_bytes + scales (0: none)
+ *   plan           host struct, filled on QL_OK
+ * Errors: the shape errors of the GEMMs; QL_ERR_NULL for plan == NULL; QL_ERR_SHAPE for M == 0. */
+enum { QL_FAMILY_DECODE = 1, QL_FAMILY_TILE = 2 };
+typedef struct ql_plan {
+    int family;         /* QL_FAMILY_DECODE: weight-streaming kernels (every workgroup owns tile_channels channels and
+                           the whole K for a block of tile_tokens tokens); QL_FAMILY_TILE: prefill tile kernels */
+    int variant;        /* the ql_set_kernel_variant value closest to this choice (0: int4 tiles, which have one shape) */
+    int tile_tokens;    /* tokens x channels one workgroup owns */
+    int tile_channels;
+    int splits;         /* workgroups sharing one tile's K range (1: unsplit; > 1 needs the scratch) */
+    double est_us;      /* the estimate the choice was made by, microseconds (model fitted to measurements on MI355X) */
+} ql_plan;
+int ql_plan_gemm(int M, int N, int K, int bits, int group, size_t scratch_bytes, ql_plan *plan);
+
 /* ---- The two enhanced W4A8 configurations of the paper (usable with int8 weights as well) -------------------
  * SmoothQuant (Eq. 3): Y = (X S^-1)(S W), s_j = max|X_j|^alpha / max|W_j|^(1-alpha) per input channel j.
  * Hadamard (Eq. 4):    Y = (X H)(H^T W), H a normalized Hadamard matrix: here the natural-order (Sylvester)

@@ -22,7 +22,7 @@ EXPORTS = [
     "ql_version", "ql_last_error", "ql_weight_bytes", "ql_act_kernel_bytes", "ql_workspace_bytes",
     "ql_quant_act_per_token", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
     "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
-    "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant",
+    "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant", "ql_plan_gemm",
     "ql_probe_mfma_int8", "ql_probe_hbm_read",
     "ql_hadamard_block", "ql_smooth_calibrate", "ql_smooth_scales",
     "ql_quant_act_per_token_transformed", "ql_quant_weight_transformed",
@@ -30,6 +30,15 @@ EXPORTS = [
 ]
 
 QL_RANGE_SYMMETRIC, QL_RANGE_EQ2 = 0, 1
+QL_FAMILY_DECODE, QL_FAMILY_TILE = 1, 2
+
+
+class QlPlan(ctypes.Structure):
+    """Mirror of the C struct ql_plan."""
+    _fields_ = [("family", ctypes.c_int), ("variant", ctypes.c_int), ("tile_tokens", ctypes.c_int),
+                ("tile_channels", ctypes.c_int), ("splits", ctypes.c_int), ("est_us", ctypes.c_double)]
+
+
 QL_SCOPE_FINE, QL_SCOPE_TENSOR, QL_SCOPE_STATIC = 0, 1, 2
 
 
@@ -60,6 +69,7 @@ def lib() -> ctypes.CDLL:
         l.ql_last_error.argtypes = []
         sigs = {
             "ql_set_kernel_variant": [i],
+            "ql_plan_gemm": [i, i, i, i, i, sz, c.POINTER(QlPlan)],
             "ql_weight_bytes": [i, i, i, i, szp, szp, szp],
             "ql_act_kernel_bytes": [i, i, szp],
             "ql_workspace_bytes": [i, i, i, i, szp],
@@ -126,6 +136,13 @@ def ql_last_error() -> str:
 
 def ql_set_kernel_variant(variant: int):
     _check(lib().ql_set_kernel_variant(variant))
+
+
+def ql_plan_gemm(M: int, N: int, K: int, bits: int, group: int, scratch_bytes: int = 0) -> QlPlan:
+    """What the automatic choice launches for this GEMM shape and the estimate it goes by (host only)."""
+    plan = QlPlan()
+    _check(lib().ql_plan_gemm(M, N, K, bits, group, scratch_bytes, ctypes.byref(plan)))
+    return plan
 
 
 def ql_probe_mfma_int8(workgroups: int, iters: int, random_operands: bool, sink) -> int:

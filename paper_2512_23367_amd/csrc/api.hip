@@ -93,12 +93,17 @@ int check_out(const void *y, int64_t ldy, int N)
     return QL_OK;
 }
 
+// automatic choice between the two kernel families
+bool decode_family(const GemmArgs &a)
+{
+    return a.M <= DECODE_MAX_M || (a.M <= DECODE_BLOCKED_MAX_M && decode_estimate_us(a) < prefill_estimate_us(a));
+}
+
 int run_gemm(GemmArgs &a, hipStream_t st)
 {
     if (a.M == 0) return QL_OK;
     int variant = g_variant;
-    if (variant == 0 && (a.M <= DECODE_MAX_M || (a.M <= DECODE_BLOCKED_MAX_M && decode_estimate_us(a) < prefill_estimate_us(a))))
-        variant = 100;
+    if (variant == 0 && decode_family(a)) variant = 100;
 #ifdef QL_TRACE_DISPATCH
     fprintf(stderr, "dispatch M=%d N=%d K=%d bits=%d: decode %.1f us, tiles %.1f us -> %d\n", a.M, a.N, a.K, a.bits,
             decode_estimate_us(a), prefill_estimate_us(a), variant);
@@ -208,6 +213,35 @@ int ql_set_kernel_variant(int variant)
     if (!known)
         return fail(QL_ERR_UNSUPPORTED, "unknown kernel variant %d", variant);
     g_variant = variant;
+    return QL_OK;
+}
+
+int ql_plan_gemm(int M, int N, int K, int bits, int group, size_t scratch_bytes, ql_plan *plan)
+{
+    QL_TRY(check_bits(bits, group));
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_nk(N, K, bits));
+    if (!plan) return fail(QL_ERR_NULL, "plan is NULL");
+    if (M == 0) return fail(QL_ERR_SHAPE, "M must be at least 1");
+    GemmArgs a = {};
+    a.M = M, a.N = N, a.K = K, a.bits = bits, a.group = group;
+    a.ws = scratch_bytes ? reinterpret_cast<void *>(256) : nullptr;   // only tested against NULL while planning
+    a.ws_bytes = scratch_bytes;
+    *plan = ql_plan{};
+    if (decode_family(a)) {
+        int block = 0, c = 0;
+        decode_plan(a, &block, &c);
+        plan->family = QL_FAMILY_DECODE;
+        plan->variant = 100 + c;
+        plan->tile_tokens = block;
+        plan->tile_channels = 16 * c;
+        plan->splits = 1;
+        plan->est_us = decode_estimate_us(a);
+    } else {
+        plan->family = QL_FAMILY_TILE;
+        prefill_plan(a, &plan->variant, &plan->tile_tokens, &plan->tile_channels, &plan->splits);
+        plan->est_us = prefill_estimate_us(a);
+    }
     return QL_OK;
 }
 

@@ -131,6 +131,9 @@ int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st);
 // estimated time (us) of the automatic choice of the tile kernels / of the decode kernels (33 tokens and more)
 double prefill_estimate_us(const GemmArgs &a);
 double decode_estimate_us(const GemmArgs &a);
+// what the automatic choice would launch (host only)
+void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_channels, int *splits);
+void decode_plan(const GemmArgs &a, int *token_block, int *channel_groups);
 bool decode_fuses_quant(int M, int K, int variant);
 
 }  // namespace ql

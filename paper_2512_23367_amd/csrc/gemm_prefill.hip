@@ -906,6 +906,29 @@ double prefill_estimate_us(const GemmArgs &a)
     return a.bits == 4 ? 0.85 * choose_w4(a, scratch, a.partials != nullptr).us : choose_w8(a, scratch, a.partials != nullptr).us;
 }
 
+void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_channels, int *splits)
+{
+    const size_t scratch = a.ws ? a.ws_bytes : 0;
+    if (a.bits == 4) {
+        *splits = choose_w4(a, scratch, a.partials != nullptr).splits;
+        *variant = *splits > 1 ? 200 + *splits : 0;
+        *tile_tokens = 128, *tile_channels = 256;
+        return;
+    }
+    Choice c = choose_w8(a, scratch, a.partials != nullptr);
+    if (c.variant == 19 && a.K % 128) c.variant = 13;
+    *splits = c.splits;
+    *variant = c.variant == 200 || c.variant == 300 ? c.variant + c.splits : c.variant;
+    switch (c.variant) {
+    case 23: *tile_tokens = 256, *tile_channels = 384; break;
+    case 6: case 300: *tile_tokens = 256, *tile_channels = 256; break;
+    case 15: *tile_tokens = 256, *tile_channels = 192; break;
+    case 17: *tile_tokens = 128, *tile_channels = 256; break;
+    case 20: *tile_tokens = 64, *tile_channels = 64; break;
+    default: *tile_tokens = 128, *tile_channels = 128; break;
+    }
+}
+
 int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st)
 {
     if (a.M == 0) return QL_OK;

@@ -90,6 +90,7 @@ def test_header_is_plain_c_and_a_c_program_links(tmp_path):
         "int main(void) {\n"
         "    size_t canon = 0, scales = 0, kernel = 0, ws = 0;\n"
         "    int block = 0;\n"
+        "    ql_plan plan;\n"
         "    if (ql_version() < 100) return 1;\n"
         "    if (ql_weight_bytes(4096, 4096, 4, 128, &canon, &scales, &kernel) != QL_OK) return 2;\n"
         "    if (canon != (size_t)4096 * 2048 || scales != (size_t)4096 * 32 * 2 || kernel < canon + 2 * scales) return 3;\n"
@@ -97,6 +98,8 @@ def test_header_is_plain_c_and_a_c_program_links(tmp_path):
         "    if (ql_hadamard_block(11008, &block) != QL_OK || block != 256) return 5;\n"
         "    if (ql_weight_bytes(10, 100, 8, 0, &canon, &scales, &kernel) != QL_ERR_SHAPE) return 6;\n"
         '    if (ql_last_error()[0] == 0) return 7;\n'
+        "    if (ql_plan_gemm(1, 4096, 4096, 8, 0, 0, &plan) != QL_OK || plan.family != QL_FAMILY_DECODE) return 8;\n"
+        "    if (ql_plan_gemm(4096, 4096, 4096, 8, 0, 0, &plan) != QL_OK || plan.family != QL_FAMILY_TILE || plan.est_us <= 0) return 9;\n"
         '    printf("ok %d\\n", ql_version());\n'
         "    return 0;\n}\n")
     exe = tmp_path / "use_abi"
