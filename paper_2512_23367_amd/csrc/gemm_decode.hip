@@ -1,12 +1,13 @@
-// Decode-shaped GEMM (at most 32 tokens) + dequantization epilogue of the W8A8 / W4A8 linear layer
-// for gfx950.  Same arithmetic as the prefill kernel (integer accumulation, Y = XW, per-token and
+// Weight-streaming GEMM + dequantization epilogue of the W8A8 / W4A8 linear layer for gfx950: the decode
+// shapes (up to 32 tokens per call) and, in blocks of 64 or 32 tokens, up to 1024 tokens where that is faster than
+// the prefill tile kernels.  Same arithmetic as the prefill kernel (integer accumulation, Y = XW, per-token and
 // per-channel / per-group scales), but the time goes into streaming the weights from HBM once, so:
-//   * one workgroup owns 16 output channels and the whole K; its 8 (or 16) wavefronts split K and add their
+//   * one workgroup owns 16 C output channels (C = 1..8) and the whole K; its 8 (or 16) wavefronts split K and add their
 //     exact integer (W8A8) or fp32 (W4A8) partial sums through LDS -- no atomics, no second pass;
 //   * weight fragments go global -> registers with 16-byte loads per lane, a ring of them in flight
 //     per wavefront, straight into the 16x16x64 int8 matrix instruction (int4: after a shift/mask
 //     unpack); nothing is reused, so nothing is staged in LDS;
-//   * the (at most 32) quantized tokens are re-read from L2 in the same tile order, or staged in LDS when
+//   * the quantized tokens (of the workgroup's block) are re-read from L2 in the same tile order, or staged in LDS when
 //     they are few; for up to four tokens the linear-layer entry points skip the separate quantization
 //     kernel and every workgroup quantizes the fp16 tokens itself on the way into LDS (paper Eq. 1-2,
 //     same arithmetic as the stand-alone quantizer), while its first weight fragments are in flight.
