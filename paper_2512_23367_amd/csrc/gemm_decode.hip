@@ -69,8 +69,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     if (MH >= 2) {   // more tokens than the kernel's 16 * MH: blockIdx.y picks a block of them
         const int t0 = 16 * MH * blockIdx.y;
         p.xq += (size_t)t0 * p.K;
-        p.sx += t0;
-        p.y += (size_t)t0 * p.ldy;
+        if (p.sx) p.sx += t0;
+        if (p.y) p.y += (size_t)t0 * p.ldy;
         if (p.acc) p.acc += (size_t)t0 * p.N;
         p.row0 -= t0;
         p.M = p.M - t0 < 16 * MH ? p.M - t0 : 16 * MH;
