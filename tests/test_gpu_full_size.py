@@ -77,6 +77,22 @@ def test_config4_decode(G, sh):
     _check_shape(G, sh)
 
 
+def _few_token_shapes():
+    out = []
+    for s in synth.workload(4):
+        if s.M == 1:
+            for M in (64, 256):
+                out.append(synth.Shape(s.config, s.layer, M, s.K, s.N, s.bits, s.group, s.bias))
+    return out
+
+
+@pytest.mark.parametrize("sh", _few_token_shapes(), ids=lambda s: s.name)
+def test_config4_few_tokens(G, sh):
+    """64 and 256 tokens on the 7B shapes (the benchmark's few-token detail rows): the automatic choice between
+    the decode kernels on token blocks and the tile kernels, every sampled row against the oracle."""
+    _check_shape(G, sh)
+
+
 def test_config4_long_prefill_accumulators(G):
     """M=16384 down projection: integer accumulators of sampled rows, bit-exact, plus the fp16 layer."""
     sh = [s for s in synth.workload(4) if s.M > 32][0]
