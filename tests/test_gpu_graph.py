@@ -44,7 +44,9 @@ def _replay_and_compare(torch, enqueue, outputs):
                                    (128, 11008, 512),     # split-K: two kernels, partial sums in the workspace
                                    (2, 4096, 520),        # decode with the quantizer fused into the GEMM
                                    (8, 4096, 520),        # decode behind the separate quantizer
-                                   (24, 1536, 4608)])     # decode, 17..32 tokens
+                                   (24, 1536, 4608),      # decode, 17..32 tokens
+                                   (64, 4096, 520),       # decode kernels on token blocks (33 tokens and more)
+                                   (200, 2048, 1000)])    # the same, several blocks
 def test_linear_layer_in_a_graph(G, bits, M, K, N):
     import torch
     x = G.dev(synth.activations(M, K, 0, "single"))
