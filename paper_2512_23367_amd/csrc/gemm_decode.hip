@@ -574,7 +574,7 @@ inline BlockedPlan plan_blocked(int M, int N, int K, bool w4, int force_block = 
         const int blocks = ceil_div(M, block);
         const int tokens = M >= block ? block : round_up(M, 16);
         for (int c : cs) {
-            if (c > 4 && (w4 || block == 32)) continue;                        // register budget; 32-token kernels have C <= 4
+            if (c > 4 && (w4 || block == 32)) continue;   // int4: register budget; 32-token kernels: 6 or 8 measured no faster
             if (w4 && (size_t)c * (K / 128) * 32 > 16384) continue;            // int4: staged scales
             const double passes = (double)ceil_div(ceil_div(groups, c) * blocks, 256);
             const double us = 1.0 + passes * (2.5 + K * ((w4 ? 8.0 : 16.0) * c + tokens) / (c <= 4 ? 50e3 : 40e3));
@@ -595,9 +595,9 @@ inline void auto_shape(int M, int N, int K, bool w4, int force_block, int &block
         block = 16, c = 2;
         while (c > 1 && ceil_div(groups, c) < 320) c /= 2;
     } else if (M <= 32) {
-        // 17..32 tokens: token fragments are 2/C of the bytes a wavefront pulls through its CU's L1, so
-        // three channel groups per workgroup as soon as that still leaves one workgroup per CU
-        block = 32, c = groups >= 768 ? 3 : groups >= 512 ? 2 : 1;
+        // 17..32 tokens: one block of 32 in the same model as the larger token counts (measured at 20 and 32 tokens on
+        // five wide layers: the C it picks was the fastest of those tried, up to 27 % ahead of a fixed rule by N)
+        block = 32, c = plan_blocked(M, N, K, w4, 32).c;
     } else {   // blocks of 64 or 32 tokens
         const BlockedPlan plan = plan_blocked(M, N, K, w4, force_block);
         c = plan.c, block = plan.block;
@@ -617,7 +617,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     if (variant == 102 && (!W4 || (size_t)2 * (a.K / 128) * 32 <= 16384)) c = 2;
     if (variant == 103 && a.M > 16 && (!W4 || (size_t)3 * (a.K / 128) * 32 <= 16384)) c = 3;
     if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
-    if ((variant == 106 || variant == 108) && !W4 && a.M > 32) c = variant - 100;
+    if ((variant == 106 || variant == 108) && !W4 && a.M > 32 && block == 64) c = variant - 100;
     // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
     const bool wide = c == 1 && (groups <= 256 || variant == 111) && variant != 101 && a.M <= 32;
     // few tokens can be staged in LDS (ring slots then hold weights only).  Measured: it pays for int4 weights
@@ -650,7 +650,6 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         if (c == 2) return launch_one<W4, 1, 2, EPI, 8>(a, st);
         return launch_one<W4, 1, 4, EPI, 8>(a, st);
     }
-    if (a.M > 32 && block == 32 && c > 4) c = 4;
     if (a.M > 32 && block == 64) {
         if (c == 1) return launch_one<W4, 4, 1, EPI, 8>(a, st);
         if (c == 2) return launch_one<W4, 4, 2, EPI, 8>(a, st);
