@@ -88,3 +88,33 @@ def fwht_blocks(v: np.ndarray, block: int) -> np.ndarray:
         h *= 2
     norm = F32(1.0 / np.sqrt(float(block)))
     return (a * norm).astype(F32).reshape(v.shape)
+
+
+def rmsnorm_act(x16: np.ndarray, gamma16: np.ndarray, eps: float) -> np.ndarray:
+    """RMSNorm in front of the activation quantizer (the pre-normalisation of the decoder layers the quantized
+    linears sit in; the paper does not spell it out -- this is the textbook definition, Zhang & Sennrich 2019):
+        h_k = x_k / sqrt(mean_k(x^2) + eps) * gamma_k
+    Reading, one correctly rounded fp32 operation per step, so that a fused kernel can be bit-identical:
+        ss   = fp32(sum_k x_k^2)          the EXACT sum (every square of an fp16 value is exact), rounded once
+        mean = ss / K                     K as fp32 (exact up to 2^24)
+        r    = 1 / sqrt(mean + eps)       one addition, one square root, one division
+        h_k  = (x_k * r) * gamma_k        two multiplications, gamma widened from fp16
+    The result is an fp32 array that goes to the per-token quantizer like the other transformed activations.
+    """
+    if x16.dtype != np.float16 or gamma16.dtype != np.float16:
+        raise TypeError("activations and gamma are fp16")
+    M, K = x16.shape
+    if gamma16.shape != (K,):
+        raise ValueError("gamma has one entry per feature")
+    if not (eps >= 0 and np.isfinite(eps)):
+        raise ValueError("eps must be finite and non-negative")
+    import math
+    x64 = x16.astype(np.float64)
+    # exact: squares of fp16 values are exact in fp64 and math.fsum returns the correctly rounded sum of exact terms
+    ss = np.array([math.fsum((row * row).tolist()) for row in x64], dtype=np.float64).astype(F32)
+    mean = (ss / F32(K)).astype(F32)
+    t = (mean + F32(eps)).astype(F32)
+    r = (F32(1) / np.sqrt(t).astype(F32)).astype(F32)     # mean + eps == 0: r = inf, the caller must not ask for it
+    x = x16.astype(F32)
+    h = ((x * r[:, None]).astype(F32) * gamma16.astype(F32)[None, :]).astype(F32)
+    return h
