@@ -457,10 +457,13 @@ def main():
             B = ql.ql_hadamard_block(K)
             scratch = torch.zeros(1, dtype=torch.int32, device="cuda:0")
             static = torch.full((1,), 0.05, dtype=torch.float32, device="cuda:0")
+            gam = (torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5).to(torch.float16)
             row = {"shape": f"act_quant.M{M}.K{K}", "hadamard_block": B}
             for name, fn in (("plain", lambda i: ql.ql_quant_act_per_token(x, None, kl, sxv)),
                              ("smoothquant", lambda i: ql.ql_quant_act_per_token_transformed(x, inv, 0, None, kl, sxv)),
                              ("hadamard", lambda i: ql.ql_quant_act_per_token_transformed(x, None, B, None, kl, sxv)),
+                             # RMSNorm (textbook definition) fused in front of the quantizer
+                             ("rmsnorm", lambda i: ql.ql_quant_act_rmsnorm(x, gam, 1e-6, None, kl, sxv)),
                              # the other quantizer forms: Eq. 2 as printed, per-tensor dynamic, calibrated static scale
                              ("eq2_per_token", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_EQ2, ql.QL_SCOPE_FINE, None,
                                                                              None, kl, sxv, None)),

@@ -97,6 +97,17 @@ int ql_workspace_bytes(int M, int N, int K, int bits, size_t *bytes /* host */);
 int ql_quant_act_per_token(const void *x, int64_t ldx, int M, int K,
                            int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx, void *stream);
 
+/* RMSNorm fused in front of the per-token quantizer (the normalisation a decoder layer applies to the input of its
+ * QKV and gate/up projections; textbook definition, the paper does not spell it out):
+ *     h[m,k] = x[m,k] / sqrt(mean_k(x[m,:]^2) + eps) * gamma[k],   then Eq. 1-2 on h as in ql_quant_act_per_token.
+ * Arithmetic: the sum of squares is the exact sum rounded once to fp32 (accumulated in fp64), every later step one
+ * correctly rounded fp32 operation (divide by K, add eps, square root, reciprocal, two multiplies per element).
+ *   x      device, fp16 [M, ldx] (as ql_quant_act_per_token);  gamma  device, fp16 [K], 16-byte aligned
+ *   eps    finite, >= 0 (a token with mean(x^2) + eps == 0 is the caller's error: its codes are unspecified)
+ *   outputs as ql_quant_act_per_token.  Errors: as there; QL_ERR_SHAPE for a bad eps. */
+int ql_quant_act_rmsnorm(const void *x, int64_t ldx, int M, int K, const void *gamma, float eps, int8_t *xq_rowmajor,
+                         int8_t *xq_kernel, float *sx, void *stream);
+
 /* Row-major int8 [M,K] -> kernel layout (lets a caller supply its own quantized activations). */
 int ql_act_repack(const int8_t *xq_rowmajor, int M, int K, int8_t *xq_kernel, void *stream);
 

@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "QL_OK", 1: "QL_ERR_NULL", 2: "QL_ERR_SHAPE", 3: "QL_ERR_ALIG
 
 EXPORTS = [
     "ql_version", "ql_last_error", "ql_weight_bytes", "ql_act_kernel_bytes", "ql_workspace_bytes",
-    "ql_quant_act_per_token", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
+    "ql_quant_act_per_token", "ql_quant_act_rmsnorm", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
     "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
     "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant", "ql_plan_gemm",
     "ql_probe_mfma_int8", "ql_probe_hbm_read",
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
             "ql_act_kernel_bytes": [i, i, szp],
             "ql_workspace_bytes": [i, i, i, i, szp],
             "ql_quant_act_per_token": [vp, i64, i, i, vp, vp, vp, vp],
+            "ql_quant_act_rmsnorm": [vp, i64, i, i, vp, c.c_float, vp, vp, vp, vp],
             "ql_act_repack": [vp, i, i, vp, vp],
             "ql_quant_weight": [vp, i, i, i, i, vp, vp, vp, vp],
             "ql_export_canonical": [vp, i, i, i, i, vp, vp, vp],
@@ -238,6 +239,13 @@ def ql_quant_act_per_token(x, xq_rowmajor=None, xq_kernel=None, sx=None):
     M, K = x.shape
     _check(lib().ql_quant_act_per_token(_p(x), _ld(x) if M else K, M, K, _p(xq_rowmajor), _p(xq_kernel), _p(sx),
                                         _stream()))
+
+
+def ql_quant_act_rmsnorm(x, gamma, eps, xq_rowmajor=None, xq_kernel=None, sx=None):
+    _want(x, torch.float16, "x"), _want(gamma, torch.float16, "gamma")
+    M, K = x.shape
+    _check(lib().ql_quant_act_rmsnorm(_p(x), _ld(x) if M else K, M, K, _p(gamma), float(eps), _p(xq_rowmajor),
+                                      _p(xq_kernel), _p(sx), _stream()))
 
 
 def ql_act_repack(xq_rowmajor, xq_kernel):

@@ -4,6 +4,7 @@
 #include <stdio.h>
 
 #include "common.h"
+#include <cmath>
 
 namespace ql {
 
@@ -308,6 +309,23 @@ int ql_quant_act_per_token(const void *x, int64_t ldx, int M, int K, int8_t *xq_
         return fail(QL_ERR_ALIGN, "xq_rowmajor needs 16-byte, xq_kernel 256-byte alignment");
     return launch_act_quant(static_cast<const __half *>(x), ldx, M, K, xq_rowmajor, xq_kernel, sx,
                             static_cast<hipStream_t>(stream));
+}
+
+int ql_quant_act_rmsnorm(const void *x, int64_t ldx, int M, int K, const void *gamma, float eps, int8_t *xq_rowmajor,
+                         int8_t *xq_kernel, float *sx, void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(QL_ERR_SHAPE, "eps must be finite and non-negative");
+    if (M == 0) return QL_OK;
+    if (!x || !gamma || !sx || (!xq_rowmajor && !xq_kernel))
+        return fail(QL_ERR_NULL, "x, gamma, sx and one of the outputs are required");
+    if (!aligned(x, 16) || ldx < K || ldx % 8)
+        return fail(QL_ERR_ALIGN, "x must be 16-byte aligned, ldx >= K and a multiple of 8 (ldx=%lld)", (long long)ldx);
+    if (!aligned(gamma, 16)) return fail(QL_ERR_ALIGN, "gamma must be 16-byte aligned");
+    if ((xq_rowmajor && !aligned(xq_rowmajor, 16)) || (xq_kernel && !aligned(xq_kernel, 256)) || !aligned(sx, 4))
+        return fail(QL_ERR_ALIGN, "xq_rowmajor needs 16-byte, xq_kernel 256-byte alignment");
+    return launch_act_quant_rmsnorm(static_cast<const __half *>(x), ldx, M, K, static_cast<const __half *>(gamma), eps,
+                                    xq_rowmajor, xq_kernel, sx, static_cast<hipStream_t>(stream));
 }
 
 int ql_act_repack(const int8_t *xq_rowmajor, int M, int K, int8_t *xq_kernel, void *stream)
