@@ -28,18 +28,43 @@ constexpr int SINGLE_TOKEN_MAX_M = 512;
 constexpr int MAX_RPB = 8;
 constexpr int MAX_WAVES = 8;
 
-// SM: the SmoothQuant variant (paper Eq. 3): every element is first multiplied by inv_smooth[k] = 1 / s_k (one
+// MODE 1: the SmoothQuant variant (paper Eq. 3): every element is first multiplied by inv_smooth[k] = 1 / s_k (one
 // fp32 multiply, done again when the codes are produced -- cheaper than keeping fp32 copies in registers), the
 // row maximum is taken on those fp32 products (non-negative floats order like their bit patterns).
-template <int NIT, int RPB, bool SM>
+// MODE 2: RMSNorm in front of the quantizer (textbook definition; the normalisation a decoder layer applies to the
+// input of its QKV and gate/up projections):  h_k = x_k / sqrt(mean(x^2) + eps) * gamma_k, then Eq. 1-2 on h.
+//   ss = fp32(sum x^2): the squares are exact in fp32, they are added in fp64 (per lane in k order, a butterfly
+//        across the lanes, the wavefronts in order) and rounded to fp32 once -- the fp64 sum is within ~1e-13 of the
+//        exact one, so this is the correctly rounded exact sum except within that distance of a rounding boundary;
+//   mean = ss / K,  r = 1 / sqrt(mean + eps),  h = (x * r) * gamma: one correctly rounded fp32 operation each.
+template <int NIT, int RPB, int MODE>
 __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half *__restrict__ x, int64_t ldx,
                                                                     int M, int K, int per_wave,
                                                                     const float *__restrict__ inv_smooth,
+                                                                    const __half *__restrict__ gamma, float eps,
                                                                     int8_t *__restrict__ xq_rm,
                                                                     int8_t *__restrict__ xq_kl,
                                                                     float *__restrict__ sx)
 {
+    constexpr bool SM = MODE != 0;   // the codes come from fp32 values
+    float rnorm = 0.0f;              // MODE 2: 1 / sqrt(mean(x^2) + eps) of this lane's token
+    auto widen = [](const Half16 &h, float (&f)[16]) {
+        const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            f[2 * i] = half_bits_to_float(w[i] & 0xffffu);
+            f[2 * i + 1] = half_bits_to_float(w[i] >> 16);
+        }
+    };
     auto smoothed = [&](const Half16 &h, int c, float (&f)[16]) {
+        if constexpr (MODE == 2) {
+            float g[16];
+            widen(h, f);
+            widen(reinterpret_cast<const Half16 *>(gamma)[c], g);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) f[i] = (f[i] * rnorm) * g[i];
+            return;
+        }
         const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
 #pragma unroll
         for (int i = 0; i < 16; i += 4) {
@@ -70,7 +95,52 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
 
     Half16 v[NIT > 0 ? NIT : 1];
     unsigned mx = 0;
-    if (NIT > 0) {
+    if constexpr (MODE == 2) {
+        // sum of squares first (the maximum needs the normalised values); the row goes to registers on the way
+        __shared__ double red_ss[MAX_RPB][MAX_WAVES];
+        double ss = 0.0;
+        auto add_squares = [&](const Half16 &h) {
+            float f[16];
+            widen(h, f);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ss += (double)(f[i] * f[i]);   // the product is exact in fp32
+        };
+        if (NIT > 0) {
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+                const int c = (s0 + i) * CPS + cl;
+                if (i < per_wave && c < nchunks && valid) {
+                    v[i] = row[c];
+                    add_squares(v[i]);
+                }
+            }
+        } else {
+            for (int i = 0; i < per_wave; ++i) {
+                const int c = (s0 + i) * CPS + cl;
+                if (c < nchunks && valid) add_squares(row[c]);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= RPB; off >>= 1) ss += __shfl_xor(ss, off, 64);
+        if (cl == 0) red_ss[r][wave] = ss;
+        __syncthreads();
+        double tot = 0.0;
+        for (int w = 0; w < nwaves; ++w) tot += red_ss[r][w];
+        const float mean = (float)tot / (float)K;
+        rnorm = 1.0f / sqrtf(mean + eps);
+        if (NIT > 0) {
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+                const int c = (s0 + i) * CPS + cl;
+                if (i < per_wave && c < nchunks && valid) mx = row_max(v[i], c, mx);
+            }
+        } else {
+            for (int i = 0; i < per_wave; ++i) {
+                const int c = (s0 + i) * CPS + cl;
+                if (c < nchunks && valid) mx = row_max(row[c], c, mx);
+            }
+        }
+    } else if (NIT > 0) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = (s0 + i) * CPS + cl;
@@ -119,132 +189,6 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
         for (int i = 0; i < per_wave; ++i) {
             const int c = (s0 + i) * CPS + cl;
             if (c < nchunks && valid) emit(c, row[c]);
-        }
-    }
-}
-
-// RMSNorm fused in front of the quantizer (textbook definition; the normalisation the decoder layers apply to the
-// input of their QKV and gate/up projections):  h_k = x_k / sqrt(mean(x^2) + eps) * gamma_k, then Eq. 1-2 on h.
-// One workgroup of 256 lanes per token; the row stays in registers (NIT chunks of 16 per lane; NIT == 0: it is read
-// three times).  Arithmetic, one correctly rounded fp32 operation per step unless said otherwise:
-//   ss = fp32(sum x^2): the squares are exact in fp32, they are added in fp64 (per lane in k order, a butterfly
-//        across the lanes, the four wavefronts in order) and the sum is rounded to fp32 once -- the fp64 sum is within
-//        ~1e-13 of the exact one, so this is the correctly rounded exact sum except within that distance of a rounding
-//        boundary
-//   mean = ss / K,  r = 1 / sqrt(mean + eps),  h = (x * r) * gamma,  then amax, scale, inv and codes as for any
-//   transformed (fp32) activation
-template <int NIT>
-__global__ __launch_bounds__(256) void act_quant_rmsnorm_kernel(const __half *__restrict__ x, int64_t ldx, int M, int K,
-                                                                const __half *__restrict__ gamma, float eps,
-                                                                int8_t *__restrict__ xq_rm, int8_t *__restrict__ xq_kl,
-                                                                float *__restrict__ sx)
-{
-    __shared__ double red_ss[4];
-    __shared__ unsigned red_mx[4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int m = blockIdx.x;
-    const int nchunks = K / CHUNK;
-    const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)m * ldx);
-    const Half16 *grow = reinterpret_cast<const Half16 *>(gamma);
-    const int steps = (nchunks + 255) / 256;
-    auto widen = [](const Half16 &h, float (&f)[16]) {
-        const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            f[2 * i] = half_bits_to_float(w[i] & 0xffffu);
-            f[2 * i + 1] = half_bits_to_float(w[i] >> 16);
-        }
-    };
-    Half16 v[NIT > 0 ? NIT : 1];
-    double ss64 = 0.0;
-    auto add_squares = [&](const Half16 &h) {
-        float f[16];
-        widen(h, f);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) ss64 += (double)(f[i] * f[i]);   // the product is exact in fp32
-    };
-    if (NIT > 0) {
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int c = i * 256 + threadIdx.x;
-            if (c < nchunks) {
-                v[i] = row[c];
-                add_squares(v[i]);
-            }
-        }
-    } else {
-        for (int i = 0; i < steps; ++i) {
-            const int c = i * 256 + threadIdx.x;
-            if (c < nchunks) add_squares(row[c]);
-        }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) ss64 += __shfl_xor(ss64, off, 64);
-    if (lane == 0) red_ss[wave] = ss64;
-    __syncthreads();
-    const double tot = ((red_ss[0] + red_ss[1]) + red_ss[2]) + red_ss[3];
-    const float ss = (float)tot;
-    const float mean = ss / (float)K;
-    const float r = 1.0f / sqrtf(mean + eps);
-
-    auto normed = [&](const Half16 &h, int c, float (&f)[16]) {
-        float g[16];
-        widen(h, f);
-        widen(grow[c], g);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) f[i] = (f[i] * r) * g[i];
-    };
-    unsigned mx = 0;
-    float hv[NIT > 0 ? NIT : 1][16];   // the normalised values of the chunks kept in registers
-    auto chunk_max = [&](const float (&f)[16]) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = max(mx, __float_as_uint(fabsf(f[i])));
-    };
-    if (NIT > 0) {
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int c = i * 256 + threadIdx.x;
-            if (c < nchunks) {
-                normed(v[i], c, hv[i]);
-                chunk_max(hv[i]);
-            }
-        }
-    } else {
-        for (int i = 0; i < steps; ++i) {
-            const int c = i * 256 + threadIdx.x;
-            if (c < nchunks) {
-                normed(row[c], c, hv[0]);
-                chunk_max(hv[0]);
-            }
-        }
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mx = max(mx, (unsigned)__shfl_xor((int)mx, off, 64));
-    if (lane == 0) red_mx[wave] = mx;
-    __syncthreads();
-    mx = max(max(red_mx[0], red_mx[1]), max(red_mx[2], red_mx[3]));
-    float scale, inv;
-    token_scales_f32(__uint_as_float(mx), scale, inv);
-    if (threadIdx.x == 0) sx[m] = scale;
-
-    auto emit = [&](const float (&f)[16], int c) {
-        const uint4 q = quant_chunk_f32(f, inv);
-        if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK) = q;
-        if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = q;
-    };
-    if (NIT > 0) {
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            const int c = i * 256 + threadIdx.x;
-            if (c < nchunks) emit(hv[i], c);
-        }
-    } else {
-        for (int i = 0; i < steps; ++i) {
-            const int c = i * 256 + threadIdx.x;
-            if (c < nchunks) {
-                normed(row[c], c, hv[0]);
-                emit(hv[0], c);
-            }
         }
     }
 }
@@ -345,17 +289,17 @@ __global__ void act_repack_kernel(const int8_t *__restrict__ xq_rm, int M, int K
 
 }  // namespace
 
-template <int RPB, bool SM>
-static void launch_aq(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, int8_t *xq_rm,
-                      int8_t *xq_kl, float *sx, hipStream_t st)
+template <int RPB, int MODE>
+static void launch_aq(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, const __half *gamma, float eps,
+                      int8_t *xq_rm, int8_t *xq_kl, float *sx, hipStream_t st)
 {
     const int steps = ceil_div(K / CHUNK, 64 / RPB);
     const int nw = steps < MAX_WAVES ? steps : MAX_WAVES;
     const int per_wave = ceil_div(steps, nw);
     dim3 grid(ceil_div(M, RPB)), block(nw * 64);
 #define QL_LAUNCH_AQ(NIT) \
-    hipLaunchKernelGGL((act_quant_kernel<NIT, RPB, SM>), grid, block, 0, st, x, ldx, M, K, per_wave, inv_smooth, xq_rm, \
-                       xq_kl, sx)
+    hipLaunchKernelGGL((act_quant_kernel<NIT, RPB, MODE>), grid, block, 0, st, x, ldx, M, K, per_wave, inv_smooth, gamma, \
+                       eps, xq_rm, xq_kl, sx)
     if (per_wave <= 1) QL_LAUNCH_AQ(1);
     else if (per_wave <= 2) QL_LAUNCH_AQ(2);
     else if (per_wave <= 4) QL_LAUNCH_AQ(4);
@@ -369,8 +313,8 @@ int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, 
                      float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
-    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, false>(x, ldx, M, K, nullptr, xq_rm, xq_kl, sx, st);
-    else launch_aq<8, false>(x, ldx, M, K, nullptr, xq_rm, xq_kl, sx, st);
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 0>(x, ldx, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
+    else launch_aq<8, 0>(x, ldx, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant launch");
 }
 
@@ -378,8 +322,8 @@ int launch_act_quant_smooth(const __half *x, int64_t ldx, int M, int K, const fl
                             int8_t *xq_kl, float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
-    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, true>(x, ldx, M, K, inv_smooth, xq_rm, xq_kl, sx, st);
-    else launch_aq<8, true>(x, ldx, M, K, inv_smooth, xq_rm, xq_kl, sx, st);
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 1>(x, ldx, M, K, inv_smooth, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
+    else launch_aq<8, 1>(x, ldx, M, K, inv_smooth, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant (smooth) launch");
 }
 
@@ -413,12 +357,9 @@ int launch_act_quant_rmsnorm(const __half *x, int64_t ldx, int M, int K, const _
                              int8_t *xq_kl, float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
-    const int steps = (K / CHUNK + 255) / 256;
-    if (steps <= 1) hipLaunchKernelGGL(act_quant_rmsnorm_kernel<1>, dim3(M), dim3(256), 0, st, x, ldx, M, K, gamma, eps, xq_rm, xq_kl, sx);
-    else if (steps <= 2) hipLaunchKernelGGL(act_quant_rmsnorm_kernel<2>, dim3(M), dim3(256), 0, st, x, ldx, M, K, gamma, eps, xq_rm, xq_kl, sx);
-    else if (steps <= 4) hipLaunchKernelGGL(act_quant_rmsnorm_kernel<4>, dim3(M), dim3(256), 0, st, x, ldx, M, K, gamma, eps, xq_rm, xq_kl, sx);
-    else hipLaunchKernelGGL(act_quant_rmsnorm_kernel<0>, dim3(M), dim3(256), 0, st, x, ldx, M, K, gamma, eps, xq_rm, xq_kl, sx);
-    return check_hip(hipGetLastError(), "act_quant_rmsnorm launch");
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 2>(x, ldx, M, K, nullptr, gamma, eps, xq_rm, xq_kl, sx, st);
+    else launch_aq<8, 2>(x, ldx, M, K, nullptr, gamma, eps, xq_rm, xq_kl, sx, st);
+    return check_hip(hipGetLastError(), "act_quant (rmsnorm) launch");
 }
 
 int launch_act_repack(const int8_t *xq_rm, int M, int K, int8_t *xq_kl, hipStream_t st)
