@@ -78,9 +78,13 @@ def test_quantizers_in_a_graph(G):
     sx3 = torch.zeros(M, dtype=torch.float32, device="cuda:0")
     scratch = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     B = ql.ql_hadamard_block(K)
+    xq4 = torch.zeros((M, K), dtype=torch.int8, device="cuda:0")
+    sx4 = torch.zeros(M, dtype=torch.float32, device="cuda:0")
+    gamma = torch.full((K,), 0.75, dtype=torch.float16, device="cuda:0")
 
     def enqueue():
         ql.ql_quant_act_per_token(x, xq, xk, sx)
         ql.ql_quant_act_opt(x, ql.QL_RANGE_EQ2, ql.QL_SCOPE_TENSOR, None, xq2, None, sx2, scratch)
         ql.ql_quant_act_per_token_transformed(x, None, B, xq3, None, sx3)
-    _replay_and_compare(torch, enqueue, [xq, sx, xq2, sx2, xq3, sx3])
+        ql.ql_quant_act_rmsnorm(x, gamma, 1e-6, xq4, None, sx4)
+    _replay_and_compare(torch, enqueue, [xq, sx, xq2, sx2, xq3, sx3, xq4, sx4])
