@@ -158,9 +158,12 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
 
 /* Kernel selection, for tests and tuning (process-wide, not thread-safe):
  *   0 = automatic (decode kernels for M <= 32; up to 1024 tokens whichever of the decode kernels, working on
- *       blocks of 64 tokens, and the prefill tile kernels has the lower estimated time; prefill tiles beyond)
+ *       blocks of 64 or 32 tokens, and the prefill tile kernels has the lower estimated time; prefill tiles beyond)
  *   1 = automatic among the prefill tile kernels, 100 = automatic among the decode kernels (M <= 1024)
- *   other values pick one implementation; unknown values -> QL_ERR_UNSUPPORTED. */
+ *   other values pick one implementation: 4, 6, 11, 13, 15, 17, 19, 20, 23 prefill tile shapes; 202..232 / 302..332
+ *   split-K with that many splits on 128x128 / 256x256 tiles; 101..104, 106, 108 decode kernels with that many
+ *   groups of 16 channels per workgroup; 111 sixteen wavefronts; 121 tokens never staged in LDS; 122 / 123 token
+ *   blocks of 32 / 64; 130 quantizer never fused into the decode GEMM.  Unknown values -> QL_ERR_UNSUPPORTED. */
 int ql_set_kernel_variant(int variant);
 
 /* What the automatic choice launches for a GEMM of this shape, and the time estimate it goes by (host
