@@ -1,19 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized linear layer on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config1] [--no-detail] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload config2] [--no-detail] [--no-decode] [--no-cpu]
 
 One "step" is one pass of the whole hot path over one batch: for every linear of the workload's
 decoder layer, per-token activation quantization + int8 (or int4xint8) GEMM + dequantization
 epilogue (`ql_w8a8_linear` / `ql_w4a8_linear`), inputs and quantized weights already resident in
-HBM.  Prints ONE JSON line (see the keys below); per-shape detail for the other configurations
-goes into its "detail" list.
+HBM.  Prints ONE JSON line: the headline (whole-layer throughput of the timed steps), `roofline`
+(the GEMM kernel alone: median of at least 5 repeats of at least 50 back-to-back launches per linear,
+HIP events on the launch stream; plus the decode GEMMs of the 7B-class shapes against HBM
+bandwidth), `cpu_baseline` (the CPU oracle timed on the host cores) and a compact `detail` list
+for the other configurations.  Progress and per-shape rows go to stderr.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -26,7 +30,8 @@ import numpy as np  # noqa: E402
 METRIC = "int8 TOPS (% of MFMA peak) prefill GEMM; HBM GB/s (% peak) decode GEMM"
 PEAK_INT8_TOPS = 5000.0     # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E, published
-MALL_BYTES = 256 << 20      # Infinity Cache: decode weights are rotated over > 2x this
+MALL_BYTES = 256 << 20      # Infinity Cache: weights are rotated over 3x this so that they come from HBM
+MIN_LAUNCHES, MIN_REPEATS = 50, 5   # timing protocol of the roofline figures
 
 
 def log(*a):
@@ -36,26 +41,35 @@ def log(*a):
 class Layer:
     """Device-resident state of one linear: input, quantized weights, output, workspace."""
 
-    def __init__(self, sh, torch, ql, synth, copies=1):
+    def __init__(self, sh, torch, ql, synth, copies=1, share=None, hashes=None):
         self.sh = sh
         dev = "cuda:0"
-        x, w, b = synth.tensors(sh)
+        x = synth.activations(sh.M, sh.K, sh.config, sh.layer)
         self.x = torch.from_numpy(x).to(dev)
-        wd = torch.from_numpy(w).to(dev)
+        b = synth.bias(sh.N, sh.config, sh.layer) if sh.bias else None
         self.bias = torch.from_numpy(b).to(dev) if b is not None else None
-        cb, sb, kb = ql.ql_weight_bytes(sh.N, sh.K, sh.bits, sh.group)
-        self.scales = torch.empty(sb, dtype=torch.uint8, device=dev)
-        kern = torch.empty(kb, dtype=torch.uint8, device=dev)
-        ql.ql_quant_weight(wd, sh.bits, sh.group, None, self.scales, kern)
-        self.kernels = [kern] + [kern.clone() for _ in range(copies - 1)]
-        self.sw = self.scales.view(torch.float32) if sh.bits == 8 else None
-        self.ys = [torch.empty((sh.M, sh.N), dtype=torch.float16, device=dev) for _ in range(min(copies, 4))]
+        if hashes is not None:
+            hashes[sh.name + ".x"] = synth.sha256(x)[:16]
+        if share is not None:     # same weight matrix as another Layer (the decode shapes differ only in M)
+            self.scales, self.kernels, self.sw, self.weight_bytes = share.scales, share.kernels, share.sw, share.weight_bytes
+        else:
+            w = synth.weights(sh.N, sh.K, sh.config, sh.layer)
+            if hashes is not None:
+                hashes[sh.name + ".w"] = synth.sha256(w)[:16]
+            wd = torch.from_numpy(w).to(dev)
+            cb, sb, kb = ql.ql_weight_bytes(sh.N, sh.K, sh.bits, sh.group)
+            self.scales = torch.empty(sb, dtype=torch.uint8, device=dev)
+            kern = torch.empty(kb, dtype=torch.uint8, device=dev)
+            ql.ql_quant_weight(wd, sh.bits, sh.group, None, self.scales, kern)
+            self.kernels = [kern] + [kern.clone() for _ in range(copies - 1)]
+            self.sw = self.scales.view(torch.float32) if sh.bits == 8 else None
+            self.weight_bytes = kb
+            del wd
+        self.ys = [torch.empty((sh.M, sh.N), dtype=torch.float16, device=dev) for _ in range(min(len(self.kernels), 4))]
         self.ws = torch.empty(ql.ql_workspace_bytes(sh.M, sh.N, sh.K, sh.bits), dtype=torch.uint8, device=dev)
         self.xq = torch.empty(ql.ql_act_kernel_bytes(sh.M, sh.K), dtype=torch.uint8, device=dev)
         self.sx = torch.empty(sh.M, dtype=torch.float32, device=dev)
-        self.weight_bytes = kb
         self.ql = ql
-        del wd
 
     def linear(self, i=0):
         sh, ql = self.sh, self.ql
@@ -87,56 +101,57 @@ class Layer:
         return self.sh.M * self.sh.K * 3 + self.sh.M * 4
 
 
-def event_time_ms(torch, fn, reps, per_launch):
-    """Average GPU time of fn() in ms over `reps` launches on torch's current stream (the stream the
-    library launches on), from HIP events: one pair per launch, or one pair around all launches."""
-    if per_launch:
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for i, (a, b) in enumerate(ev):
-            a.record()
-            fn(i)
-            b.record()
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in ev) / reps
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for i in range(reps):
-        fn(i)
-    b.record()
-    torch.cuda.synchronize()
-    return a.elapsed_time(b) / reps
+def copies_for(sh, forced=0):
+    """Copies of a weight matrix the launches rotate through: enough that consecutive launches never find it in
+    the Infinity Cache (in a model a layer's weights always come from HBM)."""
+    if forced:
+        return forced
+    return -(-3 * MALL_BYTES // (sh.N * sh.K // (1 if sh.bits == 8 else 2)))
 
 
-def best_time_ms(torch, fn, reps, per_launch=False, warm=30, rounds=5):
-    """Warm up, then the best of `rounds` event-timed averages (the first tens of launches on fresh buffers
-    run 10-15 % slower)."""
+def event_times_ms(torch, fn, launches, repeats, warm):
+    """`repeats` averages (ms per launch), each from one HIP-event pair on torch's current stream (the stream the
+    library launches on) around `launches` back-to-back launches; `warm` untimed launches first."""
     for i in range(warm):
         fn(i)
-    return min(event_time_ms(torch, fn, reps, per_launch) for _ in range(rounds))
+    out = []
+    for _ in range(repeats):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(launches):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        out.append(a.elapsed_time(b) / launches)
+    return out
 
 
-def graph_time_ms(torch, fn, reps, warm=10, rounds=5):
-    """Average GPU time of fn(i) with `reps` launches captured into one HIP graph and replayed: for kernels
-    of a few microseconds the Python/ctypes/hipLaunchKernel path (~7 us per call) would otherwise be what is
-    measured.  Best of `rounds` replays, each bracketed by HIP events on the replay stream."""
+def graph_times_ms(torch, fn, launches, repeats, warm=10):
+    """The same with the launches captured into one HIP graph and replayed: for kernels of a few microseconds the
+    Python/ctypes/hipLaunchKernel path (~7 us per call) would otherwise be what is measured."""
     for i in range(warm):
         fn(i)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
-        for i in range(reps):
+        for i in range(launches):
             fn(i)
     g.replay()
     torch.cuda.synchronize()
-    best = float("inf")
-    for _ in range(rounds):
+    out = []
+    for _ in range(repeats):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         g.replay()
         b.record()
         torch.cuda.synchronize()
-        best = min(best, a.elapsed_time(b) / reps)
-    return best
+        out.append(a.elapsed_time(b) / launches)
+    return out
+
+
+def median_ms(torch, fn, launches=MIN_LAUNCHES, repeats=MIN_REPEATS, graph=False, warm=30):
+    ts = graph_times_ms(torch, fn, launches, repeats) if graph else event_times_ms(torch, fn, launches, repeats, warm)
+    return statistics.median(ts)
 
 
 def profiled_traffic(cfg):
@@ -152,70 +167,150 @@ def profiled_traffic(cfg):
     return None
 
 
-def measured_ceilings(torch, ql):
+def measured_ceilings(torch):
     """What this GPU sustains on the matrix pipe and on HBM reads, measured here and now (context for
     `roofline.frac`, which stays against the published peaks): register-resident int8 MFMA loop on every CU
-    with constant and with hashed operands, and a read stream over 2 GiB."""
+    with constant and with hashed operands, and a read stream over 2 GiB (helper library libqlprobe.so)."""
+    from paper_2512_23367_amd import probe
     sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     out = {}
     for name, rnd in (("mfma_int8_constant_operands_tops", False), ("mfma_int8_random_operands_tops", True)):
         ops = [0]
 
         def f(i, rnd=rnd):
-            ops[0] = ql.ql_probe_mfma_int8(2048, 2000, rnd, sink)
-        ms = best_time_ms(torch, f, 3, warm=2, rounds=3)
+            ops[0] = probe.mfma_int8(2048, 2000, rnd, sink)
+        ms = min(event_times_ms(torch, f, 3, 3, 2))
         out[name] = round(ops[0] / (ms * 1e-3) / 1e12, 1)
     buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda:0")
     buf.zero_()
-    ms = best_time_ms(torch, lambda i: ql.ql_probe_hbm_read(buf, sink), 5, warm=2, rounds=3)
+    ms = min(event_times_ms(torch, lambda i: probe.hbm_read(buf, sink), 5, 3, 2))
     out["hbm_read_stream_gbs"] = round(buf.numel() / (ms * 1e-3) / 1e9, 1)
     del buf
     torch.cuda.empty_cache()
     return out
 
 
-def cpu_baseline(shapes, synth):
-    """The oracle as it stands, timed on the host cores on the same workload (all rows)."""
+def cpu_baseline(shapes, synth, slice_rows):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload: the first
+    `slice_rows` token rows of every linear (rows are independent under per-token quantization), all host
+    threads, repeated until about 10 s of CPU work; then one pass of a quarter of those rows on one thread."""
+    import ctypes
     import oracle
     from oracle import linear as olin
-    t_total, ops, passes = 0.0, 0, 0
     prepared = []
     for sh in shapes:
-        x, w, b = synth.tensors(sh)
+        rows = min(slice_rows, sh.M)
+        x = synth.activations(sh.M, sh.K, sh.config, sh.layer, rows=slice(0, rows))
+        w = synth.weights(sh.N, sh.K, sh.config, sh.layer)
+        b = synth.bias(sh.N, sh.config, sh.layer) if sh.bias else None
         if sh.bits == 8:
             wq, sw = oracle.quant_weight_int8(w)        # offline, not timed
-            prepared.append((sh, lambda x=x, wq=wq, sw=sw, b=b: oracle.linear_w8a8(x, wq, sw, b)))
+            run = lambda x, wq=wq, sw=sw, b=b: oracle.linear_w8a8(x, wq, sw, b)
         else:
             p, _, s = oracle.quant_weight_int4(w, sh.group)
-            prepared.append((sh, lambda x=x, p=p, s=s, g=sh.group, b=b: oracle.linear_w4a8(x, p, s, g, b)))
-    while t_total < 10.0 and passes < 20:               # bounded: about 10 s of CPU work
-        for sh, run in prepared:
+            run = lambda x, p=p, s=s, g=sh.group, b=b: oracle.linear_w4a8(x, p, s, g, b)
+        prepared.append((sh, x, run))
+        del w
+    threads = olin.num_threads()
+    t_total, ops, passes = 0.0, 0, 0
+    while t_total < 10.0 and passes < 20:
+        for sh, x, run in prepared:
             t0 = time.perf_counter()
-            run()
+            run(x)
             t_total += time.perf_counter() - t0
-            ops += sh.ops
+            ops += 2 * x.shape[0] * sh.N * sh.K
         passes += 1
-    return dict(value=ops / t_total / 1e12, unit="TOPS", cores=olin.num_threads(), kind="oracle",
-                sample=f"all {len(shapes)} linears of the workload in full (every token row), {passes} passes, "
-                       f"{ops / 1e9:.1f} GOP in {t_total:.1f} s; weight quantization not timed")
+    out = dict(value=ops / t_total / 1e12, unit="TOPS", cores=threads, kind="oracle")
+    # one thread: OpenMP's own switch, the oracle is untouched
+    one = None
+    try:
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        t1, ops1 = 0.0, 0
+        for sh, x, run in prepared:
+            xs = x[:max(1, x.shape[0] // 4)]
+            t0 = time.perf_counter()
+            run(xs)
+            t1 += time.perf_counter() - t0
+            ops1 += 2 * xs.shape[0] * sh.N * sh.K
+        gomp.omp_set_num_threads(threads)
+        one = ops1 / t1 / 1e12
+    except OSError:
+        pass
+    out["value_one_thread"] = one
+    out["sample"] = (f"first {slice_rows} token rows of each of the workload's {len(shapes)} linears (quantize + integer GEMM + "
+                     f"epilogue), {passes} passes on {threads} threads: {ops / 1e9:.1f} GOP in {t_total:.1f} s; one thread: "
+                     f"a quarter of those rows once; weight quantization not timed")
+    return out
+
+
+def decode_table(torch, ql, synth, forced_copies, hashes):
+    """GEMM-only time of every decode shape of config 4 (7B-class layer, M in {1, 8, 32}, int8 and int4 weights)
+    against HBM bandwidth: algorithmic bytes / median launch time, launches replayed from a HIP graph, the weight
+    matrix rotated through enough copies that it comes from HBM."""
+    rows = []
+    groups = {}
+    for sh in synth.workload(4):
+        if sh.M <= 32:
+            groups.setdefault((sh.layer, sh.bits), []).append(sh)
+    for (layer, bits), shs in groups.items():
+        copies = copies_for(shs[0], forced_copies)
+        base = None
+        for sh in shs:
+            l = Layer(sh, torch, ql, synth, copies, share=base, hashes=hashes if sh.M == 1 and bits == 8 else None)
+            base = base or l
+            l.quant()
+            launches = max(MIN_LAUNCHES, 2 * copies)
+            t = median_ms(torch, l.gemm, launches, MIN_REPEATS, graph=True)
+            t_lin = median_ms(torch, l.linear, launches, 3, graph=True)
+            gbs = l.gemm_bytes() / (t * 1e-3) / 1e9
+            row = {"shape": sh.name, "gemm_us": round(t * 1e3, 2), "linear_us": round(t_lin * 1e3, 2),
+                   "gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4), "weight_copies_rotated": copies}
+            rows.append(row)
+            log("[decode]", json.dumps(row))
+        del base, l
+        torch.cuda.empty_cache()
+    return rows
+
+
+def decode_summary(rows):
+    """Compact forms of the decode table for the JSON line: a string 'w8 M1 qkv/o/gate_up/down 0.61/0.41/...' and
+    the extremes."""
+    def frac(bits, M, layer):
+        for r in rows:
+            if r["shape"].startswith(f"c4.{layer}.M{M}.") and r["shape"].endswith(f".w{bits}"):
+                return r["frac_hbm_peak"]
+        return None
+    parts = []
+    for bits in (8, 4):
+        for M in (1, 8, 32):
+            fr = [frac(bits, M, l) for l in ("qkv", "o", "gate_up", "down")]
+            parts.append(f"w{bits} M{M} " + "/".join("-" if f is None else f"{f:.2f}" for f in fr))
+    w8 = [r["frac_hbm_peak"] for r in rows if r["shape"].endswith(".w8")]
+    w4 = [r["frac_hbm_peak"] for r in rows if r["shape"].endswith(".w4")]
+    return "frac of 8 TB/s, qkv/o/gate_up/down: " + "; ".join(parts), w8, w4
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config1",
-                    help="config1 (default), config2, config3, config4 (long prefill), decode8, decode4 "
-                         "(the 7B-class decode GEMMs of config 4, int8 / int4 weights)")
-    ap.add_argument("--decode-m", type=int, default=1, help="tokens of the decode workloads: 1 .. 1024 (automatic kernel choice: beyond 32 tokens the tile kernels where they are estimated faster)")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="config2",
+                    help="config2 (default: the 7B-class W8A8 prefill layer, the largest single-GPU decoder-layer "
+                         "workload), config1, config3, config4 (long prefill), decode8, decode4 (the 7B-class decode "
+                         "GEMMs of config 4, int8 / int4 weights)")
+    ap.add_argument("--decode-m", type=int, default=1, help="tokens of the decode workloads: 1 .. 1024")
     ap.add_argument("--variant", type=int, default=0, help="kernel variant (0 = automatic)")
     ap.add_argument("--weight-copies", type=int, default=0,
                     help="copies of every weight matrix the launches rotate through (0 = enough that the copies of "
                          "a matrix exceed three times the 256 MB Infinity Cache, i.e. weights come from HBM as in a model)")
-    ap.add_argument("--no-detail", action="store_true", help="skip the per-shape table of the other configurations")
+    ap.add_argument("--no-detail", action="store_true", help="skip the rows of the other configurations")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode table (roofline.decode)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--only-step", action="store_true", help="only the timed steps (for profiling)")
+    ap.add_argument("--only-gemm", action="store_true",
+                    help="quantize once, then only GEMM launches of the workload (for profiling the GEMM kernels)")
     ap.add_argument("--copy-only", action="store_true",
                     help="run a plain 1 GiB device-to-device copy 5 times and exit (calibrates the profiler's "
                          "FETCH_SIZE / WRITE_SIZE counters against a known size)")
@@ -254,20 +349,28 @@ def main():
         cfg = int(args.workload.replace("config", ""))
         shapes = [s for s in synth.workload(cfg) if s.M > 32]
     descr = {1: "config1: W8A8 linears of a 1B-class decoder layer, prefill M=2048, d=1536 (qkv, o, gate_up, down)",
-             2: "config2: W8A8 linears (+bias) of a 7B-class decoder layer, prefill M=4096, d=4096",
+             2: "config2: W8A8 linears (+bias) of a 7B-class decoder layer, prefill M=4096, d=4096 (qkv, o, gate_up, down)",
              3: "config3: W4A8 (group 128) linears of a 7B-class decoder layer, prefill M=4096, d=4096",
              4: "config4: long-reasoning prefill of the down projection, M=16384, W8A8"}[cfg]
     if decode:
         descr = (f"config4 decode: {'W8A8' if bits == 8 else 'W4A8 (group 128)'} linears of a 7B-class decoder "
                  f"layer, M={args.decode_m} (qkv, o, gate_up, down), weights rotated over >768 MB of copies")
 
-    def copies_for(s):   # enough copies that the weights cannot come from the Infinity Cache, per matrix:
-        if args.weight_copies:   # the per-layer GEMM timings below rotate one matrix at a time
-            return args.weight_copies
-        return -(-3 * MALL_BYTES // (s.N * s.K // (1 if s.bits == 8 else 2)))
-
-    layers = [Layer(s, torch, ql, synth, copies_for(s)) for s in shapes]
+    hashes = {}
+    layers = [Layer(s, torch, ql, synth, copies_for(s, args.weight_copies), hashes=hashes) for s in shapes]
     total_ops = sum(s.ops for s in shapes)
+    log("[inputs] sha256[:16] of the host tensors:", json.dumps(hashes))
+
+    if args.only_gemm:
+        for l in layers:
+            l.quant()
+        for i in range(args.warmup + args.steps):
+            for l in layers:
+                l.gemm(i)
+        torch.cuda.synchronize()
+        print(json.dumps({"only_gemm": True, "launches_per_linear": args.warmup + args.steps,
+                          "layers": [s.name for s in shapes]}), flush=True)
+        return
 
     def step(i=0):
         for l in layers:
@@ -278,7 +381,7 @@ def main():
     torch.cuda.synchronize()
     graph = None
     if decode:
-        # a decode step is 8 launches of 4-16 us: replay them from a HIP graph so that the GPU, not the
+        # a decode step is 4-8 launches of 4-16 us: replay them from a HIP graph so that the GPU, not the
         # launch path, is timed (the warm-up above ran every kernel once outside the capture)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
@@ -318,171 +421,157 @@ def main():
         print(json.dumps(out), flush=True)
         return
 
-    # ---- roofline of the dominant kernel (the prefill GEMM), timed with HIP events on the launch stream
+    # ---- roofline of the dominant kernel (the GEMM + fused epilogue), timed with HIP events on the launch stream:
+    # median of MIN_REPEATS repeats of >= MIN_LAUNCHES back-to-back launches per linear, whatever --steps says
     for l in layers:
         l.quant()
-    reps = max(20, min(args.steps, 100))
-    gemm_ms, gemm_ms_b2b, quant_ms = [], [], []
+    gemm_ms, quant_ms = [], []
     for l in layers:
-        # one event pair around `reps` back-to-back launches: per-launch pairs add ~2-7 us of event
-        # overhead to kernels this short and would not agree with the profiler's kernel durations
-        timer = graph_time_ms if decode else best_time_ms
-        reps_l = max(reps, len(l.kernels))   # at least one cycle through the weight copies
-        gemm_ms.append(timer(torch, l.gemm, reps_l))
-        gemm_ms_b2b.append(best_time_ms(torch, l.gemm, reps_l, per_launch=True, warm=0, rounds=1))
-        # the quantizer runs 2-10 us: replay it from a HIP graph, or the launch path is what gets timed
-        quant_ms.append(graph_time_ms(torch, lambda i, l=l: l.quant(), reps))
-    achieved = total_ops / (sum(gemm_ms) * 1e-3) / 1e12
-    roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
-            "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": profiled_traffic(cfg),
-            "kernel": "gemm_prefill_kernel (int8 MFMA GEMM + fused dequant epilogue), one launch per linear"}
-    if decode:
+        launches = max(MIN_LAUNCHES, len(l.kernels))   # at least one cycle through the weight copies
+        gemm_ms.append(median_ms(torch, l.gemm, launches, MIN_REPEATS, graph=decode))
+        # the quantizer runs 2-30 us: replay it from a HIP graph, or the launch path is what gets timed
+        quant_ms.append(median_ms(torch, lambda i, l=l: l.quant(), MIN_LAUNCHES, MIN_REPEATS, graph=True))
+    timing = f"median of {MIN_REPEATS} repeats of >= {MIN_LAUNCHES} back-to-back launches per linear, one HIP-event pair per repeat"
+    if not decode:
+        achieved = total_ops / (sum(gemm_ms) * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
+                "frac": round(achieved / PEAK_INT8_TOPS, 4), "traffic": profiled_traffic(cfg),
+                "kernel": "gemm_prefill_kernel (int8 MFMA GEMM + fused dequant epilogue), one launch per linear",
+                "timing": timing,
+                "per_layer": "; ".join(f"{l.sh.layer} {t * 1e3:.1f} us {l.sh.ops / (t * 1e-3) / 1e12:.0f} TOPS "
+                                       f"{l.sh.ops / (t * 1e-3) / 1e12 / PEAK_INT8_TOPS:.3f}" for l, t in zip(layers, gemm_ms))}
+    else:
         achieved = sum(l.gemm_bytes() for l in layers) / (sum(gemm_ms) * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
                 "kernel": "gemm_decode_kernel (weight-streaming int8 MFMA GEMM + fused epilogue), one launch per linear",
-                "per_layer_gbs": {l.sh.layer: round(l.gemm_bytes() / (t * 1e-3) / 1e9, 1) for l, t in zip(layers, gemm_ms)}}
-    out["roofline"] = {
-        **roof,
-        "launch_us": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, gemm_ms)},
-        "launch_us_event_pair_each": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, gemm_ms_b2b)},
-        "per_layer_tops": {l.sh.layer: round(l.sh.ops / (t * 1e-3) / 1e12, 1) for l, t in zip(layers, gemm_ms)},
-        "act_quant_us": {l.sh.layer: round(t * 1e3, 2) for l, t in zip(layers, quant_ms)},
-        "act_quant_gbs": {l.sh.layer: round(l.quant_bytes() / (t * 1e-3) / 1e9, 1) for l, t in zip(layers, quant_ms)},
-    }
-    ceil = measured_ceilings(torch, ql)
-    ref = ceil["hbm_read_stream_gbs"] if decode else ceil["mfma_int8_random_operands_tops"]
-    out["roofline"]["measured_ceilings"] = {**ceil, "achieved_over_measured": round(out["roofline"]["achieved"] / ref, 4),
-                                            "note": "context only; frac is against the published peak. The matrix-pipe probe "
-                                                    "keeps its operands in registers; hashed operands lower the shader clock"}
-    log("[roofline]", json.dumps(out["roofline"]))
+                "timing": timing + " (launches replayed from a HIP graph)",
+                "per_layer": "; ".join(f"{l.sh.layer} {t * 1e3:.2f} us {l.gemm_bytes() / (t * 1e-3) / 1e9:.0f} GB/s"
+                                       for l, t in zip(layers, gemm_ms))}
+    roof["act_quant"] = "; ".join(f"{l.sh.layer} {t * 1e3:.1f} us {l.quant_bytes() / (t * 1e-3) / 1e9:.0f} GB/s"
+                                  for l, t in zip(layers, quant_ms))
+    out["roofline"] = roof
+    log("[roofline]", json.dumps(roof))
+    del layers
+    torch.cuda.empty_cache()
 
-    # ---- detail: GEMM-only throughput of the other configurations (parity-test cases, not the headline)
+    # ---- the decode GEMMs of config 4 against HBM bandwidth (the second half of the metric)
+    if not args.no_decode and not decode:
+        rows = decode_table(torch, ql, synth, args.weight_copies, hashes)
+        text, w8, w4 = decode_summary(rows)
+        roof["decode"] = text
+        roof["decode_w8a8_frac_min"], roof["decode_w8a8_frac_max"] = min(w8), max(w8)
+        roof["decode_w4a8_frac_min"], roof["decode_w4a8_frac_max"] = min(w4), max(w4)
+        roof["decode_rows"] = {r["shape"]: [r["gemm_us"], r["linear_us"], r["gbs"]] for r in rows}
+        roof["decode_rows_columns"] = "gemm_us, linear_us (quantize + GEMM), GB/s of algorithmic bytes"
+
+    ceil = measured_ceilings(torch)
+    ref = ceil["hbm_read_stream_gbs"] if decode else ceil["mfma_int8_random_operands_tops"]
+    roof["measured_ceilings"] = {**ceil, "achieved_over_measured": round(roof["achieved"] / ref, 4)}
+    roof["measured_ceilings_note"] = ("context only; frac is against the published peak. The matrix-pipe probe keeps its "
+                                      "operands in registers; hashed operands lower the shader clock")
+    log("[ceilings]", json.dumps(roof["measured_ceilings"]))
+
+    # ---- detail: the other prefill configurations (parity-test cases, not the headline), GEMM-only
     if not args.no_detail and not decode:
         detail = []
-        del layers
-        torch.cuda.empty_cache()
-        for c in (2, 3, 4):
-            shapes_c = [s for s in synth.workload(c) if not (c == cfg and s.M > 32)]
-            # decode shapes differ only in M: quantize each weight matrix once and rotate over enough
-            # copies that the stream comes from HBM, not from the Infinity Cache
-            groups = {}
-            for sh in shapes_c:
-                groups.setdefault((sh.layer, sh.K, sh.N, sh.bits, sh.M <= 32), []).append(sh)
-            for (layer, K, N, bits, _), shs in groups.items():
-                wbytes = N * K // (1 if bits == 8 else 2)
-                decode = shs[0].M <= 32
-                copies = -(-3 * MALL_BYTES // wbytes)
-                base = Layer(shs[0], torch, ql, synth, copies)
-                for sh in shs:
-                    l = base if sh is shs[0] else Layer(sh, torch, ql, synth, 1)
-                    if l is not base:
-                        l.kernels, l.scales, l.sw = base.kernels, base.scales, base.sw
-                    l.quant()
-                    r = max(20, copies) if not decode else max(50, 2 * copies)   # at least one cycle through the copies
-                    timer = graph_time_ms if decode else best_time_ms
-                    t_bb = timer(torch, l.gemm, r)
-                    t_lin = timer(torch, l.linear, r, warm=3, rounds=2)
-                    row = {"shape": sh.name, "gemm_us": round(t_bb * 1e3, 2), "linear_us": round(t_lin * 1e3, 2)}
-                    if not decode:
-                        row["tops"] = round(sh.ops / (t_bb * 1e-3) / 1e12, 1)
-                        row["frac_mfma_peak"] = round(row["tops"] / PEAK_INT8_TOPS, 4)
-                    else:
-                        row["gbs"] = round(l.gemm_bytes() / (t_bb * 1e-3) / 1e9, 1)
-                        row["frac_hbm_peak"] = round(row["gbs"] / PEAK_HBM_GBS, 4)
-                    row["weight_copies_rotated"] = copies
-                    detail.append(row)
-                    log("[detail]", json.dumps(row))
-                del base, l
-                torch.cuda.empty_cache()
-        # between decode and prefill: 64 and 256 tokens on the 7B-class shapes (weights rotated as for decode);
-        # these are weight-stream-bound, so the rate is weight bytes per second
-        for base_sh in [s_ for s_ in synth.workload(4) if s_.M == 1]:
-            wbytes = base_sh.N * base_sh.K * base_sh.bits // 8
-            copies = -(-3 * MALL_BYTES // wbytes)
-            base = None
-            for M in (64, 256):
-                sh = synth.Shape(base_sh.config, base_sh.layer, M, base_sh.K, base_sh.N, base_sh.bits, base_sh.group, base_sh.bias)
-                l = Layer(sh, torch, ql, synth, copies if base is None else 1)
-                if base is None:
-                    base = l
-                else:
-                    l.kernels, l.scales, l.sw = base.kernels, base.scales, base.sw
+        for c in (1, 2, 3, 4):
+            if c == cfg:
+                continue
+            for sh in [s for s in synth.workload(c) if s.M > 32]:
+                l = Layer(sh, torch, ql, synth, copies_for(sh, args.weight_copies))
                 l.quant()
-                r = max(50, 2 * copies)
-                t_bb = graph_time_ms(torch, l.gemm, r)
-                t_lin = graph_time_ms(torch, l.linear, r)
-                row = {"shape": sh.name, "gemm_us": round(t_bb * 1e3, 2), "linear_us": round(t_lin * 1e3, 2),
-                       "weight_gbs": round(wbytes / (t_bb * 1e-3) / 1e9, 1),
-                       "frac_hbm_peak": round(wbytes / (t_bb * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                       "weight_copies_rotated": copies}
+                launches = max(MIN_LAUNCHES if sh.ops < 5e11 else 20, len(l.kernels))
+                t = median_ms(torch, l.gemm, launches, MIN_REPEATS)
+                t_lin = median_ms(torch, l.linear, launches, 3, warm=5)
+                tops = sh.ops / (t * 1e-3) / 1e12
+                row = {"shape": sh.name, "gemm_us": round(t * 1e3, 1), "linear_us": round(t_lin * 1e3, 1),
+                       "tops": round(tops, 1), "frac_mfma_peak": round(tops / PEAK_INT8_TOPS, 4)}
                 detail.append(row)
                 log("[detail]", json.dumps(row))
-            del base, l
-            torch.cuda.empty_cache()
-        # context for the paper's Table 3 (INT8 against FP16 prefill latency, weight memory): the same linears
-        # as FP16 GEMMs of the vendor library (torch.matmul -> hipBLASLt/rocBLAS), a comparison system, not
-        # part of this library; W8A8 / W4A8 = quantize + GEMM + epilogue through ql_*_linear
-        for c, bits_list in ((1, (8,)), (2, (8, 4))):
-            tot = {"fp16": 0.0, "w8a8": 0.0, "w4a8": 0.0}
-            mem = {"fp16": 0, "w8a8": 0, "w4a8": 0}
-            for sh in [s_ for s_ in synth.workload(c) if s_.M > 32]:
-                xh = torch.randn((sh.M, sh.K), dtype=torch.float16, device="cuda:0")
-                wh = torch.randn((sh.N, sh.K), dtype=torch.float16, device="cuda:0") * 0.02
-                tot["fp16"] += best_time_ms(torch, lambda i: torch.matmul(xh, wh.t()), 20, warm=5, rounds=3)
-                mem["fp16"] += sh.N * sh.K * 2
-                del xh, wh
-                for b in bits_list + ((4,) if c == 1 else ()):
-                    l = Layer(synth.Shape(sh.config, sh.layer, sh.M, sh.K, sh.N, b, 0 if b == 8 else 128, sh.bias),
-                              torch, ql, synth)
-                    key = "w8a8" if b == 8 else "w4a8"
-                    tot[key] += best_time_ms(torch, l.linear, 20, warm=5, rounds=3)
-                    mem[key] += l.weight_bytes + (sh.N * 4 if b == 8 else 0)
-                    del l
+                del l
                 torch.cuda.empty_cache()
-            row = {"shape": f"layer.c{c}.prefill", "fp16_library_gemm_us": round(tot["fp16"] * 1e3, 1),
-                   "w8a8_linear_us": round(tot["w8a8"] * 1e3, 1), "w4a8_linear_us": round(tot["w4a8"] * 1e3, 1),
-                   "w8a8_speedup_over_fp16": round(tot["fp16"] / tot["w8a8"], 2),
-                   "w4a8_speedup_over_fp16": round(tot["fp16"] / tot["w4a8"], 2),
-                   "weight_mb": {k: round(v / 1e6, 1) for k, v in mem.items()}}
-            log("[detail]", json.dumps(row))
-            detail.append(row)
-        # the activation quantizer alone and with the paper's two operand transforms fused in front of it
-        # (SmoothQuant per-channel multiply, block Hadamard rotation), graph-replayed; 3 B per element
-        for M, K in ((2048, 1536), (4096, 4096), (4096, 11008)):
-            x = torch.randn((M, K), dtype=torch.float16, device="cuda:0")
-            kl = torch.empty(ql.ql_act_kernel_bytes(M, K), dtype=torch.uint8, device="cuda:0")
-            sxv = torch.empty(M, dtype=torch.float32, device="cuda:0")
-            inv = torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5
-            B = ql.ql_hadamard_block(K)
-            scratch = torch.zeros(1, dtype=torch.int32, device="cuda:0")
-            static = torch.full((1,), 0.05, dtype=torch.float32, device="cuda:0")
-            gam = (torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5).to(torch.float16)
-            row = {"shape": f"act_quant.M{M}.K{K}", "hadamard_block": B}
-            for name, fn in (("plain", lambda i: ql.ql_quant_act_per_token(x, None, kl, sxv)),
-                             ("smoothquant", lambda i: ql.ql_quant_act_per_token_transformed(x, inv, 0, None, kl, sxv)),
-                             ("hadamard", lambda i: ql.ql_quant_act_per_token_transformed(x, None, B, None, kl, sxv)),
-                             # RMSNorm (textbook definition) fused in front of the quantizer
-                             ("rmsnorm", lambda i: ql.ql_quant_act_rmsnorm(x, gam, 1e-6, None, kl, sxv)),
-                             # the other quantizer forms: Eq. 2 as printed, per-tensor dynamic, calibrated static scale
-                             ("eq2_per_token", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_EQ2, ql.QL_SCOPE_FINE, None,
-                                                                             None, kl, sxv, None)),
-                             ("per_tensor", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_SYMMETRIC, ql.QL_SCOPE_TENSOR,
-                                                                          None, None, kl, sxv, scratch)),
-                             ("static_scale", lambda i: ql.ql_quant_act_opt(x, ql.QL_RANGE_SYMMETRIC, ql.QL_SCOPE_STATIC,
-                                                                            static, None, kl, sxv, None))):
-                t = graph_time_ms(torch, fn, 50)
-                row[name + "_us"] = round(t * 1e3, 2)
-                row[name + "_gbs"] = round(3 * M * K / (t * 1e-3) / 1e9, 1)
-            log("[detail]", json.dumps(row))
-            detail.append(row)
-            del x, kl
+        detail += layer_table(torch, ql, synth)
+        detail += act_quant_rows(torch, ql)
         out["detail"] = detail
 
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(shapes, synth)
+        out["cpu_baseline"] = cpu_baseline(shapes, synth, 256 if shapes[0].K >= 4096 else shapes[0].M)
         log("[cpu]", json.dumps(out["cpu_baseline"]))
     print(json.dumps(out), flush=True)
+
+
+def layer_table(torch, ql, synth):
+    """Context for the paper's Table 3 (INT8 against FP16 prefill latency and memory by batch size): the four
+    linears of the 7B-class layer (QKV -> O -> gate+up -> down) over a sweep of token counts, as FP16 GEMMs of
+    the vendor library (torch.matmul, a comparison system that is not part of this library) and as W8A8 / W4A8
+    linears (quantize + GEMM + epilogue through ql_*_linear); weight bytes per precision."""
+    rows = []
+    base = [s for s in synth.workload(2)]
+    weights = {}
+    for sh in base:
+        for b in (8, 4):
+            l = Layer(synth.Shape(sh.config, sh.layer, 32, sh.K, sh.N, b, 0 if b == 8 else 128, sh.bias), torch, ql, synth)
+            weights[(sh.layer, b)] = l
+        weights[(sh.layer, 16)] = torch.randn((sh.N, sh.K), dtype=torch.float16, device="cuda:0") * 0.02
+    mem = {"fp16": sum(s.N * s.K * 2 for s in base),
+           "w8a8": sum(weights[(s.layer, 8)].weight_bytes + s.N * 4 for s in base),
+           "w4a8": sum(weights[(s.layer, 4)].weight_bytes for s in base)}
+    for M in (512, 1024, 2048, 4096, 8192, 16384):
+        tot = {"fp16": 0.0, "w8a8": 0.0, "w4a8": 0.0}
+        for sh in base:
+            xh = torch.randn((M, sh.K), dtype=torch.float16, device="cuda:0")
+            wh = weights[(sh.layer, 16)]
+            reps = 10 if M >= 8192 else 20
+            tot["fp16"] += statistics.median(event_times_ms(torch, lambda i: torch.matmul(xh, wh.t()), reps, 3, 3))
+            for b in (8, 4):
+                wl = weights[(sh.layer, b)]
+                y = torch.empty((M, sh.N), dtype=torch.float16, device="cuda:0")
+                ws = torch.empty(ql.ql_workspace_bytes(M, sh.N, sh.K, b), dtype=torch.uint8, device="cuda:0")
+                if b == 8:
+                    fn = lambda i: ql.ql_w8a8_linear(xh, wl.kernels[0], wl.sw, wl.bias, sh.N, y, ws)
+                else:
+                    fn = lambda i: ql.ql_w4a8_linear(xh, wl.kernels[0], 128, wl.bias, sh.N, y, ws)
+                tot["w8a8" if b == 8 else "w4a8"] += statistics.median(event_times_ms(torch, fn, reps, 3, 3))
+                del y, ws
+            del xh
+            torch.cuda.empty_cache()
+        row = {"shape": f"layer7b.prefill.M{M}", "fp16_library_gemm_us": round(tot["fp16"] * 1e3, 1),
+               "w8a8_linear_us": round(tot["w8a8"] * 1e3, 1), "w4a8_linear_us": round(tot["w4a8"] * 1e3, 1),
+               "w8a8_speedup_over_fp16": round(tot["fp16"] / tot["w8a8"], 2),
+               "w4a8_speedup_over_fp16": round(tot["fp16"] / tot["w4a8"], 2)}
+        log("[detail]", json.dumps(row))
+        rows.append(row)
+    rows.append({"shape": "layer7b.weight_mb", **{k: round(v / 1e6, 1) for k, v in mem.items()}})
+    log("[detail]", json.dumps(rows[-1]))
+    del weights
+    torch.cuda.empty_cache()
+    return rows
+
+
+def act_quant_rows(torch, ql):
+    """The activation quantizer alone and with the operand transforms fused in front of it (SmoothQuant per-channel
+    multiply, block Hadamard rotation, RMSNorm), graph-replayed; 3 B per element."""
+    rows = []
+    for M, K in ((2048, 1536), (4096, 4096), (4096, 11008)):
+        x = torch.randn((M, K), dtype=torch.float16, device="cuda:0")
+        kl = torch.empty(ql.ql_act_kernel_bytes(M, K), dtype=torch.uint8, device="cuda:0")
+        sxv = torch.empty(M, dtype=torch.float32, device="cuda:0")
+        inv = torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5
+        B = ql.ql_hadamard_block(K)
+        gam = (torch.rand(K, dtype=torch.float32, device="cuda:0") + 0.5).to(torch.float16)
+        row = {"shape": f"act_quant.M{M}.K{K}"}
+        for name, fn in (("plain", lambda i: ql.ql_quant_act_per_token(x, None, kl, sxv)),
+                         ("smoothquant", lambda i: ql.ql_quant_act_per_token_transformed(x, inv, 0, None, kl, sxv)),
+                         ("hadamard", lambda i: ql.ql_quant_act_per_token_transformed(x, None, B, None, kl, sxv)),
+                         ("rmsnorm", lambda i: ql.ql_quant_act_rmsnorm(x, gam, 1e-6, None, kl, sxv))):
+            t = median_ms(torch, fn, MIN_LAUNCHES, 3, graph=True)
+            row[name + "_us"] = round(t * 1e3, 2)
+            row[name + "_gbs"] = round(3 * M * K / (t * 1e-3) / 1e9, 1)
+        log("[detail]", json.dumps(row))
+        rows.append(row)
+        del x, kl
+    return rows
 
 
 if __name__ == "__main__":

@@ -100,7 +100,9 @@ int ql_quant_act_per_token(const void *x, int64_t ldx, int M, int K,
 /* RMSNorm fused in front of the per-token quantizer (the normalisation a decoder layer applies to the input of its
  * QKV and gate/up projections; textbook definition, the paper does not spell it out):
  *     h[m,k] = x[m,k] / sqrt(mean_k(x[m,:]^2) + eps) * gamma[k],   then Eq. 1-2 on h as in ql_quant_act_per_token.
- * Arithmetic: the sum of squares is the exact sum rounded once to fp32 (accumulated in fp64), every later step one
+ * Arithmetic: the sum of squares is accumulated in fp64 (within ~1e-13 relative of the exact sum) and then rounded to
+ * fp32 -- the correctly rounded exact sum except when the exact sum lies that close to an fp32 rounding boundary
+ * (bit-identical to the reference arithmetic almost surely, not by construction); every later step is one
  * correctly rounded fp32 operation (divide by K, add eps, square root, reciprocal, two multiplies per element).
  *   x      device, fp16 [M, ldx] (as ql_quant_act_per_token);  gamma  device, fp16 [K], 16-byte aligned
  *   eps    finite, >= 0 (a token with mean(x^2) + eps == 0 is the caller's error: its codes are unspecified)
@@ -156,7 +158,8 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
                          int N, int32_t *acc, int32_t *partials, int row0, int nrows,
                          void *ws, size_t ws_bytes, void *stream);
 
-/* Kernel selection, for tests and tuning (process-wide, not thread-safe):
+/* Kernel selection, for tests and tuning (a setting of the calling thread: it applies to the GEMM calls this
+ * thread makes afterwards; other threads keep theirs, initially 0):
  *   0 = automatic (decode kernels for M <= 32; up to 1024 tokens whichever of the decode kernels, working on
  *       blocks of 64 or 32 tokens, and the prefill tile kernels has the lower estimated time; prefill tiles beyond)
  *   1 = automatic among the prefill tile kernels, 100 = automatic among the decode kernels (M <= 1024)
@@ -247,17 +250,6 @@ int ql_quant_act_opt(const void *x, int64_t ldx, int M, int K, int range, int sc
 /* scope: QL_SCOPE_FINE or QL_SCOPE_TENSOR. */
 int ql_quant_weight_opt(const void *w, int N, int K, int bits, int group, int range, int scope,
                         void *wq_canonical, void *scales, void *wq_kernel, void *scratch, void *stream);
-
-/* Ceiling probes for benchmarks (nothing of the method): what the GPU sustains on the two resources the
- * layer is bound by, to be timed by the caller with events on `stream`.
- *   ql_probe_mfma_int8: `workgroups` workgroups of 8 wavefronts each issue 4*iters register-resident
- *     32x32x32 int8 matrix instructions; operands constant (random_operands = 0) or hashed per lane (the
- *     shader clock depends on data toggling).  *ops (host, may be NULL) receives the operation count.
- *   ql_probe_hbm_read: streams `bytes` bytes of `buf` once through non-temporal 16-byte loads.
- * `sink` is a device int the kernels never actually write (it keeps their loops alive). */
-int ql_probe_mfma_int8(int workgroups, int iters, int random_operands, void *sink, int64_t *ops /* host */,
-                       void *stream);
-int ql_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -95,7 +95,9 @@ def rmsnorm_act(x16: np.ndarray, gamma16: np.ndarray, eps: float) -> np.ndarray:
     linears sit in; the paper does not spell it out -- this is the textbook definition, Zhang & Sennrich 2019):
         h_k = x_k / sqrt(mean_k(x^2) + eps) * gamma_k
     Reading, one correctly rounded fp32 operation per step, so that a fused kernel can be bit-identical:
-        ss   = fp32(sum_k x_k^2)          the EXACT sum (every square of an fp16 value is exact), rounded once
+        ss   = fp32(fp64(sum_k x_k^2))    the exact sum (every square of an fp16 value is exact) rounded to fp64
+                                          (math.fsum), then to fp32: two roundings, which differ from a single one
+                                          only if the fp64 value lands exactly on an fp32 tie
         mean = ss / K                     K as fp32 (exact up to 2^24)
         r    = 1 / sqrt(mean + eps)       one addition, one square root, one division
         h_k  = (x_k * r) * gamma_k        two multiplications, gamma widened from fp16

@@ -1,11 +1,15 @@
-// Ceiling probes for the benchmark: what this GPU sustains on the two resources the linear layer is
-// bound by, measured in the same job as the kernels (they compute nothing of the method).
+// Ceiling probes for the benchmark (libqlprobe.so, a helper library of its own: not part of the quantized
+// linear layer's C ABI): what this GPU sustains on the two resources the layer is bound by, measured in the
+// same job as the kernels.  They compute nothing of the method.
 //   * int8 matrix pipe: register-resident v_mfma_i32_32x32x32_i8 loop on every CU, operands either
 //     constant or hashed per lane (the shader clock drops under data toggling, so the two differ);
 //   * HBM read stream: every lane sums 16-byte non-temporal loads over a buffer larger than the caches.
-#include "common.h"
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
-namespace ql {
+#include "qlprobe.h"
+
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -61,17 +65,25 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__
 
 }  // namespace
 
-int launch_probe_mfma(int workgroups, int iters, int random_operands, int *sink, hipStream_t st)
+extern "C" {
+
+__attribute__((visibility("default"))) int qlprobe_mfma_int8(int workgroups, int iters, int random_operands, void *sink,
+                                                             int64_t *ops, void *stream)
 {
-    hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(PROBE_WAVES * 64), 0, st, iters, random_operands, sink);
-    return check_hip(hipGetLastError(), "probe_mfma launch");
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24) || !sink) return 1;
+    // 8 wavefronts x 4 instructions per iteration x 2*32*32*32 operations
+    if (ops) *ops = (int64_t)workgroups * PROBE_WAVES * PROBE_ACC * iters * 65536;
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(PROBE_WAVES * 64), 0, static_cast<hipStream_t>(stream),
+                       iters, random_operands != 0, static_cast<int *>(sink));
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
-int launch_probe_read(const void *buf, size_t bytes, int *sink, hipStream_t st)
+__attribute__((visibility("default"))) int qlprobe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream)
 {
-    hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, st, static_cast<const v4i *>(buf), bytes / 16,
-                       sink);
-    return check_hip(hipGetLastError(), "probe_read launch");
+    if (!buf || !sink || (reinterpret_cast<uintptr_t>(buf) & 15) || bytes % 16) return 1;
+    hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const v4i *>(buf), bytes / 16, static_cast<int *>(sink));
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
-}  // namespace ql
+}  // extern "C"

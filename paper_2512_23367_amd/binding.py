@@ -23,7 +23,6 @@ EXPORTS = [
     "ql_quant_act_per_token", "ql_quant_act_rmsnorm", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
     "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
     "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant", "ql_plan_gemm",
-    "ql_probe_mfma_int8", "ql_probe_hbm_read",
     "ql_hadamard_block", "ql_smooth_calibrate", "ql_smooth_scales",
     "ql_quant_act_per_token_transformed", "ql_quant_weight_transformed",
     "ql_act_scale_calibrate", "ql_quant_act_opt", "ql_quant_weight_opt",
@@ -84,8 +83,6 @@ def lib() -> ctypes.CDLL:
             "ql_w4a8_gemm": [vp, vp, i, i, vp, i, vp, i, vp, i64, vp, sz, vp],
             "ql_w8a8_gemm_acc_i32": [vp, i, i, vp, i, vp, vp, sz, vp],
             "ql_w4a8_gemm_acc_i32": [vp, i, i, vp, i, i, vp, vp, i, i, vp, sz, vp],
-            "ql_probe_mfma_int8": [i, i, i, vp, c.POINTER(c.c_int64), vp],
-            "ql_probe_hbm_read": [vp, sz, vp, vp],
             "ql_hadamard_block": [i, c.POINTER(c.c_int)],
             "ql_smooth_calibrate": [vp, i64, i, i, vp, vp],
             "ql_smooth_scales": [vp, vp, i, i, c.c_float, vp, vp, vp],
@@ -144,18 +141,6 @@ def ql_plan_gemm(M: int, N: int, K: int, bits: int, group: int, scratch_bytes: i
     plan = QlPlan()
     _check(lib().ql_plan_gemm(M, N, K, bits, group, scratch_bytes, ctypes.byref(plan)))
     return plan
-
-
-def ql_probe_mfma_int8(workgroups: int, iters: int, random_operands: bool, sink) -> int:
-    """Enqueues the matrix-pipe ceiling probe; returns the number of int8 operations it performs."""
-    ops = ctypes.c_int64()
-    _check(lib().ql_probe_mfma_int8(workgroups, iters, int(random_operands), _p(sink), ctypes.byref(ops), _stream()))
-    return ops.value
-
-
-def ql_probe_hbm_read(buf, sink):
-    """Enqueues one pass of the HBM read-stream probe over the whole of `buf`."""
-    _check(lib().ql_probe_hbm_read(_p(buf), buf.numel() * buf.element_size(), _p(sink), _stream()))
 
 
 def ql_hadamard_block(K: int) -> int:
@@ -270,9 +255,31 @@ def _ws(ws):
     return (_p(ws), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
 
 
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def _check_gemm_buffers(M, K, N, bits, group, w_kernel, sw, bias, y, xq_kernel=None, sx=None):
+    """Host-side size checks the C side cannot make (it sees pointers only): a buffer that is too small or of the
+    wrong layout would be read or written out of bounds by the kernels."""
+    if w_kernel is None or _nbytes(w_kernel) < ql_weight_bytes(N, K, bits, group)[2]:
+        raise ValueError("w_kernel is smaller than the kernel-layout blob of ql_weight_bytes (canonical codes passed?)")
+    if y.dim() != 2 or tuple(y.shape) != (M, N) or (M and y.stride(1) != 1):
+        raise ValueError(f"y must be [M,N] = [{M},{N}] with unit inner stride")
+    if bits == 8 and (sw is None or sw.numel() < N):
+        raise ValueError("sw needs N fp32 entries")
+    if bias is not None and (bias.dtype != torch.float16 or bias.numel() < N):
+        raise ValueError("bias must be fp16 with N entries")
+    if xq_kernel is not None and _nbytes(xq_kernel) < ql_act_kernel_bytes(M, K):
+        raise ValueError("xq_kernel is smaller than ql_act_kernel_bytes")
+    if sx is not None and (sx.dtype != torch.float32 or sx.numel() < M):
+        raise ValueError("sx needs M fp32 entries")
+
+
 def ql_w8a8_linear(x, wq_kernel, sw, bias, N, y, ws):
     _want(x, torch.float16, "x"), _want(y, torch.float16, "y"), _want(sw, torch.float32, "sw")
     M, K = x.shape
+    _check_gemm_buffers(M, K, N, 8, 0, wq_kernel, sw, bias, y)
     wsp, wsb = _ws(ws)
     _check(lib().ql_w8a8_linear(_p(x), _ld(x) if M else K, M, K, _p(wq_kernel), _p(sw), _p(bias), N, _p(y),
                                 _ld(y) if M else N, wsp, wsb, _stream()))
@@ -281,18 +288,23 @@ def ql_w8a8_linear(x, wq_kernel, sw, bias, N, y, ws):
 def ql_w4a8_linear(x, w4_kernel, group, bias, N, y, ws):
     _want(x, torch.float16, "x"), _want(y, torch.float16, "y")
     M, K = x.shape
+    _check_gemm_buffers(M, K, N, 4, group, w4_kernel, None, bias, y)
     wsp, wsb = _ws(ws)
     _check(lib().ql_w4a8_linear(_p(x), _ld(x) if M else K, M, K, _p(w4_kernel), group, _p(bias), N, _p(y),
                                 _ld(y) if M else N, wsp, wsb, _stream()))
 
 
 def ql_w8a8_gemm(xq_kernel, sx, M, K, wq_kernel, sw, bias, N, y, ws=None):
+    _want(y, torch.float16, "y")
+    _check_gemm_buffers(M, K, N, 8, 0, wq_kernel, sw, bias, y, xq_kernel, sx)
     wsp, wsb = _ws(ws)
     _check(lib().ql_w8a8_gemm(_p(xq_kernel), _p(sx), M, K, _p(wq_kernel), _p(sw), _p(bias), N, _p(y),
                               _ld(y) if M else N, wsp, wsb, _stream()))
 
 
 def ql_w4a8_gemm(xq_kernel, sx, M, K, w4_kernel, group, bias, N, y, ws=None):
+    _want(y, torch.float16, "y")
+    _check_gemm_buffers(M, K, N, 4, group, w4_kernel, None, bias, y, xq_kernel, sx)
     wsp, wsb = _ws(ws)
     _check(lib().ql_w4a8_gemm(_p(xq_kernel), _p(sx), M, K, _p(w4_kernel), group, _p(bias), N, _p(y),
                               _ld(y) if M else N, wsp, wsb, _stream()))
@@ -300,12 +312,22 @@ def ql_w4a8_gemm(xq_kernel, sx, M, K, w4_kernel, group, bias, N, y, ws=None):
 
 def ql_w8a8_gemm_acc_i32(xq_kernel, M, K, wq_kernel, N, acc, ws=None):
     _want(acc, torch.int32, "acc")
+    if acc.numel() < M * N or not acc.is_contiguous():
+        raise ValueError("acc must be a contiguous int32 [M,N]")
+    if _nbytes(wq_kernel) < ql_weight_bytes(N, K, 8, 0)[2] or _nbytes(xq_kernel) < ql_act_kernel_bytes(M, K):
+        raise ValueError("wq_kernel / xq_kernel smaller than their size queries report")
     wsp, wsb = _ws(ws)
     _check(lib().ql_w8a8_gemm_acc_i32(_p(xq_kernel), M, K, _p(wq_kernel), N, _p(acc), wsp, wsb, _stream()))
 
 
 def ql_w4a8_gemm_acc_i32(xq_kernel, M, K, w4_kernel, group, N, acc, partials=None, row0=0, nrows=0, ws=None):
     _want(acc, torch.int32, "acc")
+    if acc.numel() < M * N or not acc.is_contiguous():
+        raise ValueError("acc must be a contiguous int32 [M,N]")
+    if _nbytes(w4_kernel) < ql_weight_bytes(N, K, 4, group)[2] or _nbytes(xq_kernel) < ql_act_kernel_bytes(M, K):
+        raise ValueError("w4_kernel / xq_kernel smaller than their size queries report")
+    if partials is not None and (partials.dtype != torch.int32 or partials.numel() < nrows * (K // group) * N):
+        raise ValueError("partials must be int32 [nrows, K/group, N]")
     wsp, wsb = _ws(ws)
     _check(lib().ql_w4a8_gemm_acc_i32(_p(xq_kernel), M, K, _p(w4_kernel), group, N, _p(acc), _p(partials), row0,
                                       nrows, wsp, wsb, _stream()))

@@ -9,7 +9,7 @@
 namespace ql {
 
 static thread_local char g_err[512] = "";
-static int g_variant = 0;
+static thread_local int g_variant = 0;   // kernel selection of the calling thread (ql_set_kernel_variant)
 
 int fail(int status, const char *fmt, ...)
 {
@@ -244,23 +244,6 @@ int ql_plan_gemm(int M, int N, int K, int bits, int group, size_t scratch_bytes,
         plan->est_us = prefill_estimate_us(a);
     }
     return QL_OK;
-}
-
-int ql_probe_mfma_int8(int workgroups, int iters, int random_operands, void *sink, int64_t *ops, void *stream)
-{
-    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 24))
-        return fail(QL_ERR_SHAPE, "probe: workgroups in [1,65536], iters in [1,2^24]");
-    if (!sink) return fail(QL_ERR_NULL, "sink is NULL");
-    // 8 wavefronts x 4 instructions per iteration x 2*32*32*32 operations
-    if (ops) *ops = (int64_t)workgroups * 8 * 4 * iters * 65536;
-    return launch_probe_mfma(workgroups, iters, random_operands != 0, static_cast<int *>(sink), static_cast<hipStream_t>(stream));
-}
-
-int ql_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream)
-{
-    if (!buf || !sink) return fail(QL_ERR_NULL, "buf or sink is NULL");
-    if (!aligned(buf, 16) || bytes % 16) return fail(QL_ERR_ALIGN, "probe: buf 16-byte aligned, bytes a multiple of 16");
-    return launch_probe_read(buf, bytes, static_cast<int *>(sink), static_cast<hipStream_t>(stream));
 }
 
 int ql_weight_bytes(int N, int K, int bits, int group, size_t *canonical, size_t *scales, size_t *kernel)

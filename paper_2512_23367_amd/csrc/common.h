@@ -126,8 +126,6 @@ struct GemmArgs {
     void *ws;
     size_t ws_bytes;
 };
-int launch_probe_mfma(int workgroups, int iters, int random_operands, int *sink, hipStream_t st);
-int launch_probe_read(const void *buf, size_t bytes, int *sink, hipStream_t st);
 int launch_gemm_prefill(const GemmArgs &a, int variant, hipStream_t st);
 int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st);
 // estimated time (us) of the automatic choice of the tile kernels / of the decode kernels (33 tokens and more)

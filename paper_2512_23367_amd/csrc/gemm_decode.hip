@@ -316,11 +316,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         // load -> unpack -> multiply -> fold -> reduce chain better than a deeper ring does
         constexpr int U = C >= 4 ? 1 : 4 / C;   // without XL a slot also holds token fragments
         v4i wv[U][C], xv[XL ? 1 : U][2][MH];
-        // 17 tokens and more (fp16 output, 8 wavefronts): branch-free refills through range-checked buffer loads, as
+        // 17 tokens and more (8 wavefronts; the accumulator dump runs the same loop): branch-free refills through range-checked buffer loads, as
         // in the int8 loop above (absent rows and channel groups: lane offset behind the buffer; groups past this
         // wavefront's range: a buffer of zero length).  Measured on one box against the conditional pointer loads:
         // 2-10 % faster at 64 tokens, 1-4 % at 128, 3-5 % slower with 16 wavefronts (kept on the old loop).
-        constexpr bool BR = !XL && MH >= 2 && EPI == EPI_F16 && WAVES == 8;
+        constexpr bool BR = !XL && MH >= 2 && WAVES == 8;
         constexpr unsigned OOB = 0xFFFFF000u;
         unsigned wo[C], xo[MH];
 #pragma unroll
@@ -536,14 +536,11 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     const int grid = ceil_div(p.Npad / 16, C);
     const size_t xs_bytes = (XL ? (size_t)(a.M + 1) * a.K : 0) + (W4 ? (size_t)C * (a.K / 128) * 32 : 0);
     if (XL || W4) {   // static reduction buffer + staged tokens/scales can exceed the default 64 KB limit
-        static bool attr_set = false;
-        if (!attr_set) {
-            QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(
-                                                     gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, 40960 + 32768),
-                             "hipFuncSetAttribute(max dynamic LDS)"));
-            attr_set = true;
-        }
+        // once per kernel and process; the initialisation of a function-local static is thread-safe
+        static const hipError_t attr_status = hipFuncSetAttribute(
+            reinterpret_cast<const void *>(gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, 40960 + 32768);
+        QL_TRY(check_hip(attr_status, "hipFuncSetAttribute(max dynamic LDS)"));
     }
     hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid, MH >= 2 ? ceil_div(a.M, 16 * MH) : 1),
                        dim3(WAVES * 64), xs_bytes, st, p);

@@ -164,15 +164,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     // split-K: this workgroup multiplies stages [stage0, stage0 + nstages) only (never an empty range)
     const int stage0 = blockIdx.y * p.stages_per_split;
     const int nstages = min(p.stages_per_split, KB / KBS - stage0);
-    const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, p.x_bytes);
-    const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, p.w_bytes);
-    const __amdgpu_buffer_rsrc_t sr = make_rsrc(p.wscales, W4 ? (unsigned)(p.K / 128) * p.Npad * 2u : 0u);
-    const unsigned voff = lane * 16;
+    const unsigned s_bytes = W4 ? (unsigned)(p.K / 128) * p.Npad * 2u : 0u;
+    const unsigned lane16 = lane * 16;
 
     // Fragment f of a stage lives at LDS offset f*1024 (activation fragments first) and, in global memory, at
     //   row-block base + (stage * fragments-per-row-block + f % fragments-per-row-block) * 1024.
+    // Range checking: the whole byte offset travels in the per-lane (vector) offset, the scalar offset stays 0,
+    // so the hardware compares exactly that offset with the buffer's size: row-blocks beyond ceil32(M) /
+    // ceil32(N) inside the last tiles return nothing, whichever way the scalar offset enters the check.  The dead
+    // stages behind the last one use buffers of zero length: no traffic, no branch around the loads.
     auto issue_stage = [&](int s) {
         const bool live = s < nstages;
+        const __amdgpu_buffer_rsrc_t xr = make_rsrc(p.xq, live ? p.x_bytes : 0u);
+        const __amdgpu_buffer_rsrc_t wr = make_rsrc(p.wq, live ? p.w_bytes : 0u);
         char *buf = smem + (s % STAGES) * STAGE_BYTES;
         auto load_fragment = [&](int i) {                // i-th load of this wavefront: fragment i*NW + wave
             const int f = i * NW + wave;
@@ -180,25 +184,23 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
             const bool is_x = (XFR % NW == 0) ? (i < XFR / NW) : (f < XFR);
             if (is_x) {
                 const int mb = f / KBS, kb = f % KBS;
-                unsigned off = ((unsigned)(tm * TMB + mb) * KB + (stage0 + s) * KBS + kb) * 1024u;
-                if (!live) off = 0xFFFFF000u;            // beyond the buffer: the load returns nothing
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(buf + f * 1024), 16, voff, off, 0, 0);
+                const unsigned off = ((unsigned)(tm * TMB + mb) * KB + (stage0 + s) * KBS + kb) * 1024u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, LDS_PTR(buf + f * 1024), 16, lane16 + off, 0, 0, 0);
             } else {
                 const int g = f - XFR;
                 const int nb = g / WKB, kb = g % WKB;
-                unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + (stage0 + s) * WKB + kb) * 1024u;
-                if (!live) off = 0xFFFFF000u;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + f * 1024), 16, voff, off, 0, 0);
+                const unsigned off = ((unsigned)(tn * TNB + nb) * (KB / (W4 ? 2 : 1)) + (stage0 + s) * WKB + kb) * 1024u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, LDS_PTR(buf + f * 1024), 16, lane16 + off, 0, 0, 0);
             }
         };
 #pragma unroll
         for (int i = 0; i < FR / NW; ++i) load_fragment(i);
         if (NHI != 0 && wave < NHI) load_fragment(FR / NW);
         if (SCALE_DMA) {   // stage s = scale group s: 4 bytes per lane, the first WN*16 lanes carry the wavefront's channels
-            unsigned off = ((unsigned)(stage0 + s) * p.Npad + (tn * TNB + wn * WN) * 32) * 2u;
-            if (!live) off = 0xFFFFF000u;
+            const __amdgpu_buffer_rsrc_t sr = make_rsrc(p.wscales, live ? s_bytes : 0u);
+            const unsigned off = ((unsigned)(stage0 + s) * p.Npad + (tn * TNB + wn * WN) * 32) * 2u;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(sr, LDS_PTR(scale_slots + ((s % STAGES) * NW + wave) * 256), 4,
-                                                     lane * 4, off, 0, 0);
+                                                     lane * 4 + off, 0, 0, 0);
         }
     };
 
@@ -663,13 +665,10 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N * WK) + 1) <= 63, "vmcnt range");
     auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP, WK>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        QL_TRY(check_hip(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, LDS),
-                         "hipFuncSetAttribute(max dynamic LDS)"));
-        attr_set = true;
-    }
+    // once per kernel and process; the initialisation of a function-local static is thread-safe
+    static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+    QL_TRY(check_hip(attr_status, "hipFuncSetAttribute(max dynamic LDS)"));
     PrefillParams p;
     p.xq = a.xq;
     p.wq = a.wq;

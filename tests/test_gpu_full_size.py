@@ -2,12 +2,22 @@
 
 The GPU computes the whole layer; the oracle recomputes a stratified sample of token rows (rows are
 independent under per-token quantization): the first and last row of every 256-row tile plus seeded
-random rows, all N columns.  Weights quantized on the GPU are compared bit-for-bit in full.
+random rows, all N columns.  Checked per shape:
+  * weights quantized on the GPU against the oracle's own quantization of the same fp16 weights, in full, bit
+    for bit (codes and scales);
+  * activation codes and scales of the sampled rows, bit for bit;
+  * the raw int32 accumulators of the full-size GEMM (the accumulator hook runs the same main loop, tile order
+    and kernel choice as the fp16 call) on the sampled rows, bit for bit -- for int4 weights the sums over the
+    groups and, for a window of rows that straddles a token-tile edge, every group partial;
+  * the fp16 output of the sampled rows within 1e-3 (max-abs error normalised by the largest reference value).
+The oracle works from its own quantized weights throughout; nothing it consumes comes from the GPU.
 """
 import numpy as np
 import pytest
+import torch
 
 import oracle
+from paper_2512_23367_amd import binding as ql
 from paper_2512_23367_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -28,27 +38,67 @@ def _sample_rows(M, seed, extra=24):
     return np.array(rows)
 
 
+def _scratch_bytes(sh):
+    """The split-K scratch a ql_*_linear call of this shape hands to its GEMM: what ql_workspace_bytes reports
+    beyond the quantized activations and their scales."""
+    up = lambda n: (n + 255) // 256 * 256
+    return ql.ql_workspace_bytes(sh.M, sh.N, sh.K, sh.bits) - up(ql.ql_act_kernel_bytes(sh.M, sh.K)) - up(4 * sh.M)
+
+
 def _check_shape(G, sh):
     x, w, b = synth.tensors(sh)
     g = G.gpu_quant_weight(w, sh.bits, sh.group)
     if sh.bits == 8:
         wq_o, sw_o = oracle.quant_weight_int8(w)
-        assert (g["canon"] == wq_o).all() and (g["scales"] == sw_o).all()
+        assert (g["canon"] == wq_o).all() and (g["scales"].view(np.uint32) == sw_o.view(np.uint32)).all()
     else:
-        p_o, _, s_o = oracle.quant_weight_int4(w, sh.group)
-        assert (g["canon"] == p_o).all() and (g["scales"].view(np.uint16) == s_o.view(np.uint16)).all()
+        wq_o, _, sw_o = oracle.quant_weight_int4(w, sh.group)
+        assert (g["canon"] == wq_o).all() and (g["scales"].view(np.uint16) == sw_o.view(np.uint16)).all()
     y = G.gpu_linear(x, g, b)
     rows = _sample_rows(sh.M, sh.K + sh.N)
     if sh.bits == 8:
-        ref = oracle.linear_w8a8(x[rows], g["canon"], g["scales"], b)
+        ref = oracle.linear_w8a8(x[rows], wq_o, sw_o, b)
     else:
-        ref = oracle.linear_w4a8(x[rows], g["canon"], g["scales"], sh.group, b)
+        ref = oracle.linear_w4a8(x[rows], wq_o, sw_o, sh.group, b)
     assert np.isfinite(y).all()
     # normalise by the largest magnitude of the sampled reference rows
     assert G.norm_err(y[rows], ref["y64"]) <= TOL, sh.name
     # activation codes of the sampled rows, bit-exact
     xq_g, sx_g, _ = G.gpu_quant_act(x[rows])
-    assert (xq_g == ref["xq"]).all() and (sx_g == ref["sx"]).all()
+    assert (xq_g == ref["xq"]).all() and (sx_g.view(np.uint32) == ref["sx"].view(np.uint32)).all()
+
+    # integer accumulators of the full problem: the GPU quantizes all tokens (bit-checked on the sampled rows
+    # above), the accumulator hook multiplies them with the same kernel choice as the fp16 call
+    xd = G.dev(x)
+    xk = G.empty_bytes(ql.ql_act_kernel_bytes(sh.M, sh.K))
+    sx = torch.empty(sh.M, dtype=torch.float32, device=G.DEV)
+    ql.ql_quant_act_per_token(xd, None, xk, sx)
+    acc = torch.full((sh.M, sh.N), -12345, dtype=torch.int32, device=G.DEV)
+    scratch = _scratch_bytes(sh)
+    ws = G.empty_bytes(scratch) if scratch > 0 else None
+    rows_d = torch.from_numpy(rows).to(G.DEV)
+    if sh.bits == 8:
+        ql.ql_w8a8_gemm_acc_i32(xk, sh.M, sh.K, g["kernel"], sh.N, acc, ws)
+        torch.cuda.synchronize()
+        assert (acc[rows_d].cpu().numpy() == ref["acc"]).all(), sh.name
+    else:
+        # totals first (split-K allowed, as in the fp16 call), then the group partials of a row window across the
+        # first 128-token tile edge (the partials dump takes the unsplit kernel)
+        ql.ql_w4a8_gemm_acc_i32(xk, sh.M, sh.K, g["kernel"], sh.group, sh.N, acc, None, 0, 0, ws)
+        torch.cuda.synchronize()
+        assert (acc[rows_d].cpu().numpy() == ref["acc"]).all(), sh.name
+        row0 = max(0, min(sh.M - 8, 124))
+        nrows = min(8, sh.M)
+        G_ = sh.K // sh.group
+        part = torch.full((nrows, G_, sh.N), -12345, dtype=torch.int32, device=G.DEV)
+        acc.fill_(-12345)
+        ql.ql_w4a8_gemm_acc_i32(xk, sh.M, sh.K, g["kernel"], sh.group, sh.N, acc, part, row0, nrows, None)
+        torch.cuda.synchronize()
+        xq_w, _ = oracle.quant_act_per_token(x[row0:row0 + nrows])
+        _, total, part_o = oracle.igemm_grouped(xq_w, oracle.unpack_int4(wq_o), sw_o, sh.group, want_partials=True)
+        assert (part.cpu().numpy() == part_o).all(), sh.name
+        assert (acc[row0:row0 + nrows].cpu().numpy() == total).all(), sh.name
+        assert (acc[rows_d].cpu().numpy() == ref["acc"]).all(), sh.name
 
 
 @pytest.fixture(scope="module")
@@ -88,12 +138,13 @@ def _few_token_shapes():
 
 @pytest.mark.parametrize("sh", _few_token_shapes(), ids=lambda s: s.name)
 def test_config4_few_tokens(G, sh):
-    """64 and 256 tokens on the 7B shapes (the benchmark's few-token detail rows): the automatic choice between
-    the decode kernels on token blocks and the tile kernels, every sampled row against the oracle."""
+    """64 and 256 tokens on the 7B shapes: the automatic choice between the decode kernels on token blocks and
+    the tile kernels (split-K included), every sampled row against the oracle."""
     _check_shape(G, sh)
 
 
-def test_config4_long_prefill_accumulators(G):
-    """M=16384 down projection: integer accumulators of sampled rows, bit-exact, plus the fp16 layer."""
+def test_config4_long_prefill(G):
+    """M=16384 down projection (64 token tiles, several passes over the CUs, every XCD's share of the tile order):
+    accumulators of the sampled rows bit-exact, fp16 layer within tolerance."""
     sh = [s for s in synth.workload(4) if s.M > 32][0]
     _check_shape(G, sh)

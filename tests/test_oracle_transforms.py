@@ -1,5 +1,5 @@
 """Pins for the oracle's SmoothQuant (paper Eq. 3) and Hadamard (Eq. 4) transforms: library Hadamard matrices,
-exact integer cases, closed forms, the equivalence the paper states, and the effect its Figure 2 shows."""
+exact integer cases, closed forms, the equivalence the paper states, and the effect its Figure 1 shows."""
 from fractions import Fraction
 
 import numpy as np
@@ -125,7 +125,7 @@ def test_eq3_equivalence_in_full_precision():
     np.testing.assert_allclose(got, ref, atol=1e-6 * np.abs(ref).max())
 
 
-# ------------------------------------------------------------------ what the transforms are for (Figure 2, Table 2)
+# ------------------------------------------------------------------ what the transforms are for (Figure 1, Table 2)
 def _rel(y, ref):
     return np.linalg.norm(y - ref) / np.linalg.norm(ref)
 
