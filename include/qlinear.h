@@ -136,6 +136,21 @@ int ql_w8a8_linear(const void *x, int64_t ldx, int M, int K,
                    const void *wq_kernel, const float *sw, const void *bias, int N,
                    void *y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
 
+/* ql_w8a8_linear for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arithmetic, kernels and results as ql_w8a8_linear; the workspace
+ * (quantized activations, their scales, split-K partial sums) is a static device array of QL_STATIC_WS_BYTES that
+ * belongs to the library -- every GPU the library runs on holds it until the process ends.  The call allocates
+ * and frees nothing (the array's device address is looked up once per device, on the first call there).
+ *   limit   ceil32(M)*K + 4*M (each rounded up to 256) <= QL_STATIC_WS_BYTES, else QL_ERR_WORKSPACE and nothing
+ *           is launched (use ql_w8a8_linear with your own workspace)
+ *   sharing every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different
+ *           streams or threads) race; the array keeps the last call's contents, nothing in it has to start at zero
+ * Other arguments and errors as ql_w8a8_linear. */
+#define QL_STATIC_WS_BYTES (64u << 20)
+int ql_w8a8_linear_static(const void *x, int64_t ldx, int M, int K,
+                          const void *wq_kernel, const float *sw, const void *bias, int N,
+                          void *y, int64_t ldy, void *stream);
+
 /* W4A8 linear layer (group scales live in the blob). */
 int ql_w4a8_linear(const void *x, int64_t ldx, int M, int K,
                    const void *w4_kernel, int group, const void *bias, int N,

@@ -21,7 +21,7 @@ STATUS_NAMES = {0: "QL_OK", 1: "QL_ERR_NULL", 2: "QL_ERR_SHAPE", 3: "QL_ERR_ALIG
 EXPORTS = [
     "ql_version", "ql_last_error", "ql_weight_bytes", "ql_act_kernel_bytes", "ql_workspace_bytes",
     "ql_quant_act_per_token", "ql_quant_act_rmsnorm", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
-    "ql_w8a8_linear", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
+    "ql_w8a8_linear", "ql_w8a8_linear_static", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
     "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant", "ql_plan_gemm",
     "ql_hadamard_block", "ql_smooth_calibrate", "ql_smooth_scales",
     "ql_quant_act_per_token_transformed", "ql_quant_weight_transformed",
@@ -79,6 +79,7 @@ def lib() -> ctypes.CDLL:
             "ql_export_canonical": [vp, i, i, i, i, vp, vp, vp],
             "ql_w8a8_linear": [vp, i64, i, i, vp, vp, vp, i, vp, i64, vp, sz, vp],
             "ql_w4a8_linear": [vp, i64, i, i, vp, i, vp, i, vp, i64, vp, sz, vp],
+            "ql_w8a8_linear_static": [vp, i64, i, i, vp, vp, vp, i, vp, i64, vp],
             "ql_w8a8_gemm": [vp, vp, i, i, vp, vp, vp, i, vp, i64, vp, sz, vp],
             "ql_w4a8_gemm": [vp, vp, i, i, vp, i, vp, i, vp, i64, vp, sz, vp],
             "ql_w8a8_gemm_acc_i32": [vp, i, i, vp, i, vp, vp, sz, vp],
@@ -283,6 +284,15 @@ def ql_w8a8_linear(x, wq_kernel, sw, bias, N, y, ws):
     wsp, wsb = _ws(ws)
     _check(lib().ql_w8a8_linear(_p(x), _ld(x) if M else K, M, K, _p(wq_kernel), _p(sw), _p(bias), N, _p(y),
                                 _ld(y) if M else N, wsp, wsb, _stream()))
+
+
+def ql_w8a8_linear_static(x, wq_kernel, sw, bias, N, y):
+    """ql_w8a8_linear on the library's own static workspace (allocates nothing)."""
+    _want(x, torch.float16, "x"), _want(y, torch.float16, "y"), _want(sw, torch.float32, "sw")
+    M, K = x.shape
+    _check_gemm_buffers(M, K, N, 8, 0, wq_kernel, sw, bias, y)
+    _check(lib().ql_w8a8_linear_static(_p(x), _ld(x) if M else K, M, K, _p(wq_kernel), _p(sw), _p(bias), N, _p(y),
+                                       _ld(y) if M else N, _stream()))
 
 
 def ql_w4a8_linear(x, w4_kernel, group, bias, N, y, ws):

@@ -5,6 +5,7 @@
 
 #include "common.h"
 #include <cmath>
+#include <mutex>
 
 namespace ql {
 
@@ -196,6 +197,34 @@ int linear_common(const void *x, int64_t ldx, int M, int K, const void *wq, cons
 }  // namespace ql
 
 using namespace ql;
+
+// ---- workspace of ql_w8a8_linear_static: device memory that belongs to the library, for callers that cannot allocate.
+// Every GPU the library runs on holds its own copy of the array (at its own address) until the process ends.  In
+// host code the array's name is only a handle for hipGetSymbolAddress: the device address is looked up once per
+// device, with that device current, and only that address is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[QL_STATIC_WS_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+
+int static_scratch(void **out)
+{
+    int dev = -1;
+    QL_TRY(check_hip(hipGetDevice(&dev), "hipGetDevice"));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(QL_ERR_UNSUPPORTED, "device index %d beyond %d", dev, MAX_DEVICES - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        QL_TRY(check_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(static workspace)"));
+        if (!ptr) return fail(QL_ERR_HIP, "hipGetSymbolAddress returned a null address for the static workspace");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return QL_OK;
+}
+}  // namespace
 
 #pragma GCC visibility push(default)
 extern "C" {
@@ -516,6 +545,25 @@ int ql_w4a8_linear(const void *x, int64_t ldx, int M, int K, const void *w4_kern
 {
     return linear_common(x, ldx, M, K, w4_kernel, nullptr, 4, group, bias, N, y, ldy, ws, ws_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+int ql_w8a8_linear_static(const void *x, int64_t ldx, int M, int K, const void *wq_kernel, const float *sw,
+                          const void *bias, int N, void *y, int64_t ldy, void *stream)
+{
+    QL_TRY(check_mk(M, K));
+    QL_TRY(check_nk(N, K, 8));
+    if (M == 0) return QL_OK;
+    // quantized activations + their scales must fit; split-K scratch is taken as far as the rest reaches
+    const size_t need = ws_layout(M, K).total;
+    if (need > (size_t)QL_STATIC_WS_BYTES)
+        return fail(QL_ERR_WORKSPACE,
+                    "ql_w8a8_linear_static: M=%d K=%d needs %zu bytes of workspace, the library's own holds %zu "
+                    "(use ql_w8a8_linear with a caller-allocated workspace)", M, K, need, (size_t)QL_STATIC_WS_BYTES);
+    void *ws = nullptr;
+    QL_TRY(static_scratch(&ws));
+    size_t bytes = need + splitk_scratch(M, N);
+    if (bytes > (size_t)QL_STATIC_WS_BYTES) bytes = QL_STATIC_WS_BYTES;
+    return linear_common(x, ldx, M, K, wq_kernel, sw, 8, 0, bias, N, y, ldy, ws, bytes, static_cast<hipStream_t>(stream));
 }
 
 int ql_w8a8_gemm(const int8_t *xq_kernel, const float *sx, int M, int K, const void *wq_kernel, const float *sw,

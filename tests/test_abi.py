@@ -69,6 +69,9 @@ def test_null_and_alignment_validation_without_launch():
     # ldy not a multiple of 8
     assert lib.ql_w8a8_gemm(vp(0x1000), vp(0x2000), 4, 128, vp(0x3000), vp(0x4000), None, 64, vp(0x5000), 68,
                             None, 0, None) == 3
+    # the static-workspace variant refuses what its 64 MiB array cannot hold, before anything else happens
+    assert lib.ql_w8a8_linear_static(vp(0x1000), 11008, 16384, 11008, vp(0x2000), vp(0x3000), None, 4096, vp(0x4000),
+                                     4096, None) == 5
     # unknown kernel variant
     assert lib.ql_set_kernel_variant(77) == 4
     assert lib.ql_set_kernel_variant(0) == 0
