@@ -174,7 +174,8 @@ def measured_ceilings(torch):
     from paper_2512_23367_amd import probe
     sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     out = {}
-    for name, rnd in (("mfma_int8_constant_operands_tops", False), ("mfma_int8_random_operands_tops", True)):
+    for name, rnd in (("mfma_int8_constant_operands_tops", 0), ("mfma_int8_random_operands_tops", 1),
+                      ("mfma_int8_layer_like_operands_tops", 2), ("mfma_int8_16x16x64_random_operands_tops", 3)):
         ops = [0]
 
         def f(i, rnd=rnd):

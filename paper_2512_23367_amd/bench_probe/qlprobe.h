@@ -2,8 +2,10 @@
  * what the GPU sustains on the two resources the layer is bound by, to be timed by the caller with events on
  * `stream`.  Return 0 on success, 1 for a bad argument, 2 when the launch failed.
  *   qlprobe_mfma_int8: `workgroups` workgroups of 8 wavefronts each issue 4*iters register-resident 32x32x32 int8
- *     matrix instructions; operands constant (random_operands = 0) or hashed per lane (the shader clock depends
- *     on data toggling).  *ops (host, may be NULL) receives the operation count.
+ *     matrix instructions (the same number of operations through twice as many 16x16x64 instructions with
+ *     random_operands = 3); operands constant (random_operands = 0), hashed per lane (1, 3) or distributed like
+ *     a quantized layer's codes (2) -- the shader clock depends on data toggling.  *ops (host, may be NULL)
+ *     receives the operation count.
  *   qlprobe_hbm_read: streams `bytes` bytes of `buf` (device, 16-byte aligned) once through non-temporal 16-byte
  *     loads.
  * `sink` is a device int the kernels never actually write (it keeps their loops alive). */

@@ -236,7 +236,7 @@ const char *ql_last_error(void) { return g_err; }
 int ql_set_kernel_variant(int variant)
 {
     // 0 automatic; 1 automatic among the tile kernels; prefill tile configurations; decode configurations; split-K with 2..32 splits on 128x128 / 256x256 tiles
-    static const int prefill[] = {4, 6, 11, 13, 15, 17, 19, 20, 23};
+    static const int prefill[] = {4, 6, 11, 13, 15, 17, 19, 20, 23, 26, 35, 37, 39, 43};
     bool known = variant == 0 || variant == 1 || (variant >= 100 && variant <= 104) || variant == 106 || variant == 108 || variant == 111 || (variant >= 121 && variant <= 123) || variant == 130 ||
                  (variant >= 202 && variant <= 232) || (variant >= 302 && variant <= 332);
     for (int v : prefill) known = known || variant == v;

@@ -14,6 +14,13 @@
 #include "common.h"
 #include "quant_math.h"
 
+#ifndef QL_RING8
+#define QL_RING8 8     // weight fragments (1 KiB each) a wavefront keeps in flight, int8 weights
+#endif
+#ifndef QL_RING4
+#define QL_RING4 4     // the same for int4 weights
+#endif
+
 namespace ql {
 namespace {
 
@@ -216,7 +223,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const int nchunks = p.K / 64;
         const int per = (nchunks + WAVES - 1) / WAVES;
         const int c0 = wave * per, c1 = (c0 + per < nchunks) ? c0 + per : nchunks;
-        constexpr int U = C >= 8 ? 1 : 8 / C;
+        constexpr int U = C >= QL_RING8 ? 1 : QL_RING8 / C;
         v4i wv[U][C], xv[XL ? 1 : U][MH];
         const int th0 = 4 * c0, th1 = c0 < c1 ? 4 * c1 : 4 * c0;
         if constexpr (!XL && MH >= 2) {
@@ -314,7 +321,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const char *xb4 = reinterpret_cast<const char *>(p.xq) + (2 * (ch / 2)) * 1024 + (r + 32 * (ch % 2)) * 16;
                 // a short ring keeps the register count low: more resident workgroups hide a workgroup's serial
         // load -> unpack -> multiply -> fold -> reduce chain better than a deeper ring does
-        constexpr int U = C >= 4 ? 1 : 4 / C;   // without XL a slot also holds token fragments
+        constexpr int U = C >= QL_RING4 ? 1 : QL_RING4 / C;   // without XL a slot also holds token fragments
         v4i wv[U][C], xv[XL ? 1 : U][2][MH];
         // 17 tokens and more (8 wavefronts; the accumulator dump runs the same loop): branch-free refills through range-checked buffer loads, as
         // in the int8 loop above (absent rows and channel groups: lane offset behind the buffer; groups past this
@@ -365,21 +372,72 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         };
         const int th0 = 8 * g0, th1 = g0 < g1 ? 8 * g1 : 8 * g0;
         if (FQ) load_tokens(th0, th1);
+        // The group scales of this wavefront's groups g0..g1-1 for the C channel groups ((g1-g0)*32 contiguous bytes
+        // each in the blob's decode-ordered copy [channel group][K/128][16]) and, with XL, the quantized tokens of its
+        // k-range are requested BEFORE the first weight fragments and parked in registers: loads return in order, so
+        // they arrive first and are copied to LDS while the weights are still on their way.  (Requested after the
+        // weights, each staging step was one more full trip to memory in front of the first multiply.)
+        constexpr int SREG = 2, TREG = 3;              // 16-byte pieces per lane parked in registers
+        const int n16 = (g1 - g0) * 2;                 // 16-byte scale pieces per channel group
+        const int spieces = g0 < g1 ? C * n16 : 0;
+        const int tpieces = (XL && !FQ && g0 < g1) ? (th1 - th0) * xrows : 0;
+        const bool s_regs = spieces <= 64 * SREG, t_regs = tpieces <= 64 * TREG;
+        v4i sreg[SREG], treg[TREG];
+        if (s_regs) {
+#pragma unroll
+            for (int q = 0; q < SREG; ++q) {
+                const int i = lane + 64 * q;
+                sreg[q] = v4i{0, 0, 0, 0};
+                if (i < spieces && rg0 + i / n16 < ngroups)
+                    sreg[q] = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(p.wscales) +
+                                                             ((size_t)(rg0 + i / n16) * G + g0) * 32 + (size_t)(i % n16) * 16);
+            }
+        }
+        if (XL && !FQ && t_regs) {
+#pragma unroll
+            for (int q = 0; q < TREG; ++q) {
+                const int i = lane + 64 * q;
+                treg[q] = v4i{0, 0, 0, 0};
+                if (i < tpieces && i % xrows < p.M) {
+                    const int th = th0 + i / xrows, row = i % xrows;
+                    treg[q] = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(p.xq) + (size_t)(th / 2) * 1024 +
+                                                             (row + 32 * (th % 2)) * 16);
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);             // keep these requests in front of the weights'
 #pragma unroll
         for (int u = 0; u < U; ++u) fetch(u, g0 + u);
         if (g0 < g1) {
-            // scales of this wavefront's groups g0..g1-1 for the C channel groups: (g1-g0)*32 contiguous
-            // bytes each in the blob's decode-ordered copy [channel group][K/128][16]
-            const int n16 = (g1 - g0) * 2;             // 16-byte pieces per channel group
-            for (int i = lane; i < C * n16; i += 64) {
-                const int j = i / n16, o = i % n16;
-                v4i v = v4i{0, 0, 0, 0};
-                if (rg0 + j < ngroups)
-                    v = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(p.wscales) +
-                                                       ((size_t)(rg0 + j) * G + g0) * 32 + (size_t)o * 16);
-                *reinterpret_cast<v4i *>(ss + ((size_t)j * G + g0) * 32 + (size_t)o * 16) = v;
+            if (s_regs) {
+#pragma unroll
+                for (int q = 0; q < SREG; ++q) {
+                    const int i = lane + 64 * q;
+                    if (i < spieces)
+                        *reinterpret_cast<v4i *>(ss + ((size_t)(i / n16) * G + g0) * 32 + (size_t)(i % n16) * 16) = sreg[q];
+                }
+            } else {
+                for (int i = lane; i < spieces; i += 64) {
+                    const int j = i / n16, o = i % n16;
+                    v4i v = v4i{0, 0, 0, 0};
+                    if (rg0 + j < ngroups)
+                        v = *reinterpret_cast<const v4i *>(reinterpret_cast<const char *>(p.wscales) +
+                                                           ((size_t)(rg0 + j) * G + g0) * 32 + (size_t)o * 16);
+                    *reinterpret_cast<v4i *>(ss + ((size_t)j * G + g0) * 32 + (size_t)o * 16) = v;
+                }
             }
-            if (XL && !FQ) stage_tokens(8 * g0, 8 * g1);
+            if (XL && !FQ) {
+                if (t_regs) {
+#pragma unroll
+                    for (int q = 0; q < TREG; ++q) {
+                        const int i = lane + 64 * q;
+                        if (i < tpieces)
+                            *reinterpret_cast<v4i *>(xs + ((size_t)(th0 + i / xrows) * xrows + i % xrows) * 16) = treg[q];
+                    }
+                } else {
+                    stage_tokens(8 * g0, 8 * g1);
+                }
+            }
             asm volatile("" ::: "memory");
             __builtin_amdgcn_wave_barrier();
         }
@@ -614,7 +672,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     auto_shape(a.M, a.N, a.K, W4, variant == 122 ? 32 : variant == 123 ? 64 : 0, block, c);
     if (variant == 101 || variant == 111) c = 1;
     if (variant == 102 && (!W4 || (size_t)2 * (a.K / 128) * 32 <= 16384)) c = 2;
-    if (variant == 103 && a.M > 16 && (!W4 || (size_t)3 * (a.K / 128) * 32 <= 16384)) c = 3;
+    if (variant == 103 && (!W4 || (size_t)3 * (a.K / 128) * 32 <= 16384)) c = 3;
     if (variant == 104 && (!W4 || (size_t)4 * (a.K / 128) * 32 <= 16384)) c = 4;
     if ((variant == 106 || variant == 108) && !W4 && a.M > 32 && block == 64) c = variant - 100;
     // 16 wavefronts (K split 16 ways) when there is at most one workgroup per CU: twice the bytes in flight
@@ -633,6 +691,7 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         if constexpr (EPI == EPI_F16) {
             if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, 2>(a, st);
             if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, 2>(a, st);
+            if (c == 3) return launch_one<W4, 1, 3, EPI, 8, true, 2>(a, st);
             return launch_one<W4, 1, 4, EPI, 8, true, 2>(a, st);
         }
     }
@@ -641,12 +700,14 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         if (wide) return launch_one<W4, 1, 1, EPI, 16, true>(a, st);
         if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true>(a, st);
         if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true>(a, st);
+        if (c == 3) return launch_one<W4, 1, 3, EPI, 8, true>(a, st);
         return launch_one<W4, 1, 4, EPI, 8, true>(a, st);
     }
     if (a.M <= 16) {
         if (wide) return launch_one<W4, 1, 1, EPI, 16>(a, st);
         if (c == 1) return launch_one<W4, 1, 1, EPI, 8>(a, st);
         if (c == 2) return launch_one<W4, 1, 2, EPI, 8>(a, st);
+        if (c == 3) return launch_one<W4, 1, 3, EPI, 8>(a, st);
         return launch_one<W4, 1, 4, EPI, 8>(a, st);
     }
     if (a.M > 32 && block == 64) {

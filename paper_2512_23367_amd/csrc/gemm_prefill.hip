@@ -111,11 +111,17 @@ inline int strip_height(int tiles_m, int tiles_n, int TM, int TN, int occupancy)
 // WK = 2: the k-blocks of every stage are split between two sets of WAVES_M x WAVES_N wavefronts (the two
 // ping-pong groups) that work on the same output tile and add their accumulators through LDS at the end;
 // gives 64x64 accumulators per wavefront on a 128x128 tile, for shapes with too few tiles for larger ones.
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC, bool PP, int WK>
+// MI16: the matrix instruction is 16x16x64 instead of 32x32x32 (int8 ping-pong kernels).  Same operand tiles in
+// memory and LDS, same number of LDS reads and accumulator registers, twice as many (half as long) matrix
+// instructions; measured on MI355X, the 16x16x64 form sustains ~20 % more operations per second on random operands
+// before the power limit lowers the shader clock.  A 32x32 block of the output is then four 16x16 quads
+// (channel half, token half) instead of four 8-channel strips.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC, bool PP, int WK, bool MI16>
 __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_kernel(PrefillParams p)
 {
     constexpr int NW = WAVES_M * WAVES_N * WK;
     static_assert(WK == 1 || (WK == 2 && PP && !W4 && WM % 2 == 0), "k-split: int8 ping-pong kernels only");
+    static_assert(!MI16 || (!W4 && PP && EPI != EPI_PART), "16x16x64: int8 ping-pong kernels, fused epilogues");
     constexpr int TMB = WAVES_M * WM;                    // activation row-blocks per workgroup tile
     constexpr int TNB = WAVES_N * WN;                    // weight row-blocks per workgroup tile
     constexpr int XFR = TMB * KBS;                       // 1024-byte fragments per stage: activations
@@ -210,13 +216,34 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
         else wait_vmcnt<(STAGES - 2) * LPW_LO>();
     };
 
-    v16i acc[WN][WM];
+    // accumulators of the 32x32 output block (i, j): element 4*q + e of a lane is channel ch_of(q) + e, token
+    // tok_of(q) of the block (see the epilogue); one 16-register value for the 32x32x32 instruction, four
+    // 4-register quads for the 16x16x64 one
+    v16i acc[MI16 ? 1 : WN][MI16 ? 1 : WM];
+    v4i acc4[MI16 ? WN : 1][MI16 ? WM : 1][4];
 #pragma unroll
-    for (int i = 0; i < WN; ++i)
+    for (int i = 0; i < (MI16 ? 1 : WN); ++i)
 #pragma unroll
-        for (int j = 0; j < WM; ++j)
+        for (int j = 0; j < (MI16 ? 1 : WM); ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+#pragma unroll
+    for (int i = 0; i < (MI16 ? WN : 1); ++i)
+#pragma unroll
+        for (int j = 0; j < (MI16 ? WM : 1); ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc4[i][j][q] = v4i{0, 0, 0, 0};
+    auto acc_get = [&](int i, int j, int q, int e) -> int {
+        if constexpr (MI16) return acc4[i][j][q][e];
+        else return acc[i][j][4 * q + e];
+    };
+    auto acc_add = [&](int i, int j, int q, int e, int v) {
+        if constexpr (MI16) acc4[i][j][q][e] += v;
+        else acc[i][j][4 * q + e] += v;
+    };
+    // position of accumulator quad q inside its 32x32 block: first of its 4 consecutive channels, and its token
+    auto ch_of = [&](int q) { return MI16 ? 16 * (q >> 1) + 4 * (lane >> 4) : 8 * q + 4 * (lane >> 5); };
+    auto tok_of = [&](int q) { return MI16 ? 16 * (q & 1) + (lane & 15) : (lane & 31); };
 
     // W4A8 only: fp32 accumulators over groups (EPI_F16) or integer totals (EPI_ACC)
     float accf[W4 ? WN : 1][W4 ? WM : 1][16];
@@ -252,6 +279,9 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
         const bool late = wave >= NW / 2;
         const int kb0 = (WK == 2) ? 2 * wk : 0;   // first of this wavefront's two k-blocks in a stage
         v4i wf[2][WN], xf[2][WM];
+        // 16x16x64: a fragment is 16 rows x 64 k -- lane (row r = lane % 16, 16-k chunk c = lane / 16) takes the 16
+        // bytes of row 16h + r, k-half c % 2 of the stage's 32-k tile c / 2 (four runs of 256 contiguous bytes)
+        const int frag16 = (lane >> 5) * 1024 + ((lane & 15) + 32 * ((lane >> 4) & 1)) * 16;
         wait_stage();        // stage 0 has landed (this wavefront's part)
         __builtin_amdgcn_s_barrier();            // ... everyone's
         if (late) __builtin_amdgcn_s_barrier();  // phase shift
@@ -259,13 +289,15 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
             // ---- memory phase
             const char *buf = smem + (it % STAGES) * STAGE_BYTES;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
+            for (int kb = 0; kb < 2; ++kb) {     // 32x32x32: k-block of the stage; 16x16x64: row half of the block
 #pragma unroll
                 for (int i = 0; i < WN; ++i)
-                    wf[kb][i] = *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb0 + kb) * 1024 + lane * 16);
+                    wf[kb][i] = MI16 ? *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb0) * 1024 + frag16 + kb * 256)
+                                     : *reinterpret_cast<const v4i *>(buf + WOFF + ((wn * WN + i) * KBS + kb0 + kb) * 1024 + lane * 16);
 #pragma unroll
                 for (int j = 0; j < WM; ++j)
-                    xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb0 + kb) * 1024 + lane * 16);
+                    xf[kb][j] = MI16 ? *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb0) * 1024 + frag16 + kb * 256)
+                                     : *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb0 + kb) * 1024 + lane * 16);
             }
             issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
             wait_stage();    // own loads of stage it+1 have landed
@@ -273,13 +305,23 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
             __builtin_amdgcn_s_barrier();
             // ---- compute phase
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            if constexpr (MI16) {
 #pragma unroll
                 for (int i = 0; i < WN; ++i)
 #pragma unroll
                     for (int j = 0; j < WM; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kb][i], xf[kb][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            acc4[i][j][q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wf[q >> 1][i], xf[q & 1][j], acc4[i][j][q], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < WN; ++i)
+#pragma unroll
+                        for (int j = 0; j < WM; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[kb][i], xf[kb][j], acc[i][j], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();
         }
@@ -450,8 +492,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         *reinterpret_cast<v4i *>(mine + ((i * HB + jj) * 4 + q) * 1024 + lane * 16) =
-                            v4i{acc[i][j0 + jj][4 * q], acc[i][j0 + jj][4 * q + 1], acc[i][j0 + jj][4 * q + 2],
-                                acc[i][j0 + jj][4 * q + 3]};
+                            v4i{acc_get(i, j0 + jj, q, 0), acc_get(i, j0 + jj, q, 1), acc_get(i, j0 + jj, q, 2),
+                                acc_get(i, j0 + jj, q, 3)};
         };
         auto take = [&](auto half) {
             constexpr int j0 = decltype(half)::value * HB;
@@ -463,7 +505,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                     for (int q = 0; q < 4; ++q) {
                         const v4i v = *reinterpret_cast<const v4i *>(theirs + ((i * HB + jj) * 4 + q) * 1024 + lane * 16);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j0 + jj][4 * q + e] += v[e];
+                        for (int e = 0; e < 4; ++e) acc_add(i, j0 + jj, q, e, v[e]);
                     }
         };
         if (wk == 0) give(std::integral_constant<int, 1>{}); else give(std::integral_constant<int, 0>{});
@@ -492,17 +534,23 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                 }
         return;
     }
-    if (EPI == EPI_ACC) {   // test hook: raw integer accumulators, element by element
+    if constexpr (EPI == EPI_ACC) {   // test hook: raw integer accumulators, element by element
 #pragma unroll
         for (int j = 0; j < WM; ++j) {
-            const int m = m_lane0 + j * 32;
-            if (m >= p.M || !my_block(j)) continue;
+            if (!my_block(j)) continue;
 #pragma unroll
             for (int i = 0; i < WN; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int n = n_lane0 + i * 32 + 8 * (r / 4) + (r % 4);
-                    if (n < p.N) p.acc[(size_t)m * p.N + n] = W4 ? (tot[i][j][r] >> 4) : acc[i][j][r];
+                for (int q = 0; q < 4; ++q) {
+                    const int m = (tm * TMB + wm * WM + j) * 32 + tok_of(q);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int n = (tn * TNB + wn * WN + i) * 32 + ch_of(q) + e;
+                        if (m < p.M && n < p.N) {
+                            if constexpr (W4) p.acc[(size_t)m * p.N + n] = tot[i][j][4 * q + e] >> 4;
+                            else p.acc[(size_t)m * p.N + n] = acc_get(i, j, q, e);
+                        }
+                    }
                 }
         }
         return;
@@ -524,12 +572,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
 #pragma unroll
     for (int j = 0; j < WM; ++j) {
         if (!my_block(j)) continue;                        // wave-uniform
-        const float sxm = side_sx[(wm * WM + j) * 32 + (lane & 31)] * (W4 ? 0.0625f : 1.0f);
 #pragma unroll
         for (int i = 0; i < WN; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int nl = (wn * WN + i) * 32 + 8 * q + 4 * (lane >> 5);   // channel inside the tile
+                const float sxm = side_sx[(wm * WM + j) * 32 + tok_of(q)] * (W4 ? 0.0625f : 1.0f);
+                const int nl = (wn * WN + i) * 32 + ch_of(q);   // channel inside the tile
                 const float4 swq = *reinterpret_cast<const float4 *>(side_sw + nl);
                 const float4 bq = *reinterpret_cast<const float4 *>(side_b + nl);
                 const float sw4[4] = {swq.x, swq.y, swq.z, swq.w}, b4[4] = {bq.x, bq.y, bq.z, bq.w};
@@ -537,11 +585,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float v;
-                    if (W4) v = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b4[e]);
-                    else v = __builtin_fmaf((float)acc[i][j][4 * q + e] * sxm, sw4[e], b4[e]);
+                    if constexpr (W4) v = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b4[e]);
+                    else v = __builtin_fmaf((float)acc_get(i, j, q, e) * sxm, sw4[e], b4[e]);
                     o[e] = (_Float16)v;
                 }
-                *reinterpret_cast<h4 *>(stg + (lane & 31) * ROW_BYTES + (i * 32 + 8 * q + 4 * (lane >> 5)) * 2) = o;
+                *reinterpret_cast<h4 *>(stg + tok_of(q) * ROW_BYTES + (i * 32 + ch_of(q)) * 2) = o;
             }
         // same wavefront, LDS operations complete in order: only the compiler has to be kept from
         // moving the differently-typed reads above the writes (and the next block's writes above them)
@@ -654,7 +702,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KBS, int STAGES, bool W4, int EPI, int OCC = 1, bool PP = false,
-          int WK = 1>
+          int WK = 1, bool MI16 = false>
 int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
 {
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
@@ -664,7 +712,7 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
                         (W4 ? STAGES * WAVES_M * WAVES_N * WK * 256 : 0);  // + int4 group-scale slots
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N * WK) + 1) <= 63, "vmcnt range");
-    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP, WK>;
+    auto kern = gemm_prefill_kernel<WAVES_M, WAVES_N, WM, WN, KBS, STAGES, W4, EPI, OCC, PP, WK, MI16>;
     // once per kernel and process; the initialisation of a function-local static is thread-safe
     static const hipError_t attr_status = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -782,12 +830,15 @@ inline Choice choose_w4(const GemmArgs &a, size_t scratch, bool dump_partials)
 inline Choice choose_w8(const GemmArgs &a, size_t scratch, bool dump_partials)
 {
     struct Candidate { int variant, tm, tn; double o, r; };
+    // (the ping-pong configurations run on the 16x16x64 matrix instruction here: 3-8 % faster than on 32x32x32 on the
+    // 4096-token shapes, where the power limit sets the clock; the rates of the two largest tiles are refitted to the
+    // 4096- and 16384-token shapes measured with it)
     static const Candidate many[] = {
-        {23, 256, 384, 3.49, 13.41},   // 256x384 ping-pong, wavefronts of 128x96: fewest LDS bytes per matrix instruction
-        {6, 256, 256, 3.40, 13.85},    // 256x256 ping-pong
-        {15, 256, 192, 3.23, 12.65},   // 256x192 ping-pong
-        {17, 128, 256, 0.67, 11.34},   // 128x256 ping-pong, two workgroups per CU
-        {19, 128, 128, 1.83, 11.46},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
+        {43, 256, 384, 3.49, 13.6},    // 256x384 ping-pong, wavefronts of 128x96: fewest LDS bytes per matrix instruction
+        {26, 256, 256, 3.40, 12.9},    // 256x256 ping-pong
+        {35, 256, 192, 3.23, 13.1},    // 256x192 ping-pong
+        {37, 128, 256, 0.67, 11.8},    // 128x256 ping-pong, two workgroups per CU
+        {39, 128, 128, 1.83, 11.46},   // 128x128 k-split ping-pong (at most one pass, K % 128 == 0)
         {13, 128, 128, 1.07, 10.32},   // 128x128, 8 wavefronts (at most one pass)
         {4, 128, 128, 0.88, 9.47},     // 128x128, 4 wavefronts, two per CU (more than one pass)
         {11, 128, 128, 0.42, 9.81},    // 128x128, 4 wavefronts, three per CU (more than two passes)
@@ -802,7 +853,7 @@ inline Choice choose_w8(const GemmArgs &a, size_t scratch, bool dump_partials)
     Choice best = {0, 1, 1e30};
     for (int i = 0; i < 8; ++i) {
         const Candidate &c = cands[i];
-        if (c.variant == 19 && (a.K % 128 != 0 || t128 > 256)) continue;
+        if ((c.variant == 19 || c.variant == 39) && (a.K % 128 != 0 || t128 > 256)) continue;
         if (c.variant == 13 && t128 > 256) continue;
         if (c.variant == 4 && t128 <= 256) continue;
         if (c.variant == 11 && t128 <= 512) continue;
@@ -870,7 +921,14 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI_PART, 1, true>(a, st, splits);
     }
     if (variant == 19 && a.K % 128) variant = 13;   // 128-k stages need K % 128 == 0
+    if (variant == 39 && a.K % 128) variant = 13;
     switch (variant) {
+    // 26, 43, 35, 37, 39: the configurations 6, 23, 15, 17, 19 on the 16x16x64 matrix instruction
+    case 26: return launch_one<2, 4, 4, 2, 2, 4, false, EPI, 1, true, 1, true>(a, st);
+    case 43: return launch_one<2, 4, 4, 3, 2, 3, false, EPI, 1, true, 1, true>(a, st);
+    case 35: return launch_one<4, 2, 2, 3, 2, 4, false, EPI, 1, true, 1, true>(a, st);
+    case 37: return launch_one<2, 4, 2, 2, 2, 3, false, EPI, 2, true, 1, true>(a, st);
+    case 39: return launch_one<2, 2, 2, 2, 4, 4, false, EPI, 1, true, 2, true>(a, st);
     case 6:   // 256x256, 8 wavefronts of 128 tokens x 64 channels in two ping-pong groups (one computes while the other fetches), 64-k stages
         return launch_one<2, 4, 4, 2, 2, 4, false, EPI, 1, true>(a, st);
     case 23:  // 256 tokens x 384 channels, 8 wavefronts of 128x96 in two ping-pong groups, 3 stages
@@ -915,14 +973,14 @@ void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_c
         return;
     }
     Choice c = choose_w8(a, scratch, a.partials != nullptr);
-    if (c.variant == 19 && a.K % 128) c.variant = 13;
+    if ((c.variant == 19 || c.variant == 39) && a.K % 128) c.variant = 13;
     *splits = c.splits;
     *variant = c.variant == 200 || c.variant == 300 ? c.variant + c.splits : c.variant;
     switch (c.variant) {
-    case 23: *tile_tokens = 256, *tile_channels = 384; break;
-    case 6: case 300: *tile_tokens = 256, *tile_channels = 256; break;
-    case 15: *tile_tokens = 256, *tile_channels = 192; break;
-    case 17: *tile_tokens = 128, *tile_channels = 256; break;
+    case 23: case 43: *tile_tokens = 256, *tile_channels = 384; break;
+    case 6: case 26: case 300: *tile_tokens = 256, *tile_channels = 256; break;
+    case 15: case 35: *tile_tokens = 256, *tile_channels = 192; break;
+    case 17: case 37: *tile_tokens = 128, *tile_channels = 256; break;
     case 20: *tile_tokens = 64, *tile_channels = 64; break;
     default: *tile_tokens = 128, *tile_channels = 128; break;
     }

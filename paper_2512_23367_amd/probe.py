@@ -33,7 +33,7 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def mfma_int8(workgroups: int, iters: int, random_operands: bool, sink) -> int:
+def mfma_int8(workgroups: int, iters: int, random_operands: int, sink) -> int:
     """Enqueues the matrix-pipe probe on torch's current stream; returns the number of int8 operations."""
     ops = ctypes.c_int64()
     rc = lib().qlprobe_mfma_int8(workgroups, iters, int(random_operands), ctypes.c_void_p(sink.data_ptr()),

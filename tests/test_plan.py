@@ -39,8 +39,8 @@ def test_few_tokens_on_7b_shapes_follow_the_measured_table():
 
 
 def test_config1_prefill_shapes_take_the_profiled_tile_kernels():
-    for N, K, variant, tile in [(4608, 1536, 15, (256, 192)), (1536, 1536, 13, (128, 128)), (12288, 1536, 23, (256, 384)),
-                                (1536, 6144, 19, (128, 128))]:
+    for N, K, variant, tile in [(4608, 1536, 35, (256, 192)), (1536, 1536, 13, (128, 128)), (12288, 1536, 43, (256, 384)),
+                                (1536, 6144, 39, (128, 128))]:
         p = plan(2048, N, K)
         assert (p.family, p.variant, (p.tile_tokens, p.tile_channels), p.splits) == (ql.QL_FAMILY_TILE, variant, tile, 1)
 
