@@ -6,8 +6,9 @@ per-channel / group-wise granularities of its Preliminary section, the
 symmetric setting of its Experimental Setup, and Y = XW of its Eq. 3), plus the
 two operand transforms of its W4A8 variants (SmoothQuant, Eq. 3; Hadamard rotation, Eq. 4)
 and the other quantizer forms of its Preliminary section (Eq. 2 as printed, per-tensor
-granularity, a calibrated static activation scale), and an RMSNorm in front of the activation quantizer
-(textbook definition; the paper does not spell out the normalisation of its decoder layers).
+granularity, a calibrated static activation scale), and an RMSNorm and a SwiGLU in front of the activation
+quantizer (textbook definitions; the paper does not spell out the normalisation or the gated MLP of its decoder
+layers).
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may use this
 package.  It shares no code with the HIP path and imports nothing from it.
@@ -43,4 +44,6 @@ from .transforms import (  # noqa: F401
     hadamard_block,
     fwht_blocks,
     rmsnorm_act,
+    swiglu_act,
+    exp_f32_steps,
 )

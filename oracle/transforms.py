@@ -120,3 +120,48 @@ def rmsnorm_act(x16: np.ndarray, gamma16: np.ndarray, eps: float) -> np.ndarray:
     x = x16.astype(F32)
     h = ((x * r[:, None]).astype(F32) * gamma16.astype(F32)[None, :]).astype(F32)
     return h
+
+
+# ---- SwiGLU in front of the activation quantizer --------------------------------------------------------------
+# The gated MLP of a decoder layer multiplies the two halves of the fused gate+up projection before the down
+# projection:  h_j = silu(gate_j) * up_j,  silu(g) = g * sigmoid(g) = g / (1 + exp(-g))   (textbook definition,
+# Shazeer 2020; the paper names no activation function).  Reading: fp32 throughout, no rounding of h back to fp16,
+# every step ONE correctly rounded fp32 operation so that a fused kernel can be bit-identical -- which needs exp
+# itself to be a stated sequence of such operations (library exponentials differ in their last bit):
+#     t = clamp(-g, -80, 80)
+#     n = rint(t * log2(e))                                  (round half to even)
+#     r = (t - n * LN2_HI) - n * LN2_LO                      (two-constant range reduction: |r| <= 0.347)
+#     p = 1 + r (1 + r (1/2 + r (1/6 + r (1/24 + r (1/120 + r (1/720 + r / 5040))))))    (Horner, mul then add)
+#     exp(t) ~ p * 2^n                                       (exact scaling)
+#     h = (g * (1 / (1 + exp(t)))) * u                       (add, divide, two multiplies)
+LOG2E = F32(1.4426950408889634)
+LN2_HI = F32(0.693359375)                  # 355/512: n * LN2_HI is exact for |n| < 2^15
+LN2_LO = F32(-2.12194440e-4)               # ln 2 - LN2_HI
+EXP_COEFFS = [F32(1.0 / 5040), F32(1.0 / 720), F32(1.0 / 120), F32(1.0 / 24), F32(1.0 / 6), F32(0.5), F32(1.0), F32(1.0)]
+
+
+def exp_f32_steps(t: np.ndarray) -> np.ndarray:
+    """exp(t) for fp32 t in [-80, 80] by the sequence above (each line one fp32 operation per element)."""
+    t = t.astype(F32)
+    n = np.rint((t * LOG2E).astype(F32)).astype(F32)
+    r = (t - (n * LN2_HI).astype(F32)).astype(F32)
+    r = (r - (n * LN2_LO).astype(F32)).astype(F32)
+    p = np.full_like(r, EXP_COEFFS[0])
+    for c in EXP_COEFFS[1:]:
+        p = ((p * r).astype(F32) + c).astype(F32)
+    return np.ldexp(p, n.astype(np.int32)).astype(F32)      # times 2^n: exact (results stay normal)
+
+
+def swiglu_act(gate_up16: np.ndarray) -> np.ndarray:
+    """h[M,F] = silu(gate) * up for the fused projection output gate_up[M, 2F] (fp16: gate = columns 0..F-1,
+    up = columns F..2F-1), as an fp32 array that goes to the per-token quantizer unrounded."""
+    if gate_up16.dtype != np.float16 or gate_up16.ndim != 2 or gate_up16.shape[1] % 2:
+        raise TypeError("gate_up is fp16 [M, 2F]")
+    F = gate_up16.shape[1] // 2
+    g = gate_up16[:, :F].astype(F32)
+    u = gate_up16[:, F:].astype(F32)
+    t = np.minimum(np.maximum(-g, F32(-80)), F32(80)).astype(F32)
+    e = exp_f32_steps(t)
+    d = (F32(1) + e).astype(F32)
+    sg = (F32(1) / d).astype(F32)
+    return ((g * sg).astype(F32) * u).astype(F32)
