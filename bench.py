@@ -552,7 +552,7 @@ def layer_table(torch, ql, synth):
 
 def act_quant_rows(torch, ql):
     """The activation quantizer alone and with the operand transforms fused in front of it (SmoothQuant per-channel
-    multiply, block Hadamard rotation, RMSNorm), graph-replayed; 3 B per element."""
+    multiply, block Hadamard rotation, RMSNorm, SwiGLU), graph-replayed; 3 B per element (SwiGLU: 5)."""
     rows = []
     for M, K in ((2048, 1536), (4096, 4096), (4096, 11008)):
         x = torch.randn((M, K), dtype=torch.float16, device="cuda:0")
@@ -569,6 +569,11 @@ def act_quant_rows(torch, ql):
             t = median_ms(torch, fn, MIN_LAUNCHES, 3, graph=True)
             row[name + "_us"] = round(t * 1e3, 2)
             row[name + "_gbs"] = round(3 * M * K / (t * 1e-3) / 1e9, 1)
+        # SwiGLU of a fused gate+up output [M, 2K] in front of the quantizer: 4 B read + 1 B written per element
+        gu = torch.randn((M, 2 * K), dtype=torch.float16, device="cuda:0")
+        t = median_ms(torch, lambda i: ql.ql_quant_act_swiglu(gu, None, kl, sxv), MIN_LAUNCHES, 3, graph=True)
+        row["swiglu_us"], row["swiglu_gbs"] = round(t * 1e3, 2), round(5 * M * K / (t * 1e-3) / 1e9, 1)
+        del gu
         log("[detail]", json.dumps(row))
         rows.append(row)
         del x, kl

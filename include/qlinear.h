@@ -110,6 +110,20 @@ int ql_quant_act_per_token(const void *x, int64_t ldx, int M, int K,
 int ql_quant_act_rmsnorm(const void *x, int64_t ldx, int M, int K, const void *gamma, float eps, int8_t *xq_rowmajor,
                          int8_t *xq_kernel, float *sx, void *stream);
 
+/* SwiGLU fused in front of the per-token quantizer (the gated MLP of a decoder layer between its fused gate+up
+ * projection and its down projection; textbook definition, the paper names no activation function):
+ *     h[m,j] = silu(gate[m,j]) * up[m,j],  silu(g) = g / (1 + exp(-g)),   then Eq. 1-2 on h as in
+ *     ql_quant_act_per_token (h stays fp32, it is never rounded to fp16).
+ * Arithmetic: every step one correctly rounded fp32 operation, the exponential included: t = clamp(-g, +-80),
+ * n = rint(t * log2 e), r = (t - n * 0.693359375) - n * (-2.12194440e-4), p = Horner polynomial of degree 7 in r with
+ * the Taylor coefficients (multiply, then add), exp(t) = p * 2^n, h = (g * (1 / (1 + exp(t)))) * u.  The codes and
+ * scales are therefore a function of the inputs alone.
+ *   gate_up  device, fp16 [M, ld]: columns 0..F-1 the gate half, F..2F-1 the up half (the output of the fused
+ *            projection), 16-byte aligned, ld >= 2F, ld % 8 == 0;  F % 64 == 0 (it is the K of the down projection)
+ *   outputs as ql_quant_act_per_token with K = F.  Errors: as there. */
+int ql_quant_act_swiglu(const void *gate_up, int64_t ld, int M, int F, int8_t *xq_rowmajor, int8_t *xq_kernel,
+                        float *sx, void *stream);
+
 /* Row-major int8 [M,K] -> kernel layout (lets a caller supply its own quantized activations). */
 int ql_act_repack(const int8_t *xq_rowmajor, int M, int K, int8_t *xq_kernel, void *stream);
 

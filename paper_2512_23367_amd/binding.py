@@ -20,7 +20,7 @@ STATUS_NAMES = {0: "QL_OK", 1: "QL_ERR_NULL", 2: "QL_ERR_SHAPE", 3: "QL_ERR_ALIG
 
 EXPORTS = [
     "ql_version", "ql_last_error", "ql_weight_bytes", "ql_act_kernel_bytes", "ql_workspace_bytes",
-    "ql_quant_act_per_token", "ql_quant_act_rmsnorm", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
+    "ql_quant_act_per_token", "ql_quant_act_rmsnorm", "ql_quant_act_swiglu", "ql_act_repack", "ql_quant_weight", "ql_export_canonical",
     "ql_w8a8_linear", "ql_w8a8_linear_static", "ql_w4a8_linear", "ql_w8a8_gemm", "ql_w4a8_gemm",
     "ql_w8a8_gemm_acc_i32", "ql_w4a8_gemm_acc_i32", "ql_set_kernel_variant", "ql_plan_gemm",
     "ql_hadamard_block", "ql_smooth_calibrate", "ql_smooth_scales",
@@ -74,6 +74,7 @@ def lib() -> ctypes.CDLL:
             "ql_workspace_bytes": [i, i, i, i, szp],
             "ql_quant_act_per_token": [vp, i64, i, i, vp, vp, vp, vp],
             "ql_quant_act_rmsnorm": [vp, i64, i, i, vp, c.c_float, vp, vp, vp, vp],
+            "ql_quant_act_swiglu": [vp, i64, i, i, vp, vp, vp, vp],
             "ql_act_repack": [vp, i, i, vp, vp],
             "ql_quant_weight": [vp, i, i, i, i, vp, vp, vp, vp],
             "ql_export_canonical": [vp, i, i, i, i, vp, vp, vp],
@@ -232,6 +233,16 @@ def ql_quant_act_rmsnorm(x, gamma, eps, xq_rowmajor=None, xq_kernel=None, sx=Non
     M, K = x.shape
     _check(lib().ql_quant_act_rmsnorm(_p(x), _ld(x) if M else K, M, K, _p(gamma), float(eps), _p(xq_rowmajor),
                                       _p(xq_kernel), _p(sx), _stream()))
+
+
+def ql_quant_act_swiglu(gate_up, xq_rowmajor=None, xq_kernel=None, sx=None):
+    """gate_up: fp16 [M, 2F] (gate half, then up half); quantizes silu(gate) * up per token (K = F)."""
+    _want(gate_up, torch.float16, "gate_up")
+    M, F2 = gate_up.shape
+    if F2 % 2:
+        raise ValueError("gate_up has an even number of columns")
+    _check(lib().ql_quant_act_swiglu(_p(gate_up), _ld(gate_up) if M else F2, M, F2 // 2, _p(xq_rowmajor), _p(xq_kernel),
+                                     _p(sx), _stream()))
 
 
 def ql_act_repack(xq_rowmajor, xq_kernel):

@@ -37,6 +37,9 @@ constexpr int MAX_WAVES = 8;
 //        across the lanes, the wavefronts in order) and rounded to fp32 once -- the fp64 sum is within ~1e-13 of the
 //        exact one, so this is the correctly rounded exact sum except within that distance of a rounding boundary;
 //   mean = ss / K,  r = 1 / sqrt(mean + eps),  h = (x * r) * gamma: one correctly rounded fp32 operation each.
+// MODE 3: SwiGLU in front of the quantizer: x is the fused gate+up projection output [M, 2K] (gate = columns 0..K-1,
+// up = columns K..2K-1), the quantized value is h_k = silu(gate_k) * up_k in fp32 (swiglu_f32: a fixed sequence of
+// single fp32 operations), recomputed when the codes are produced; the up half is re-read then (it sits in L2).
 template <int NIT, int RPB, int MODE>
 __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half *__restrict__ x, int64_t ldx,
                                                                     int M, int K, int per_wave,
@@ -56,7 +59,16 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
             f[2 * i + 1] = half_bits_to_float(w[i] >> 16);
         }
     };
+    const Half16 *row_up = nullptr;    // MODE 3: the up half of this lane's token
     auto smoothed = [&](const Half16 &h, int c, float (&f)[16]) {
+        if constexpr (MODE == 3) {
+            float u[16];
+            widen(h, f);
+            widen(row_up[c], u);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) f[i] = swiglu_f32(f[i], u[i]);
+            return;
+        }
         if constexpr (MODE == 2) {
             float g[16];
             widen(h, f);
@@ -91,11 +103,26 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     const bool valid = m < M;
     const int nchunks = K / CHUNK;
     const Half16 *row = reinterpret_cast<const Half16 *>(x + (size_t)(valid ? m : 0) * ldx);
+    if (MODE == 3) row_up = reinterpret_cast<const Half16 *>(x + (size_t)(valid ? m : 0) * ldx + K);
     const int s0 = wave * per_wave;
 
     Half16 v[NIT > 0 ? NIT : 1];
     unsigned mx = 0;
-    if constexpr (MODE == 2) {
+    // MODE 3 with the row in registers: the fp32 values themselves are kept (the transform costs ~45 vector
+    // operations per element, twice that if it were recomputed for the codes: the kernel is ALU-bound)
+    constexpr bool KEEP32 = MODE == 3 && NIT > 0;
+    float hv[KEEP32 ? NIT : 1][16];
+    if constexpr (KEEP32) {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = (s0 + i) * CPS + cl;
+            if (i < per_wave && c < nchunks && valid) {
+                smoothed(row[c], c, hv[i]);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mx = max(mx, __float_as_uint(fabsf(hv[i][e])));
+            }
+        }
+    } else if constexpr (MODE == 2) {
         // sum of squares first (the maximum needs the normalised values); the row goes to registers on the way
         __shared__ double red_ss[MAX_RPB][MAX_WAVES];
         double ss = 0.0;
@@ -179,7 +206,17 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
         if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK) = q;
         if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = q;
     };
-    if (NIT > 0) {
+    if constexpr (KEEP32) {
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = (s0 + i) * CPS + cl;
+            if (i < per_wave && c < nchunks && valid) {
+                const uint4 q = quant_chunk_f32(hv[i], inv);
+                if (xq_rm) *reinterpret_cast<uint4 *>(xq_rm + (size_t)m * K + (size_t)c * CHUNK) = q;
+                if (xq_kl) *reinterpret_cast<uint4 *>(xq_kl + tile_offset_i8(m, c * CHUNK, K)) = q;
+            }
+        }
+    } else if (NIT > 0) {
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = (s0 + i) * CPS + cl;
@@ -304,7 +341,7 @@ static void launch_aq(const __half *x, int64_t ldx, int M, int K, const float *i
     else if (per_wave <= 2) QL_LAUNCH_AQ(2);
     else if (per_wave <= 4) QL_LAUNCH_AQ(4);
     else if (per_wave <= 8) QL_LAUNCH_AQ(8);
-    else if (per_wave <= 12) QL_LAUNCH_AQ(12);
+    else if (per_wave <= 12 && MODE != 3) QL_LAUNCH_AQ(12);
     else QL_LAUNCH_AQ(0);
 #undef QL_LAUNCH_AQ
 }
@@ -360,6 +397,17 @@ int launch_act_quant_rmsnorm(const __half *x, int64_t ldx, int M, int K, const _
     if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 2>(x, ldx, M, K, nullptr, gamma, eps, xq_rm, xq_kl, sx, st);
     else launch_aq<8, 2>(x, ldx, M, K, nullptr, gamma, eps, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant (rmsnorm) launch");
+}
+
+int launch_act_quant_swiglu(const __half *gate_up, int64_t ld, int M, int K, int8_t *xq_rm, int8_t *xq_kl, float *sx,
+                            hipStream_t st)
+{
+    if (M == 0) return QL_OK;
+    // 8 tokens per workgroup keep up to 8192 features per token in registers, 4 tokens up to 16384
+    if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 3>(gate_up, ld, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
+    else if (K <= 8192) launch_aq<8, 3>(gate_up, ld, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
+    else launch_aq<4, 3>(gate_up, ld, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
+    return check_hip(hipGetLastError(), "act_quant (swiglu) launch");
 }
 
 int launch_act_repack(const int8_t *xq_rm, int M, int K, int8_t *xq_kl, hipStream_t st)

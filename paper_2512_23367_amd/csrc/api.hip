@@ -340,6 +340,21 @@ int ql_quant_act_rmsnorm(const void *x, int64_t ldx, int M, int K, const void *g
                                     xq_rowmajor, xq_kernel, sx, static_cast<hipStream_t>(stream));
 }
 
+int ql_quant_act_swiglu(const void *gate_up, int64_t ld, int M, int F, int8_t *xq_rowmajor, int8_t *xq_kernel, float *sx,
+                        void *stream)
+{
+    QL_TRY(check_mk(M, F));
+    if (M == 0) return QL_OK;
+    if (!gate_up || !sx || (!xq_rowmajor && !xq_kernel))
+        return fail(QL_ERR_NULL, "gate_up, sx and one of the outputs are required");
+    if (!aligned(gate_up, 16) || ld < 2 * (int64_t)F || ld % 8)
+        return fail(QL_ERR_ALIGN, "gate_up must be 16-byte aligned, ld >= 2F and a multiple of 8 (ld=%lld)", (long long)ld);
+    if ((xq_rowmajor && !aligned(xq_rowmajor, 16)) || (xq_kernel && !aligned(xq_kernel, 256)) || !aligned(sx, 4))
+        return fail(QL_ERR_ALIGN, "xq_rowmajor needs 16-byte, xq_kernel 256-byte alignment");
+    return launch_act_quant_swiglu(static_cast<const __half *>(gate_up), ld, M, F, xq_rowmajor, xq_kernel, sx,
+                                   static_cast<hipStream_t>(stream));
+}
+
 int ql_act_repack(const int8_t *xq_rowmajor, int M, int K, int8_t *xq_kernel, void *stream)
 {
     QL_TRY(check_mk(M, K));

@@ -81,6 +81,8 @@ int launch_act_quant_smooth(const __half *x, int64_t ldx, int M, int K, const fl
                             int8_t *xq_kl, float *sx, hipStream_t st);
 int launch_act_quant_rmsnorm(const __half *x, int64_t ldx, int M, int K, const __half *gamma, float eps, int8_t *xq_rm,
                              int8_t *xq_kl, float *sx, hipStream_t st);
+int launch_act_quant_swiglu(const __half *gate_up, int64_t ld, int M, int K, int8_t *xq_rm, int8_t *xq_kl, float *sx,
+                            hipStream_t st);
 int launch_act_repack(const int8_t *xq_rm, int M, int K, int8_t *xq_kl, hipStream_t st);
 int launch_weight_quant8(const __half *w, int N, int K, int8_t *canon, float *scales, int8_t *kl,
                          hipStream_t st);

@@ -84,6 +84,34 @@ __device__ inline void token_scales_f32(float amax, float &scale, float &inv)
     inv = zero ? 0.0f : 127.0f / amax;      // IEEE fp32 division
 }
 
+// SwiGLU of the gated MLP in front of the quantizer (textbook definition: h = silu(gate) * up, silu(g) = g / (1 +
+// exp(-g)); the paper names no activation function).  Every step is one correctly rounded fp32 operation, the
+// exponential included -- clamp, range reduction by n = rint(t log2 e) with a two-constant ln 2, degree-7 Horner
+// polynomial (multiply, then add), exact scaling by 2^n -- so that the codes are a function of the inputs alone.
+__device__ inline float exp_steps(float t)      // t in [-80, 80]
+{
+    const float n = rintf(t * 1.4426950408889634f);
+    float r = t - n * 0.693359375f;
+    r = r - n * -2.12194440e-4f;
+    float p = (float)(1.0 / 5040);
+    p = p * r + (float)(1.0 / 720);
+    p = p * r + (float)(1.0 / 120);
+    p = p * r + (float)(1.0 / 24);
+    p = p * r + (float)(1.0 / 6);
+    p = p * r + 0.5f;
+    p = p * r + 1.0f;
+    p = p * r + 1.0f;
+    return p * __int_as_float(((int)n + 127) << 23);   // times 2^n, exact: |n| <= 116
+}
+
+__device__ inline float swiglu_f32(float g, float u)
+{
+    const float t = fminf(fmaxf(-g, -80.0f), 80.0f);
+    const float d = 1.0f + exp_steps(t);
+    const float sg = 1.0f / d;                          // IEEE fp32 division
+    return (g * sg) * u;
+}
+
 // token scale and its reciprocal from the bit pattern of the largest |x|
 __device__ inline void token_scales(unsigned amax_bits, float &scale, float &inv)
 {
