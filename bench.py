@@ -504,48 +504,41 @@ def main():
 
 def layer_table(torch, ql, synth):
     """Context for the paper's Table 3 (INT8 against FP16 prefill latency and memory by batch size): the four
-    linears of the 7B-class layer (QKV -> O -> gate+up -> down) over a sweep of token counts, as FP16 GEMMs of
-    the vendor library (torch.matmul, a comparison system that is not part of this library) and as W8A8 / W4A8
-    linears (quantize + GEMM + epilogue through ql_*_linear); weight bytes per precision."""
+    chained linears of the 7B-class layer (qkv -> o -> gate_up -> SwiGLU -> down; paper_2512_23367_amd.layer) over a
+    sweep of token counts, as W8A8 and W4A8 (quantize + GEMM + epilogue, SwiGLU fused into the down projection's
+    quantizer) and as FP16 GEMMs of the vendor library (torch.matmul + torch's SiLU: a comparison system that is not
+    part of this library); weight bytes per precision."""
+    from paper_2512_23367_amd.layer import DecoderLayerLinears
+    import torch.nn.functional as tf
     rows = []
-    base = [s for s in synth.workload(2)]
-    weights = {}
-    for sh in base:
-        for b in (8, 4):
-            l = Layer(synth.Shape(sh.config, sh.layer, 32, sh.K, sh.N, b, 0 if b == 8 else 128, sh.bias), torch, ql, synth)
-            weights[(sh.layer, b)] = l
-        weights[(sh.layer, 16)] = torch.randn((sh.N, sh.K), dtype=torch.float16, device="cuda:0") * 0.02
-    mem = {"fp16": sum(s.N * s.K * 2 for s in base),
-           "w8a8": sum(weights[(s.layer, 8)].weight_bytes + s.N * 4 for s in base),
-           "w4a8": sum(weights[(s.layer, 4)].weight_bytes for s in base)}
+    d, F, max_m = 4096, 11008, 16384
+    shapes = {s.layer: s for s in synth.workload(2)}
+    wh = {k: torch.from_numpy(synth.weights(shapes[k].N, shapes[k].K, 2, k)).to("cuda:0") for k in ("qkv", "o", "gate_up", "down")}
+    layers = {b: DecoderLayerLinears(wh["qkv"], wh["o"], wh["gate_up"], wh["down"], b, max_m) for b in (8, 4)}
+    mem = {"fp16": sum(w.numel() * 2 for w in wh.values()), "w8a8": layers[8].weight_bytes, "w4a8": layers[4].weight_bytes}
+
+    def fp16_chain(x):
+        q = torch.matmul(x, wh["qkv"].t())
+        o = torch.matmul(q[:, :d], wh["o"].t())
+        gu = torch.matmul(o, wh["gate_up"].t())
+        return torch.matmul(tf.silu(gu[:, :F]) * gu[:, F:], wh["down"].t())
+
     for M in (512, 1024, 2048, 4096, 8192, 16384):
-        tot = {"fp16": 0.0, "w8a8": 0.0, "w4a8": 0.0}
-        for sh in base:
-            xh = torch.randn((M, sh.K), dtype=torch.float16, device="cuda:0")
-            wh = weights[(sh.layer, 16)]
-            reps = 10 if M >= 8192 else 20
-            tot["fp16"] += statistics.median(event_times_ms(torch, lambda i: torch.matmul(xh, wh.t()), reps, 3, 3))
-            for b in (8, 4):
-                wl = weights[(sh.layer, b)]
-                y = torch.empty((M, sh.N), dtype=torch.float16, device="cuda:0")
-                ws = torch.empty(ql.ql_workspace_bytes(M, sh.N, sh.K, b), dtype=torch.uint8, device="cuda:0")
-                if b == 8:
-                    fn = lambda i: ql.ql_w8a8_linear(xh, wl.kernels[0], wl.sw, wl.bias, sh.N, y, ws)
-                else:
-                    fn = lambda i: ql.ql_w4a8_linear(xh, wl.kernels[0], 128, wl.bias, sh.N, y, ws)
-                tot["w8a8" if b == 8 else "w4a8"] += statistics.median(event_times_ms(torch, fn, reps, 3, 3))
-                del y, ws
-            del xh
-            torch.cuda.empty_cache()
-        row = {"shape": f"layer7b.prefill.M{M}", "fp16_library_gemm_us": round(tot["fp16"] * 1e3, 1),
-               "w8a8_linear_us": round(tot["w8a8"] * 1e3, 1), "w4a8_linear_us": round(tot["w4a8"] * 1e3, 1),
-               "w8a8_speedup_over_fp16": round(tot["fp16"] / tot["w8a8"], 2),
-               "w4a8_speedup_over_fp16": round(tot["fp16"] / tot["w4a8"], 2)}
+        x = torch.from_numpy(synth.activations(M, d, 2, "qkv")).to("cuda:0")
+        reps = 5 if M >= 8192 else 10
+        t = {"fp16": statistics.median(event_times_ms(torch, lambda i: fp16_chain(x), reps, 3, 2))}
+        for b in (8, 4):
+            t["w8a8" if b == 8 else "w4a8"] = statistics.median(event_times_ms(torch, lambda i, b=b: layers[b].forward(x), reps, 3, 2))
+        row = {"shape": f"layer7b.prefill.M{M}", "fp16_library_us": round(t["fp16"] * 1e3, 1),
+               "w8a8_us": round(t["w8a8"] * 1e3, 1), "w4a8_us": round(t["w4a8"] * 1e3, 1),
+               "w8a8_speedup_over_fp16": round(t["fp16"] / t["w8a8"], 2),
+               "w4a8_speedup_over_fp16": round(t["fp16"] / t["w4a8"], 2)}
         log("[detail]", json.dumps(row))
         rows.append(row)
+        del x
     rows.append({"shape": "layer7b.weight_mb", **{k: round(v / 1e6, 1) for k, v in mem.items()}})
     log("[detail]", json.dumps(rows[-1]))
-    del weights
+    del layers, wh
     torch.cuda.empty_cache()
     return rows
 
