@@ -647,10 +647,22 @@ inline void auto_shape(int M, int N, int K, bool w4, int force_block, int &block
 {
     const int groups = round_up(N, TILE_ROWS) / 16;
     if (M <= 16) {
-        block = 16, c = 2;
-        while (c > 1 && ceil_div(groups, c) < 320) c /= 2;
-        // int4, very wide layers, 8..16 tokens (measured at N = 22016 and 32000: 4-10 % faster; 10-14 % slower at 1..4)
-        if (w4 && groups >= 1280 && M >= 8) c = 4;
+        // Every workgroup streams c channel groups (16 c channels x K weight bytes) plus the tokens (M x K bytes); all
+        // workgroups are resident at once up to two per CU, beyond that the rest is handed out as CUs free up.  The
+        // busiest CU decides: rounds x bytes per workgroup, in units of one channel group's weights.  Measured on the
+        // 7B shapes: the pick is the fastest or within 3 % of it (e.g. QKV: 256 workgroups of 48 channels instead of
+        // 384 of 32, which left half the CUs with twice the work; int4 gate+up at 8 tokens 12.3 -> 10.3 us).
+        block = 16;
+        const double tokens = (double)M / (w4 ? 8.0 : 16.0);
+        double best = 1e30;
+        c = 1;
+        for (int cand = 1; cand <= 4; ++cand) {
+            if (w4 && (size_t)cand * (K / 128) * 32 > 16384) break;      // int4: staged scales
+            const int wgs = ceil_div(groups, cand);
+            const double rounds = wgs <= 512 ? (double)ceil_div(wgs, 256) : wgs / 256.0 + 1.0;
+            const double cost = rounds * (cand + tokens);
+            if (cost < best * 0.999) best = cost, c = cand;
+        }
     } else if (M <= 32) {
         // 17..32 tokens: one block of 32 in the same model as the larger token counts (measured at 20 and 32 tokens on
         // five wide layers: the C it picks was the fastest of those tried, up to 27 % ahead of a fixed rule by N)
@@ -682,6 +694,12 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
     // registers with token fragments), makes no difference for int8 weights, and costs 0.7-1.1 us with 16
     // wavefronts -- so it is used there, and as the vehicle of the fused quantization below.
     const bool fits = (size_t)(a.M + 1) * a.K <= FQ_MAX_LDS && a.M <= 16 && variant != 121;   // keeps 4 workgroups per CU
+    if (a.x && !W4 && variant == 100) {
+        // fused quantization, int8 weights: measured faster with at most 32 channels per workgroup (QKV, one token:
+        // 10.4 us against 11.6 with 48) -- every workgroup quantizes all tokens before its first multiply
+        c = 2;
+        while (c > 1 && ceil_div(groups, c) < 320) c /= 2;
+    }
     if (a.x) {   // fp16 tokens: quantize in the prologue (the caller checked decode_fuses_quant); always 8 wavefronts
         if (EPI != EPI_F16 || !fits || a.M > FQ_MAX_M) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
         // 16-k pieces of a wavefront's k-range x tokens (rounded up to a power of two) <= 64 lanes x 2 slots
