@@ -85,7 +85,8 @@ int ql_act_kernel_bytes(int M, int K, size_t *bytes /* host */);
 /* Workspace for ql_w8a8_linear / ql_w4a8_linear for these sizes: the quantized activations in kernel layout
  * and their scales (required), followed by scratch for split-K partial sums (offered when the output has too
  * few tiles to occupy the GPU: more than 32 tokens, long K; up to 64 MiB).  The *_gemm calls take scratch only:
- * their ws may be NULL or smaller, then K is not split. */
+ * their ws may be NULL or smaller, then K is not split.
+ * A workspace serves one call at a time: calls that may run concurrently need workspaces of their own. */
 int ql_workspace_bytes(int M, int N, int K, int bits, size_t *bytes /* host */);
 
 /* Per-token dynamic int8 activation quantization (Eq. 1-2 with n = 8, one scale per token).
@@ -192,7 +193,8 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
  *   0 = automatic (decode kernels for M <= 32; up to 1024 tokens whichever of the decode kernels, working on
  *       blocks of 64 or 32 tokens, and the prefill tile kernels has the lower estimated time; prefill tiles beyond)
  *   1 = automatic among the prefill tile kernels, 100 = automatic among the decode kernels (M <= 1024)
- *   other values pick one implementation: 4, 6, 11, 13, 15, 17, 19, 20, 23 prefill tile shapes; 202..232 / 302..332
+ *   other values pick one implementation: 4, 6, 11, 13, 15, 17, 19, 20, 23 prefill tile shapes (26, 35, 37, 39, 43: the
+ *   shapes 6, 15, 17, 19, 23 on the 16x16x64 matrix instruction); 202..232 / 302..332
  *   split-K with that many splits on 128x128 / 256x256 tiles; 101..104, 106, 108 decode kernels with that many
  *   groups of 16 channels per workgroup; 111 sixteen wavefronts; 121 tokens never staged in LDS; 122 / 123 token
  *   blocks of 32 / 64; 130 quantizer never fused into the decode GEMM.  Unknown values -> QL_ERR_UNSUPPORTED. */
