@@ -414,6 +414,7 @@ def main():
                 "from HBM, not from the 256 MB Infinity Cache" if not args.weight_copies else
                 f"synthetic; {args.weight_copies} cop{'y' if args.weight_copies == 1 else 'ies'} of every weight matrix",
         "launch": "hip graph replay" if decode else "stream launches",
+        "inputs_sha256_16": hashes,
         "config": {"workload": descr, "layers": [s.name for s in shapes],
                    "weights": "int8 per-channel" if shapes[0].bits == 8 else "int4 group-128",
                    "activations": "int8 per-token dynamic", "output": "fp16"},

@@ -34,8 +34,12 @@ def gpu_quant_act(x16: np.ndarray, ldx: int | None = None):
     return xq.cpu().numpy(), sx.cpu().numpy(), xk
 
 
-def gpu_quant_weight(w16: np.ndarray, bits: int, group: int):
-    """Returns dict(canon, scales, kernel (device), N, K) with canon/scales as host arrays."""
+def gpu_quant_weight(w16: np.ndarray, bits: int, group: int, check: bool = True):
+    """Quantizes w16 on the GPU and returns dict(canon, scales, kernel (device), N, K, ...).
+
+    With `check` (default) the oracle quantizes the same weights itself, the GPU's codes and scales are compared with
+    its bit for bit, and the host arrays returned as `canon` / `scales` are the ORACLE's: every reference a test then
+    computes from them comes from the oracle alone, nothing the oracle consumes was produced by the GPU."""
     N, K = w16.shape
     cb, sb, kb = ql.ql_weight_bytes(N, K, bits, group)
     canon = empty_bytes(cb)
@@ -49,6 +53,15 @@ def gpu_quant_weight(w16: np.ndarray, bits: int, group: int):
     else:
         c = canon.cpu().numpy().reshape(N, K // 2)
         s = scales.cpu().numpy().view(np.float16).reshape(N, K // group)
+    if check:
+        import oracle
+        if bits == 8:
+            c_o, s_o = oracle.quant_weight_int8(w16)
+            assert (c == c_o).all() and (s.view(np.uint32) == s_o.view(np.uint32)).all(), "GPU weight quantization differs from the oracle's"
+        else:
+            c_o, _, s_o = oracle.quant_weight_int4(w16, group)
+            assert (c == c_o).all() and (s.view(np.uint16) == s_o.view(np.uint16)).all(), "GPU weight quantization differs from the oracle's"
+        c, s = c_o, s_o
     return dict(canon=c, scales=s, scales_dev=scales, kernel=kern, N=N, K=K, bits=bits, group=group)
 
 

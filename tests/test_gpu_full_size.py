@@ -47,7 +47,7 @@ def _scratch_bytes(sh):
 
 def _check_shape(G, sh):
     x, w, b = synth.tensors(sh)
-    g = G.gpu_quant_weight(w, sh.bits, sh.group)
+    g = G.gpu_quant_weight(w, sh.bits, sh.group, check=False)     # compared in full right below
     if sh.bits == 8:
         wq_o, sw_o = oracle.quant_weight_int8(w)
         assert (g["canon"] == wq_o).all() and (g["scales"].view(np.uint32) == sw_o.view(np.uint32)).all()
