@@ -223,7 +223,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const int nchunks = p.K / 64;
         const int per = (nchunks + WAVES - 1) / WAVES;
         const int c0 = wave * per, c1 = (c0 + per < nchunks) ? c0 + per : nchunks;
-        constexpr int U = C >= QL_RING8 ? 1 : QL_RING8 / C;
+        constexpr int U = C >= QL_RING8 ? 1 : (QL_RING8 + C - 1) / C;
         v4i wv[U][C], xv[XL ? 1 : U][MH];
         const int th0 = 4 * c0, th1 = c0 < c1 ? 4 * c1 : 4 * c0;
         if constexpr (!XL && MH >= 2) {
@@ -321,7 +321,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         const char *xb4 = reinterpret_cast<const char *>(p.xq) + (2 * (ch / 2)) * 1024 + (r + 32 * (ch % 2)) * 16;
                 // a short ring keeps the register count low: more resident workgroups hide a workgroup's serial
         // load -> unpack -> multiply -> fold -> reduce chain better than a deeper ring does
-        constexpr int U = C >= QL_RING4 ? 1 : QL_RING4 / C;   // without XL a slot also holds token fragments
+        constexpr int U = C >= QL_RING4 ? 1 : (QL_RING4 + C - 1) / C;   // without XL a slot also holds token fragments
         v4i wv[U][C], xv[XL ? 1 : U][2][MH];
         // 17 tokens and more (8 wavefronts; the accumulator dump runs the same loop): branch-free refills through range-checked buffer loads, as
         // in the int8 loop above (absent rows and channel groups: lane offset behind the buffer; groups past this
