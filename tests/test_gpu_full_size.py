@@ -148,3 +148,25 @@ def test_config4_long_prefill(G):
     accumulators of the sampled rows bit-exact, fp16 layer within tolerance."""
     sh = [s for s in synth.workload(4) if s.M > 32][0]
     _check_shape(G, sh)
+
+
+def test_7b_down_projection_input_through_swiglu(G):
+    """SwiGLU + quantizer at the size of the 7B layer's down-projection input (4096 tokens x 11008 features from a
+    4096 x 22016 gate+up output): codes and scales of sampled tokens bit-exact against the oracle (tokens are
+    independent), the whole tile-order copy consistent with the row-major one."""
+    from test_gpu_swiglu import _gate_up
+    M, F = 4096, 11008
+    gu = _gate_up(M, F, 5)
+    rows = _sample_rows(M, F)
+    xq_o, sx_o = oracle.quant_act_per_token(oracle.swiglu_act(gu[rows]))
+    d = G.dev(gu)
+    xq = torch.empty((M, F), dtype=torch.int8, device=G.DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=G.DEV)
+    xk = G.empty_bytes(ql.ql_act_kernel_bytes(M, F))
+    ql.ql_quant_act_swiglu(d, xq, xk, sx)
+    xk2 = G.empty_bytes(ql.ql_act_kernel_bytes(M, F))
+    ql.ql_act_repack(xq, xk2)
+    torch.cuda.synchronize()
+    assert (xq.cpu().numpy()[rows] == xq_o).all()
+    assert (sx.cpu().numpy()[rows].view(np.uint32) == sx_o.view(np.uint32)).all()
+    assert torch.equal(xk, xk2)

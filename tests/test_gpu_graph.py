@@ -88,3 +88,26 @@ def test_quantizers_in_a_graph(G):
         ql.ql_quant_act_per_token_transformed(x, None, B, xq3, None, sx3)
         ql.ql_quant_act_rmsnorm(x, gamma, 1e-6, xq4, None, sx4)
     _replay_and_compare(torch, enqueue, [xq, sx, xq2, sx2, xq3, sx3, xq4, sx4])
+
+
+def test_static_workspace_linear_and_swiglu_in_a_graph(G):
+    """The entry point for callers that cannot allocate is the one a graph-capturing caller would use: captured after
+    one eager call (which looks up the static workspace's device address), every replay reproduces the eager result.
+    The SwiGLU quantizer in front of a GEMM goes through the same check."""
+    import torch
+    M, K, N, F = 300, 1536, 520, 512
+    x = G.dev(synth.activations(M, K, 0, "single"))
+    g = G.gpu_quant_weight(synth.weights(N, K, 0, "single"), 8, 0)
+    b = G.dev(synth.bias(N, 0, "single"))
+    y = torch.zeros((M, N), dtype=torch.float16, device="cuda:0")
+    gu = G.dev(synth.activations(M, 2 * F, 1, "single"))
+    gd = G.gpu_quant_weight(synth.weights(N, F, 1, "single"), 8, 0)
+    xk = G.empty_bytes(ql.ql_act_kernel_bytes(M, F))
+    sx = torch.zeros(M, dtype=torch.float32, device="cuda:0")
+    y2 = torch.zeros((M, N), dtype=torch.float16, device="cuda:0")
+
+    def enqueue():
+        ql.ql_w8a8_linear_static(x, g["kernel"], g["scales_dev"].view(torch.float32), b, N, y)
+        ql.ql_quant_act_swiglu(gu, None, xk, sx)
+        ql.ql_w8a8_gemm(xk, sx, M, F, gd["kernel"], gd["scales_dev"].view(torch.float32), None, N, y2)
+    _replay_and_compare(torch, enqueue, [y, sx, y2])
