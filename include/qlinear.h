@@ -192,7 +192,8 @@ int ql_w4a8_gemm_acc_i32(const int8_t *xq_kernel, int M, int K, const void *w4_k
  * thread makes afterwards; other threads keep theirs, initially 0):
  *   0 = automatic (decode kernels for M <= 32; up to 1024 tokens whichever of the decode kernels, working on
  *       blocks of 64 or 32 tokens, and the prefill tile kernels has the lower estimated time; prefill tiles beyond)
- *   1 = automatic among the prefill tile kernels, 100 = automatic among the decode kernels (M <= 1024)
+ *   1 = automatic among the prefill tile kernels (2: the same, always as one launch -- see ql_plan.rest_channels),
+ *   100 = automatic among the decode kernels (M <= 1024)
  *   other values pick one implementation: 4, 6, 11, 13, 15, 17, 19, 20, 23 prefill tile shapes (26, 35, 37, 39, 43: the
  *   shapes 6, 15, 17, 19, 23 on the 16x16x64 matrix instruction); 202..232 / 302..332
  *   split-K with that many splits on 128x128 / 256x256 tiles; 101..104, 106, 108 decode kernels with that many
@@ -215,6 +216,9 @@ typedef struct ql_plan {
     int tile_channels;
     int splits;         /* workgroups sharing one tile's K range (1: unsplit; > 1 needs the scratch) */
     double est_us;      /* the estimate the choice was made by, microseconds (model fitted to measurements on MI355X) */
+    int rest_channels;  /* > 0: the GEMM runs as two launches on disjoint channel ranges -- the first N - rest_channels
+                           channels as described above (whole passes over the CUs), the last rest_channels channels with */
+    int rest_variant;   /* this configuration; est_us covers both.  Results are bit-identical to one launch. */
 } ql_plan;
 int ql_plan_gemm(int M, int N, int K, int bits, int group, size_t scratch_bytes, ql_plan *plan);
 

@@ -35,7 +35,8 @@ QL_FAMILY_DECODE, QL_FAMILY_TILE = 1, 2
 class QlPlan(ctypes.Structure):
     """Mirror of the C struct ql_plan."""
     _fields_ = [("family", ctypes.c_int), ("variant", ctypes.c_int), ("tile_tokens", ctypes.c_int),
-                ("tile_channels", ctypes.c_int), ("splits", ctypes.c_int), ("est_us", ctypes.c_double)]
+                ("tile_channels", ctypes.c_int), ("splits", ctypes.c_int), ("est_us", ctypes.c_double),
+                ("rest_channels", ctypes.c_int), ("rest_variant", ctypes.c_int)]
 
 
 QL_SCOPE_FINE, QL_SCOPE_TENSOR, QL_SCOPE_STATIC = 0, 1, 2

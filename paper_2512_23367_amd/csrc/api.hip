@@ -237,7 +237,7 @@ int ql_set_kernel_variant(int variant)
 {
     // 0 automatic; 1 automatic among the tile kernels; prefill tile configurations; decode configurations; split-K with 2..32 splits on 128x128 / 256x256 tiles
     static const int prefill[] = {4, 6, 11, 13, 15, 17, 19, 20, 23, 26, 35, 37, 39, 43};
-    bool known = variant == 0 || variant == 1 || (variant >= 100 && variant <= 104) || variant == 106 || variant == 108 || variant == 111 || (variant >= 121 && variant <= 123) || variant == 130 ||
+    bool known = variant == 0 || variant == 1 || variant == 2 || (variant >= 100 && variant <= 104) || variant == 106 || variant == 108 || variant == 111 || (variant >= 121 && variant <= 123) || variant == 130 ||
                  (variant >= 202 && variant <= 232) || (variant >= 302 && variant <= 332);
     for (int v : prefill) known = known || variant == v;
     if (!known)
@@ -269,7 +269,8 @@ int ql_plan_gemm(int M, int N, int K, int bits, int group, size_t scratch_bytes,
         plan->est_us = decode_estimate_us(a);
     } else {
         plan->family = QL_FAMILY_TILE;
-        prefill_plan(a, &plan->variant, &plan->tile_tokens, &plan->tile_channels, &plan->splits);
+        prefill_plan(a, &plan->variant, &plan->tile_tokens, &plan->tile_channels, &plan->splits, &plan->rest_channels,
+                     &plan->rest_variant);
         plan->est_us = prefill_estimate_us(a);
     }
     return QL_OK;

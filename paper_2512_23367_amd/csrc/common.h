@@ -121,6 +121,7 @@ struct GemmArgs {
     __half *y;             // [M, ldy]
     int64_t ldy;
     int32_t *acc;          // accumulator dump [M,N] (test hook) or nullptr
+    int64_t ldacc;         // its row stride (0: N)
     int32_t *partials;     // W4A8 group partials [nrows, G, N] or nullptr
     int row0, nrows;
     int M, N, K;
@@ -134,7 +135,8 @@ int launch_gemm_decode(const GemmArgs &a, int variant, hipStream_t st);
 double prefill_estimate_us(const GemmArgs &a);
 double decode_estimate_us(const GemmArgs &a);
 // what the automatic choice would launch (host only)
-void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_channels, int *splits);
+void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_channels, int *splits, int *rest_channels,
+                  int *rest_variant);
 void decode_plan(const GemmArgs &a, int *token_block, int *channel_groups);
 bool decode_fuses_quant(int M, int K, int variant);
 

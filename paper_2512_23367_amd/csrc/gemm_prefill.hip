@@ -51,6 +51,7 @@ struct PrefillParams {
     __half *y;
     int64_t ldy;
     int32_t *acc;
+    int64_t ldacc;           // row stride of acc
     int32_t *partials;
     int row0, nrows;
     int M, N, K, Npad;
@@ -547,8 +548,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                     for (int e = 0; e < 4; ++e) {
                         const int n = (tn * TNB + wn * WN + i) * 32 + ch_of(q) + e;
                         if (m < p.M && n < p.N) {
-                            if constexpr (W4) p.acc[(size_t)m * p.N + n] = tot[i][j][4 * q + e] >> 4;
-                            else p.acc[(size_t)m * p.N + n] = acc_get(i, j, q, e);
+                            if constexpr (W4) p.acc[(size_t)m * p.ldacc + n] = tot[i][j][4 * q + e] >> 4;
+                            else p.acc[(size_t)m * p.ldacc + n] = acc_get(i, j, q, e);
                         }
                     }
                 }
@@ -628,6 +629,7 @@ struct FinishParams {
     __half *y;
     int64_t ldy;
     int32_t *acc;            // test hook (int8 weights): raw sums instead of y
+    int64_t ldacc;
     int M, N;
     int tiles_m, tiles_n, group_m, splits;
 };
@@ -681,7 +683,7 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
             if (m >= f.M) continue;
             const int b = i * WM + j;
             if (f.acc) {
-                for (int e = 0; e < 4 && n0 + e < f.N; ++e) f.acc[(size_t)m * f.N + n0 + e] = si[b][e];
+                for (int e = 0; e < 4 && n0 + e < f.N; ++e) f.acc[(size_t)m * f.ldacc + n0 + e] = si[b][e];
                 continue;
             }
             const float sxm = f.sx[m] * (W4 ? 0.0625f : 1.0f);
@@ -726,6 +728,7 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     p.y = a.y;
     p.ldy = a.ldy;
     p.acc = a.acc;
+    p.ldacc = a.ldacc ? a.ldacc : a.N;
     p.partials = a.partials;
     p.row0 = a.row0;
     p.nrows = a.nrows;
@@ -756,6 +759,7 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     f.y = a.y;
     f.ldy = a.ldy;
     f.acc = a.acc;
+    f.ldacc = a.ldacc ? a.ldacc : a.N;
     f.M = a.M;
     f.N = a.N;
     f.tiles_m = p.tiles_m;
@@ -885,6 +889,55 @@ inline Choice choose_w8(const GemmArgs &a, size_t scratch, bool dump_partials)
     return best;
 }
 
+// Channel split (W8A8, more than 1024 tokens).  When the best configuration's tiles fill the last pass over the CUs
+// only partly (7B gate+up at 4096 tokens: 928 tiles of 256x384 = 3.6 passes, run as 4), the leading channels that
+// make whole passes go to one launch and the remaining channels to a second launch with the configuration that
+// suits them (there: 3 passes of 256x384 over 18432 channels, then one pass of 256x256 over 3584; measured 274
+// against 286 us).  Column ranges of the tile-order weights, the channel scales, the bias and the output are
+// contiguous or strided views, so the two launches are ordinary GEMMs on disjoint outputs: bit-identical results.
+struct ColumnSplit {
+    int n1;               // channels of the first launch (== N: one launch)
+    Choice first, rest;
+    double us;
+};
+
+inline ColumnSplit choose_w8_columns(const GemmArgs &a, size_t scratch, bool dump_partials)
+{
+    const Choice whole = choose_w8(a, scratch, dump_partials);
+    ColumnSplit best = {a.N, whole, {0, 1, 0.0}, whole.us};
+    if (a.M <= 1024 || whole.splits > 1) return best;
+    static const int shapes[3][2] = {{256, 384}, {256, 256}, {256, 192}};
+    for (const auto &sh : shapes) {
+        const long tiles_m = ceil_div(a.M, sh[0]);
+        const long tiles = tiles_m * ceil_div(a.N, sh[1]);
+        if (tiles_m > 256) continue;
+        for (long passes = 1; passes * 256 < tiles; ++passes) {
+            const long n1 = passes * 256 / tiles_m * sh[1];
+            if (n1 <= 0 || n1 >= a.N) continue;
+            GemmArgs a1 = a, a2 = a;
+            a1.N = (int)n1, a2.N = a.N - (int)n1;
+            const Choice c1 = choose_w8(a1, 0, dump_partials), c2 = choose_w8(a2, 0, dump_partials);
+            if (c1.us + c2.us < best.us * 0.97) best = {(int)n1, c1, c2, c1.us + c2.us};
+        }
+    }
+    return best;
+}
+
+// the channels [n0, n0 + n) of a W8A8 GEMM as a GEMM of its own
+inline GemmArgs column_range(const GemmArgs &a, int n0, int n)
+{
+    GemmArgs r = a;
+    r.N = n;
+    r.wq = static_cast<const char *>(a.wq) + (size_t)n0 * a.K;   // tile order: 32-channel row-blocks, contiguous
+    r.sw = a.sw ? a.sw + n0 : nullptr;
+    r.bias = a.bias ? a.bias + n0 : nullptr;
+    r.y = a.y ? a.y + n0 : nullptr;
+    r.ldacc = a.ldacc ? a.ldacc : a.N;
+    r.acc = a.acc ? a.acc + n0 : nullptr;
+    r.ws = nullptr, r.ws_bytes = 0;
+    return r;
+}
+
 // variant 0 = automatic choice; other values pick one of the configurations below (tests and tuning)
 template <bool W4, int EPI>
 int dispatch(const GemmArgs &a, int variant, hipStream_t st)
@@ -895,7 +948,7 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
     if (W4) {
         int splits = 1;
         if (variant >= 202 && variant <= 232) splits = variant - 200;
-        else if (variant == 0) splits = choose_w4(a, scratch, dump_partials).splits;
+        else if (variant == 0 || variant == 2) splits = choose_w4(a, scratch, dump_partials).splits;
         if (splits > 1 && EPI == EPI_F16 && !dump_partials) {
             const long tiles = (long)ceil_div(a.M, 128) * ceil_div(a.N, 256);
             if ((size_t)splits * tiles * 128 * 256 * 4 > scratch)
@@ -905,9 +958,14 @@ int dispatch(const GemmArgs &a, int variant, hipStream_t st)
         return launch_one<2, 4, 2, 2, 4, 4, true, EPI, 1, true>(a, st);
     }
     int splits = 1;
-    if (variant == 0) {
-        const Choice c = choose_w8(a, scratch, dump_partials);
-        variant = c.variant, splits = c.splits;
+    if (variant == 0 || variant == 2) {   // 2: the automatic choice without the channel split
+        const ColumnSplit cs = variant == 0 ? choose_w8_columns(a, scratch, dump_partials)
+                                            : ColumnSplit{a.N, choose_w8(a, scratch, dump_partials), {0, 1, 0.0}, 0.0};
+        if (cs.n1 < a.N) {
+            QL_TRY((dispatch<false, EPI>(column_range(a, 0, cs.n1), cs.first.variant, st)));
+            return dispatch<false, EPI>(column_range(a, cs.n1, a.N - cs.n1), cs.rest.variant, st);
+        }
+        variant = cs.first.variant, splits = cs.first.splits;
     } else if (variant >= 202 && variant <= 232) {
         splits = variant - 200, variant = 200;
     } else if (variant >= 302 && variant <= 332) {
@@ -960,19 +1018,26 @@ double prefill_estimate_us(const GemmArgs &a)
     const size_t scratch = a.ws ? a.ws_bytes : 0;
     // int4: the plan's times are ~15 % above the measured ones with the weights coming from HBM (16 layer shapes x 9
     // token counts); they only rank split counts there, here they meet another kernel's estimate
-    return a.bits == 4 ? 0.85 * choose_w4(a, scratch, a.partials != nullptr).us : choose_w8(a, scratch, a.partials != nullptr).us;
+    return a.bits == 4 ? 0.85 * choose_w4(a, scratch, a.partials != nullptr).us : choose_w8_columns(a, scratch, a.partials != nullptr).us;
 }
 
-void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_channels, int *splits)
+void prefill_plan(const GemmArgs &a, int *variant, int *tile_tokens, int *tile_channels, int *splits, int *rest_channels,
+                  int *rest_variant)
 {
     const size_t scratch = a.ws ? a.ws_bytes : 0;
+    *rest_channels = 0, *rest_variant = 0;
     if (a.bits == 4) {
         *splits = choose_w4(a, scratch, a.partials != nullptr).splits;
         *variant = *splits > 1 ? 200 + *splits : 0;
         *tile_tokens = 128, *tile_channels = 256;
         return;
     }
-    Choice c = choose_w8(a, scratch, a.partials != nullptr);
+    const ColumnSplit cs = choose_w8_columns(a, scratch, a.partials != nullptr);
+    Choice c = cs.first;
+    if (cs.n1 < a.N) {
+        *rest_channels = a.N - cs.n1;
+        *rest_variant = ((cs.rest.variant == 19 || cs.rest.variant == 39) && a.K % 128) ? 13 : cs.rest.variant;
+    }
     if ((c.variant == 19 || c.variant == 39) && a.K % 128) c.variant = 13;
     *splits = c.splits;
     *variant = c.variant == 200 || c.variant == 300 ? c.variant + c.splits : c.variant;

@@ -101,3 +101,27 @@ def test_argument_errors():
     assert lib.ql_plan_gemm(64, 128, 100, 8, 0, 0, ctypes.byref(p)) == 2           # K granularity
     assert lib.ql_plan_gemm(64, 128, 128, 8, 128, 0, ctypes.byref(p)) == 4         # unsupported (bits, group)
     assert lib.ql_plan_gemm(64, 128, 128, 8, 0, 0, ctypes.byref(p)) == 0
+
+
+def test_channel_split_only_where_whole_passes_are_left_partly_filled():
+    """7B gate+up at 4096 tokens: 928 tiles of 256x384 are 3.6 passes over 256 CUs; the plan runs 3 whole passes
+    (18432 channels) and gives the remaining 3584 channels to 256x256 tiles (224 of them, one pass).  Shapes whose tiles
+    already make whole passes, few-token shapes and int4 weights keep one launch."""
+    p = plan(4096, 22016, 4096)
+    assert (p.variant, p.tile_channels, p.rest_channels, p.rest_variant, p.splits) == (43, 384, 3584, 26, 1)
+    assert (22016 - p.rest_channels) % 384 == 0 and (4096 // 256) * ((22016 - p.rest_channels) // 384) % 256 == 0
+    for M, N, K in [(4096, 12288, 4096), (4096, 4096, 4096), (4096, 4096, 11008), (2048, 12288, 1536), (2048, 4608, 1536)]:
+        assert plan(M, N, K).rest_channels == 0
+    assert plan(1024, 22016, 4096).rest_channels == 0
+    assert plan(4096, 22016, 4096, bits=4).rest_channels == 0
+    assert plan(32, 22016, 4096).rest_channels == 0
+
+
+def test_channel_split_is_taken_only_for_a_lower_estimate_and_keeps_channel_blocks_whole():
+    for M, N, K in [(4096, 22016, 4096), (16384, 4096, 11008), (4096, 13824, 5120), (1100, 21767, 2048), (2048, 12289, 2048)]:
+        p = plan(M, N, K)
+        assert p.rest_channels > 0 and p.rest_variant > 0
+        first = N - p.rest_channels
+        assert first > 0 and first % p.tile_channels == 0          # whole tiles, hence whole 32-channel row-blocks
+        # the estimate is the sum of the two launches' own estimates (scratch is not shared between them)
+        assert p.est_us <= 1.0001 * (plan(M, first, K, scratch=0).est_us + plan(M, p.rest_channels, K, scratch=0).est_us)
