@@ -168,6 +168,29 @@ def profiled_traffic(cfg):
     return None
 
 
+def gpu_state_under_load(torch, enqueue_pass, passes):
+    """Clocks and power as rocm-smi reports them while `passes` passes over the workload's GEMMs are running
+    (a child process; None where the tool or its counters are not accessible)."""
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    if not os.path.exists(exe):
+        return None
+    for i in range(passes):
+        enqueue_pass(i)
+    state = None
+    try:
+        r = subprocess.run([exe, "--showclocks", "--showpower", "--json"], capture_output=True, text=True, timeout=20)
+        cards = json.loads(r.stdout) if r.returncode == 0 and r.stdout.strip().startswith("{") else {}
+        card = cards.get("card0") or (next(iter(cards.values())) if cards else None)
+        if isinstance(card, dict):
+            state = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "power"))}
+    except Exception as e:     # the tool is optional context
+        log("[gpu_state] rocm-smi not usable:", repr(e))
+    torch.cuda.synchronize()
+    return state or None
+
+
 def measured_ceilings(torch):
     """What this GPU sustains on the matrix pipe and on HBM reads, measured here and now (context for
     `roofline.frac`, which stays against the published peaks): register-resident int8 MFMA loop on every CU
@@ -424,6 +447,10 @@ def main():
                                            for l, t in zip(layers, gemm_ms))}
         roof["act_quant"] = "; ".join(f"{l.sh.layer} {t * 1e3:.1f} us {l.quant_bytes() / (t * 1e-3) / 1e9:.0f} GB/s"
                                       for l, t in zip(layers, quant_ms))
+        if not decode:
+            # ~0.25 s of GEMM work in flight while the tool samples
+            roof["gpu_state_under_load"] = gpu_state_under_load(torch, gemm_pass, 400)
+            log("[gpu_state]", json.dumps(roof["gpu_state_under_load"]))
 
     for _ in range(args.warmup):
         step()
