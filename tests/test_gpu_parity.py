@@ -418,3 +418,32 @@ def test_errors_are_reported_not_launched(G):
     with pytest.raises(ql.QlError) as e:
         ql.ql_w8a8_linear(x[:, :100], g["kernel"], g["scales_dev"].view(torch.float32), None, 64, y, G.empty_bytes(4096))
     assert e.value.status == 2
+
+
+def test_kernel_variant_is_a_setting_of_the_calling_thread(G):
+    """A worker thread selects split-K (which needs scratch the call does not get, so its GEMM is refused) and leaves
+    that setting behind; the main thread's setting is untouched: its GEMM of the same shape runs with the automatic
+    choice and matches the oracle.  Two threads with different tile variants give the same exact sums."""
+    import threading
+    M, K, N = 100, 1536, 264
+    rng = np.random.default_rng(77)
+    xq = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    g = G.gpu_quant_weight(synth.weights(N, K, 0, "single"), 8, 0)
+    ref = oracle.igemm(xq, g["canon"])
+    seen = {}
+
+    def worker(name, variant):
+        try:
+            ql.ql_set_kernel_variant(variant)
+            seen[name] = G.gpu_acc(xq, g)[0]
+        except ql.QlError as e:
+            seen[name] = e.status
+
+    for name, variant in (("split", 208), ("tile13", 13), ("tile26", 26)):
+        t = threading.Thread(target=worker, args=(name, variant))
+        t.start()
+        t.join()
+    assert seen["split"] == 5                                   # QL_ERR_WORKSPACE, reported in that thread only
+    assert (seen["tile13"] == ref).all() and (seen["tile26"] == ref).all()
+    acc, _ = G.gpu_acc(xq, g)                                   # this thread never changed its setting
+    assert (acc == ref).all()
