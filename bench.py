@@ -194,7 +194,8 @@ def gpu_state_under_load(torch, enqueue_pass, passes):
 def measured_ceilings(torch):
     """What this GPU sustains on the matrix pipe and on HBM reads, measured here and now (context for
     `roofline.frac`, which stays against the published peaks): register-resident int8 MFMA loop on every CU
-    with constant and with hashed operands, and a read stream over 2 GiB (helper library libqlprobe.so)."""
+    with constant and with hashed operands, a read stream over 2 GiB, and the global->LDS loads of an L2-resident
+    buffer (helper library libqlprobe.so)."""
     from paper_2512_23367_amd import probe
     sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
     out = {}
@@ -211,6 +212,15 @@ def measured_ceilings(torch):
     ms = min(event_times_ms(torch, lambda i: probe.hbm_read(buf, sink), 5, 3, 2))
     out["hbm_read_stream_gbs"] = round(buf.numel() / (ms * 1e-3) / 1e9, 1)
     del buf
+    # the path the GEMM tiles travel by: 16-byte-per-lane global->LDS loads on an L2-resident buffer, all 256 CUs
+    l2buf = torch.zeros(256 * 65536, dtype=torch.uint8, device="cuda:0")
+    moved = [0]
+
+    def g(i):
+        moved[0] = probe.l2_to_lds(l2buf, 2000, sink)
+    ms = min(event_times_ms(torch, g, 2, 3, 1))
+    out["l2_to_lds_loads_gbs"] = round(moved[0] / (ms * 1e-3) / 1e9, 1)
+    del l2buf
     torch.cuda.empty_cache()
     return out
 

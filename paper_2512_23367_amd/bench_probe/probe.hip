@@ -104,6 +104,28 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const v4i *__restrict__
 
 }  // namespace
 
+// L2 -> LDS: every wavefront re-reads its own 8 KiB of an L2-resident buffer (64 KiB per workgroup: more than the L1
+// holds) with the 16-byte-per-lane global->LDS loads the GEMM tiles travel by; fixed trip count, all offsets inside
+// the buffer (workgroups x 64 KiB) and inside the workgroup's 64 KiB of LDS.
+constexpr int L2LDS_WG_BYTES = 64 * 1024, L2LDS_WAVE_BYTES = 8 * 1024;
+__global__ __launch_bounds__(512, 1) void probe_l2_to_lds_kernel(const char *src, unsigned bytes, int iters, int *sink)
+{
+    extern __shared__ __attribute__((aligned(1024))) char probe_smem[];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(src), 0, (int)bytes, 0x00020000);
+    const unsigned base = blockIdx.x * L2LDS_WG_BYTES + wave * L2LDS_WAVE_BYTES;
+    char *slot = probe_smem + wave * L2LDS_WAVE_BYTES;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)(slot + j * 1024), 16,
+                                                     base + j * 1024 + lane * 16, 0, 0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    const v4i keep = *reinterpret_cast<const v4i *>(slot + lane * 16);
+    if ((keep[0] ^ keep[1] ^ keep[2] ^ keep[3]) == 0x12345678 && iters < 0) sink[0] = 1;
+}
+
 extern "C" {
 
 __attribute__((visibility("default"))) int qlprobe_mfma_int8(int workgroups, int iters, int random_operands, void *sink,
@@ -122,6 +144,21 @@ __attribute__((visibility("default"))) int qlprobe_hbm_read(const void *buf, siz
     if (!buf || !sink || (reinterpret_cast<uintptr_t>(buf) & 15) || bytes % 16) return 1;
     hipLaunchKernelGGL(probe_read_kernel, dim3(256 * 16), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const v4i *>(buf), bytes / 16, static_cast<int *>(sink));
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+__attribute__((visibility("default"))) int qlprobe_l2_to_lds(const void *buf, size_t bytes, int iters, void *sink,
+                                                             int64_t *moved /* host */, void *stream)
+{
+    const size_t wgs = bytes / L2LDS_WG_BYTES;
+    if (!buf || !sink || (reinterpret_cast<uintptr_t>(buf) & 255) || wgs < 1 || wgs > 4096 || bytes % L2LDS_WG_BYTES || iters < 1)
+        return 1;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(probe_l2_to_lds_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, L2LDS_WG_BYTES);
+    if (attr != hipSuccess) return 2;
+    if (moved) *moved = (int64_t)wgs * L2LDS_WG_BYTES * iters;
+    hipLaunchKernelGGL(probe_l2_to_lds_kernel, dim3((unsigned)wgs), dim3(512), L2LDS_WG_BYTES, static_cast<hipStream_t>(stream),
+                       static_cast<const char *>(buf), (unsigned)bytes, iters, static_cast<int *>(sink));
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 

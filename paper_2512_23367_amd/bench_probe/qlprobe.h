@@ -8,6 +8,9 @@
  *     receives the operation count.
  *   qlprobe_hbm_read: streams `bytes` bytes of `buf` (device, 16-byte aligned) once through non-temporal 16-byte
  *     loads.
+ *   qlprobe_l2_to_lds: one workgroup of 8 wavefronts per 64 KiB of `buf` (device, 256-byte aligned, a multiple of
+ *     64 KiB, at most 4096 of them; keep it L2-resident: 16 MiB for 256 workgroups) re-reads its 64 KiB `iters` times
+ *     with 16-byte-per-lane global->LDS loads, the way the GEMM tiles travel; *moved (host, may be NULL) receives the bytes.
  * `sink` is a device int the kernels never actually write (it keeps their loops alive). */
 #ifndef QLPROBE_H
 #define QLPROBE_H
@@ -18,6 +21,7 @@ extern "C" {
 #endif
 int qlprobe_mfma_int8(int workgroups, int iters, int random_operands, void *sink, int64_t *ops /* host */, void *stream);
 int qlprobe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream);
+int qlprobe_l2_to_lds(const void *buf, size_t bytes, int iters, void *sink, int64_t *moved /* host */, void *stream);
 #ifdef __cplusplus
 }
 #endif

@@ -25,6 +25,8 @@ def lib() -> ctypes.CDLL:
         l.qlprobe_mfma_int8.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int64), vp]
         l.qlprobe_hbm_read.restype = ctypes.c_int
         l.qlprobe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        l.qlprobe_l2_to_lds.restype = ctypes.c_int
+        l.qlprobe_l2_to_lds.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int64), vp]
         _lib = l
     return _lib
 
@@ -49,3 +51,13 @@ def hbm_read(buf, sink):
                                 ctypes.c_void_p(sink.data_ptr()), _stream())
     if rc:
         raise RuntimeError(f"qlprobe_hbm_read failed ({rc})")
+
+
+def l2_to_lds(buf, iters: int, sink) -> int:
+    """Enqueues the global->LDS load probe over `buf` (64 KiB per workgroup); returns the bytes it moves."""
+    moved = ctypes.c_int64()
+    rc = lib().qlprobe_l2_to_lds(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(), int(iters),
+                                 ctypes.c_void_p(sink.data_ptr()), ctypes.byref(moved), _stream())
+    if rc:
+        raise RuntimeError(f"qlprobe_l2_to_lds failed ({rc})")
+    return moved.value
