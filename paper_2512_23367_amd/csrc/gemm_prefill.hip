@@ -142,11 +142,14 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     // behind the stage buffers: the tile's token scales, channel scales and bias as fp32, fetched once at
     // the start so that the epilogue reads them from LDS instead of waiting for global memory
+    // (each array is padded to a whole number of entries per thread, so that every thread stores its entries
+    // unconditionally: a store under a condition lets the compiler sink the load behind the stage loads)
+    constexpr int SXI = (TMB * 32 + NW * 64 - 1) / (NW * 64), SWI = (TNB * 32 + NW * 64 - 1) / (NW * 64);
     float *side_sx = reinterpret_cast<float *>(smem + STAGES * STAGE_BYTES);
-    float *side_sw = side_sx + TMB * 32;
-    float *side_b = side_sw + TNB * 32;
+    float *side_sw = side_sx + SXI * NW * 64;
+    float *side_b = side_sw + SWI * NW * 64;
     // int4 ping-pong: per stage and wavefront a 256-byte slot with the fp16 group scales of its WN*32 channels
-    char *scale_slots = reinterpret_cast<char *>(side_b + TNB * 32);
+    char *scale_slots = reinterpret_cast<char *>(side_b + SWI * NW * 64);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -155,17 +158,40 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     int tm, tn;
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
 
-    if (EPI == EPI_F16) {
+    // The epilogue operands are requested here, in front of the first stages' loads, and parked in registers: loads
+    // return in order, so waiting for these three does not wait for the stages behind them, and the stages are on
+    // their way one memory round trip after the kernel starts instead of four (one per operand, then the stages).
+    // Range-checked buffer loads (an index beyond M / N, or an absent operand = a zero-length buffer, reads 0): no
+    // branch, hence no wait where branches would join.
+    // (int8 kernels.  The int4 kernel keeps the plain form -- load, wait, store, operand by operand: with the early
+    // loads its main loop came out 3-4 % slower, the fill being a smaller share of its longer tiles anyway.)
+    int r_sx[SXI], r_sw[SWI];
+    short r_b[SWI];   // converted when it is written to LDS: a conversion here would wait for the load
+    if (W4 && EPI == EPI_F16) {
         for (int t = threadIdx.x; t < TMB * 32; t += NW * 64) {
             const int m = tm * TMB * 32 + t;
             side_sx[t] = (m < p.M) ? p.sx[m] : 0.0f;
         }
         for (int t = threadIdx.x; t < TNB * 32; t += NW * 64) {
             const int n = tn * TNB * 32 + t;
-            side_sw[t] = (!W4 && n < p.N) ? p.sw[n] : 0.0f;
+            side_sw[t] = 0.0f;
             side_b[t] = (p.bias && n < p.N) ? __half2float(p.bias[n]) : 0.0f;
         }
-    }   // made visible by the barriers of the main loop / the one in front of the epilogue
+    }
+    if (!W4 && EPI == EPI_F16) {
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.sx, (unsigned)p.M * 4u);
+        const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, p.sw ? (unsigned)p.N * 4u : 0u);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (unsigned)p.N * 2u : 0u);
+#pragma unroll
+        for (int it = 0; it < SXI; ++it)
+            r_sx[it] = __builtin_amdgcn_raw_buffer_load_b32(rx, (unsigned)(tm * TMB * 32 + threadIdx.x + it * NW * 64) * 4u, 0, 0);
+#pragma unroll
+        for (int it = 0; it < SWI; ++it) {
+            const unsigned n = (unsigned)(tn * TNB * 32 + threadIdx.x + it * NW * 64);
+            r_sw[it] = __builtin_amdgcn_raw_buffer_load_b32(rw, n * 4u, 0, 0);
+            r_b[it] = __builtin_amdgcn_raw_buffer_load_b16(rb, n * 2u, 0, 0);
+        }
+    }
 
     const int KB = p.K / 32;                             // k-blocks
     // split-K: this workgroup multiplies stages [stage0, stage0 + nstages) only (never an empty range)
@@ -264,6 +290,17 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     // prologue: STAGES-1 stages in flight
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) issue_stage(s);
+    if (!W4 && EPI == EPI_F16) {   // made visible by the barriers of the main loop / the one in front of the epilogue
+#pragma unroll
+        for (int it = 0; it < SXI; ++it) {
+            side_sx[threadIdx.x + it * NW * 64] = __int_as_float(r_sx[it]);
+        }
+#pragma unroll
+        for (int it = 0; it < SWI; ++it) {
+            side_sw[threadIdx.x + it * NW * 64] = __int_as_float(r_sw[it]);
+            side_b[threadIdx.x + it * NW * 64] = __half2float(__ushort_as_half((unsigned short)r_b[it]));
+        }
+    }
 
     const int n_lane0 = (tn * TNB + wn * WN) * 32 + 4 * (lane >> 5);   // + bi*32 + 8*q + (r%4)
     const int m_lane0 = (tm * TMB + wm * WM) * 32 + (lane & 31);       // + bj*32
@@ -440,6 +477,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                     xf[kb][j] = *reinterpret_cast<const v4i *>(buf + XOFF + ((wm * WM + j) * KBS + kb) * 1024 + lane * 16);
             issue_stage(it + STAGES - 1);        // into the buffer of stage it-1: both groups are done with it
             fold_all(it - 1);
+            __builtin_amdgcn_sched_barrier(0);   // the fold stays in front of the wait: it covers the loads' latency
             wait_stage();    // own loads of stage it+1 have landed
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): fragments are in registers, the buffer may be reused
             __builtin_amdgcn_s_barrier();
@@ -710,7 +748,9 @@ int launch_one(const GemmArgs &a, hipStream_t st, int splits = 1)
     constexpr int TM = WAVES_M * WM * 32, TN = WAVES_N * WN * 32;
     constexpr int XFR = WAVES_M * WM * KBS;
     constexpr int WFR = W4 ? WAVES_N * WN * KBS / 2 : WAVES_N * WN * KBS;
-    constexpr int LDS = (XFR + WFR) * 1024 * STAGES + (TM + 2 * TN) * 4 +   // stages + epilogue side area
+    constexpr int THREADS = WAVES_M * WAVES_N * WK * 64;
+    constexpr int LDS = (XFR + WFR) * 1024 * STAGES +
+                        ((TM + THREADS - 1) / THREADS + 2 * ((TN + THREADS - 1) / THREADS)) * THREADS * 4 +   // + epilogue side area (padded per thread)
                         (W4 ? STAGES * WAVES_M * WAVES_N * WK * 256 : 0);  // + int4 group-scale slots
     static_assert(LDS <= 160 * 1024, "LDS budget");
     static_assert((STAGES - 2) * ((XFR + WFR) / (WAVES_M * WAVES_N * WK) + 1) <= 63, "vmcnt range");
