@@ -608,17 +608,49 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
 
     const int n_wave0 = (tn * TNB + wn * WN) * 32;
     const int m_wave0 = (tm * TMB + wm * WM) * 32;
+    // 16x16x64 accumulators: a lane meets two tokens per token block and two channel quads per channel block, so all
+    // the scales and bias values it will use fit the registers the operand fragments have left free -- read them once,
+    // in one go, instead of three dependent LDS reads in front of every one of the WN*WM*4 quads
+    // (with three channel blocks per wavefront the channel operands of one block at a time: all three do not fit)
+    constexpr bool ALL_CH = WN <= 2;
+    float sx_r[MI16 ? WM : 1][2];
+    float4 sw_r[MI16 ? (ALL_CH ? WN : 1) : 1][2], b_r[MI16 ? (ALL_CH ? WN : 1) : 1][2];
+    auto read_channel_operands = [&](int i, int slot) {
+#pragma unroll
+        for (int hc = 0; hc < 2; ++hc) {
+            const int nl = (wn * WN + i) * 32 + 16 * hc + 4 * (lane >> 4);
+            sw_r[slot][hc] = *reinterpret_cast<const float4 *>(side_sw + nl);
+            b_r[slot][hc] = *reinterpret_cast<const float4 *>(side_b + nl);
+        }
+    };
+    if constexpr (MI16) {
+#pragma unroll
+        for (int j = 0; j < WM; ++j)
+#pragma unroll
+            for (int th = 0; th < 2; ++th) sx_r[j][th] = side_sx[(wm * WM + j) * 32 + 16 * th + (lane & 15)];
+        if constexpr (ALL_CH) {
+#pragma unroll
+            for (int i = 0; i < WN; ++i) read_channel_operands(i, i);
+        }
+    }
 #pragma unroll
     for (int j = 0; j < WM; ++j) {
         if (!my_block(j)) continue;                        // wave-uniform
 #pragma unroll
-        for (int i = 0; i < WN; ++i)
+        for (int i = 0; i < WN; ++i) {
+            if constexpr (MI16 && !ALL_CH) read_channel_operands(i, 0);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float sxm = side_sx[(wm * WM + j) * 32 + tok_of(q)] * (W4 ? 0.0625f : 1.0f);
-                const int nl = (wn * WN + i) * 32 + ch_of(q);   // channel inside the tile
-                const float4 swq = *reinterpret_cast<const float4 *>(side_sw + nl);
-                const float4 bq = *reinterpret_cast<const float4 *>(side_b + nl);
+                float sxm;
+                float4 swq, bq;
+                if constexpr (MI16) {
+                    sxm = sx_r[j][q & 1], swq = sw_r[ALL_CH ? i : 0][q >> 1], bq = b_r[ALL_CH ? i : 0][q >> 1];
+                } else {
+                    const int nl = (wn * WN + i) * 32 + ch_of(q);   // channel inside the tile
+                    sxm = side_sx[(wm * WM + j) * 32 + tok_of(q)] * (W4 ? 0.0625f : 1.0f);
+                    swq = *reinterpret_cast<const float4 *>(side_sw + nl);
+                    bq = *reinterpret_cast<const float4 *>(side_b + nl);
+                }
                 const float sw4[4] = {swq.x, swq.y, swq.z, swq.w}, b4[4] = {bq.x, bq.y, bq.z, bq.w};
                 h4 o;
 #pragma unroll
@@ -630,6 +662,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                 }
                 *reinterpret_cast<h4 *>(stg + tok_of(q) * ROW_BYTES + (i * 32 + ch_of(q)) * 2) = o;
             }
+        }
         // same wavefront, LDS operations complete in order: only the compiler has to be kept from
         // moving the differently-typed reads above the writes (and the next block's writes above them)
         asm volatile("" ::: "memory");
