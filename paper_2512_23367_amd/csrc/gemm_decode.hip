@@ -117,26 +117,30 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
             }
         }
 
-    // The finishing wavefronts (w < C handles channel group w) fetch their scales and bias now, so that the
-    // epilogue does not end with a dependent trip to memory.
-    float e_sx[MH], e_sw[4], e_b[4];
+    // The scales and bias the finishing wavefronts (w < C handles channel group w) will need are requested now, in
+    // front of the weights, and stay in registers as loaded: the epilogue does not end with a dependent trip to memory,
+    // and nothing here waits for them (a conversion or a branch around a load would: loads return in order, and the
+    // weight stream is queued behind them).  Range-checked buffer loads: tokens beyond M, channels beyond N and absent
+    // operands (zero-length buffers) read 0 without a branch.
+    int e_sx_raw[MH], e_sw_raw[4];
+    int e_b_raw[4];         // fp16 bits, zero-extended
+    float e_sx_fq = 0.0f;   // fused quantizer: the token scale is computed below
 #pragma unroll
-    for (int h = 0; h < MH; ++h) e_sx[h] = 0.0f;
+    for (int h = 0; h < MH; ++h) e_sx_raw[h] = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) e_sw[e] = 0.0f, e_b[e] = 0.0f;
-    if (EPI == EPI_F16 && wave < C) {
-        const int n0 = (rg0 + wave) * 16 + 4 * ch;
-        if (!FQ) {
+    for (int e = 0; e < 4; ++e) e_sw_raw[e] = 0, e_b_raw[e] = 0;
+    if (EPI == EPI_F16 && wave < C) {   // wave-uniform
+        const unsigned n0 = (unsigned)((rg0 + wave) * 16 + 4 * ch);
+        const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.sx, (!FQ && p.sx) ? (unsigned)p.M * 4u : 0u);
+        const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, (!W4 && p.sw) ? (unsigned)p.N * 4u : 0u);
+        const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (unsigned)p.N * 2u : 0u);
 #pragma unroll
-            for (int h = 0; h < MH; ++h)
-                if (r + 16 * h < p.M) e_sx[h] = p.sx[r + 16 * h] * (W4 ? 0.0625f : 1.0f);
+        for (int h = 0; h < MH; ++h) e_sx_raw[h] = __builtin_amdgcn_raw_buffer_load_b32(rx, (unsigned)(r + 16 * h) * 4u, 0, 0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            e_sw_raw[e] = __builtin_amdgcn_raw_buffer_load_b32(rw, (n0 + e) * 4u, 0, 0);
+            e_b_raw[e] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rb, (n0 + e) * 2u, 0, 0);
         }
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (n0 + e < p.N) {
-                if (!W4) e_sw[e] = p.sw[n0 + e];
-                if (p.bias) e_b[e] = __half2float(p.bias[n0 + e]);
-            }
     }
 
     // byte offset of channel group rg0+j inside the weight blob, for this lane
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         float scale, inv;
         token_scales(a, scale, inv);
         // the finishing lanes want the scale of token r: for r < M that is this lane's own token (Mp divides 16)
-        e_sx[0] = (r < p.M) ? scale * (W4 ? 0.0625f : 1.0f) : 0.0f;
+        e_sx_fq = (r < p.M) ? scale * (W4 ? 0.0625f : 1.0f) : 0.0f;
 #pragma unroll
         for (int sl = 0; sl < FQ_SLOTS; ++sl) {
             const int i = th0 + sl * fq_ppr + (lane >> fq_lg);
@@ -553,13 +557,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                         if (n0 + e < p.N) p.acc[(size_t)m * p.N + n0 + e] = W4 ? (si[e] >> 4) : si[e];
                     continue;
                 }
-                const float sxm = e_sx[h];
+                const float sxm = FQ ? e_sx_fq : __int_as_float(e_sx_raw[h]) * (W4 ? 0.0625f : 1.0f);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (n0 + e >= p.N) break;
+                    const float be = __half2float(__ushort_as_half((unsigned short)e_b_raw[e]));
                     float v;
-                    if (W4) v = __builtin_fmaf(sf[e], sxm, e_b[e]);
-                    else v = __builtin_fmaf((float)si[e] * sxm, e_sw[e], e_b[e]);
+                    if (W4) v = __builtin_fmaf(sf[e], sxm, be);
+                    else v = __builtin_fmaf((float)si[e] * sxm, __int_as_float(e_sw_raw[e]), be);
+                    asm("" : "+v"(v));   // rounded to fp32, then to fp16, as in the tile kernels' epilogue
                     p.y[(size_t)m * p.ldy + n0 + e] = __float2half_rn(v);
                 }
             }

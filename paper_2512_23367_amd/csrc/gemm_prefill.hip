@@ -658,6 +658,10 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                     float v;
                     if constexpr (W4) v = __builtin_fmaf(accf[i][j][4 * q + e], sxm, b4[e]);
                     else v = __builtin_fmaf((float)acc_get(i, j, q, e) * sxm, sw4[e], b4[e]);
+                    // the sum is rounded to fp32, then to fp16, in every kernel variant: left alone, the compiler fuses
+                    // some of these pairs into one instruction with a single rounding, and which ones differs from
+                    // kernel to kernel (results one fp16 ulp apart between tile shapes)
+                    asm("" : "+v"(v));
                     o[e] = (_Float16)v;
                 }
                 *reinterpret_cast<h4 *>(stg + tok_of(q) * ROW_BYTES + (i * 32 + ch_of(q)) * 2) = o;
@@ -761,7 +765,8 @@ __global__ __launch_bounds__(256) void splitk_finish_kernel(FinishParams f)
             h4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const float v = W4 ? __builtin_fmaf(sf[b][e], sxm, b4[e]) : __builtin_fmaf((float)si[b][e] * sxm, sw4[e], b4[e]);
+                float v = W4 ? __builtin_fmaf(sf[b][e], sxm, b4[e]) : __builtin_fmaf((float)si[b][e] * sxm, sw4[e], b4[e]);
+                asm("" : "+v"(v));   // rounded to fp32, then to fp16, as in the fused epilogue
                 o[e] = (_Float16)v;
             }
             __half *dst = f.y + (size_t)m * f.ldy + n0;

@@ -318,6 +318,34 @@ def test_linear_fp16_within_tolerance(G, bits, M, K, N, bias):
     assert G.norm_err(y, ref["y64"]) <= 6e-4
 
 
+def test_w8a8_fp16_output_has_the_same_bits_in_every_kernel(G):
+    """The int32 sums are exact and every epilogue takes the same steps in the same order (one fp32 rounding per
+    operation, the sum rounded to fp32 and then to fp16), so the fp16 output does not depend on the tile shape, the
+    matrix instruction, split-K or the kernel family: bit-identical across all of them, and equal to those steps redone
+    here in fp32 from the oracle's exact sums."""
+    import torch
+    M, K, N = 300, 1024, 520
+    x, w, b = synth.activations(M, K, 0, "single"), synth.weights(N, K, 0, "single"), synth.bias(N, 0, "single")
+    g = G.gpu_quant_weight(w, 8, 0)
+    ref = oracle.linear_w8a8(x, g["canon"], g["scales"], b)
+    f32 = np.float32
+    t = (ref["acc"].astype(f32) * ref["sx"].astype(f32)[:, None]).astype(f32)
+    # fma(t, sw, bias): one rounding of the exact t*sw + bias -- exact in the 64-bit significand of x86 long double
+    # (24 x 24 bits of product plus an fp16 value a few binades below it)
+    ld = np.longdouble
+    assert np.finfo(ld).nmant >= 63
+    want = (t.astype(ld) * g["scales"].astype(ld)[None, :] + b.astype(ld)[None, :]).astype(f32).astype(np.float16)
+    outs = {}
+    try:
+        for variant in PREFILL_VARIANTS + [100, 104, 122, 203, 302]:
+            ql.ql_set_kernel_variant(variant)
+            outs[variant] = G.gpu_linear(x, g, b, extra_ws=64 << 20)
+    finally:
+        ql.ql_set_kernel_variant(0)
+    for variant, y in outs.items():
+        assert (y.view(np.uint16) == want.view(np.uint16)).all(), f"kernel variant {variant}"
+
+
 @pytest.mark.parametrize("bits", [8, 4])
 @pytest.mark.parametrize("M,K,N,ldx", [(1, 4096, 520, None), (2, 4096, 200, 4104), (1, 11008, 72, None), (2, 512, 33, None),
                                        (1, 128, 16, 136), (2, 8192, 48, None),
