@@ -117,11 +117,14 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
             }
         }
 
-    // The scales and bias the finishing wavefronts (w < C handles channel group w) will need are requested now, in
-    // front of the weights, and stay in registers as loaded: the epilogue does not end with a dependent trip to memory,
-    // and nothing here waits for them (a conversion or a branch around a load would: loads return in order, and the
-    // weight stream is queued behind them).  Range-checked buffer loads: tokens beyond M, channels beyond N and absent
-    // operands (zero-length buffers) read 0 without a branch.
+    // The scales and bias the finishing wavefronts (w < C handles channel group w) will need are requested before the
+    // main loop and stay in registers as loaded: the epilogue does not end with a dependent trip to memory, and nothing
+    // waits for them before it (a conversion or a branch around a load would).  Range-checked buffer loads: tokens
+    // beyond M, channels beyond N and absent operands (zero-length buffers) read 0 without a branch.  Where the ring is
+    // refilled through counted buffer loads (17 tokens and more) they go out first, so that the loop's wait counts stay
+    // exact; in the other loops right behind the first ring of weights -- in front of it, a register that one of them
+    // loads into can be wanted for a weight address, which costs the finishing wavefronts a memory round trip.
+    constexpr bool COUNTED_RING = !XL && MH >= 2 && (!W4 || WAVES == 8);
     int e_sx_raw[MH], e_sw_raw[4];
     int e_b_raw[4];         // fp16 bits, zero-extended
     float e_sx_fq = 0.0f;   // fused quantizer: the token scale is computed below
@@ -129,19 +132,22 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     for (int h = 0; h < MH; ++h) e_sx_raw[h] = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) e_sw_raw[e] = 0, e_b_raw[e] = 0;
-    if (EPI == EPI_F16 && wave < C) {   // wave-uniform
-        const unsigned n0 = (unsigned)((rg0 + wave) * 16 + 4 * ch);
-        const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.sx, (!FQ && p.sx) ? (unsigned)p.M * 4u : 0u);
-        const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, (!W4 && p.sw) ? (unsigned)p.N * 4u : 0u);
-        const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (unsigned)p.N * 2u : 0u);
+    auto request_finish_operands = [&]() {
+        if (EPI == EPI_F16 && wave < C) {   // wave-uniform
+            const unsigned n0 = (unsigned)((rg0 + wave) * 16 + 4 * ch);
+            const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.sx, (!FQ && p.sx) ? (unsigned)p.M * 4u : 0u);
+            const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, (!W4 && p.sw) ? (unsigned)p.N * 4u : 0u);
+            const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (unsigned)p.N * 2u : 0u);
 #pragma unroll
-        for (int h = 0; h < MH; ++h) e_sx_raw[h] = __builtin_amdgcn_raw_buffer_load_b32(rx, (unsigned)(r + 16 * h) * 4u, 0, 0);
+            for (int h = 0; h < MH; ++h) e_sx_raw[h] = __builtin_amdgcn_raw_buffer_load_b32(rx, (unsigned)(r + 16 * h) * 4u, 0, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            e_sw_raw[e] = __builtin_amdgcn_raw_buffer_load_b32(rw, (n0 + e) * 4u, 0, 0);
-            e_b_raw[e] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rb, (n0 + e) * 2u, 0, 0);
+            for (int e = 0; e < 4; ++e) {
+                e_sw_raw[e] = __builtin_amdgcn_raw_buffer_load_b32(rw, (n0 + e) * 4u, 0, 0);
+                e_b_raw[e] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rb, (n0 + e) * 2u, 0, 0);
+            }
         }
-    }
+    };
+    if (COUNTED_RING) request_finish_operands();
 
     // byte offset of channel group rg0+j inside the weight blob, for this lane
     size_t wgo[C];
@@ -299,6 +305,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
             if (FQ) load_tokens(th0, th1);
 #pragma unroll
             for (int u = 0; u < U; ++u) fetch(u, c0 + u);
+            if (!COUNTED_RING) request_finish_operands();
             if (FQ) quantize_tokens(th0, th1);
             else if (XL && c0 < c1) stage_tokens(4 * c0, 4 * c1);
             for (int c = c0; c < c1; c += U) {
@@ -412,6 +419,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
         __builtin_amdgcn_sched_barrier(0);             // keep these requests in front of the weights'
 #pragma unroll
         for (int u = 0; u < U; ++u) fetch(u, g0 + u);
+        if (!COUNTED_RING) request_finish_operands();
         if (g0 < g1) {
             if (s_regs) {
 #pragma unroll
