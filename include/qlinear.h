@@ -31,7 +31,7 @@
  *     device buffer 16-byte aligned (256-byte for workspaces and weight blobs)
  *   - limits: K % 64 == 0 (int8 weights) or K % 128 == 0 (int4, group = 128);
  *     K <= 131072 so that no int32 accumulator can overflow; padded sizes
- *     ceil32(M)*K and ceil32(N)*K below 2^31
+ *     ceil32(M)*K and ceil32(N)*K below 2^31; ldx <= 2^27 (QL_ERR_SHAPE beyond)
  *   - M == 0 is a valid no-op
  *
  * "Kernel layout": weights and quantized activations are consumed by the GEMM

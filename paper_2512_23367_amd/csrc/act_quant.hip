@@ -15,6 +15,8 @@
 namespace ql {
 namespace {
 
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
 // One workgroup quantizes RPB consecutive tokens.  RPB = 8 (prefill): a wavefront covers 8 tokens x 8
 // chunks per step (lane = token % 8 + 8 * chunk), so that in the GEMM's tile order the 8 lanes of one
 // chunk write one whole 128-byte line (8 token slots x 16 bytes) and in the row-major copy each token
@@ -108,6 +110,27 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
 
     Half16 v[NIT > 0 ? NIT : 1];
     unsigned mx = 0;
+    // Rows kept in registers: all NIT chunks of a lane are requested at once, through range-checked buffer loads
+    // with no branch around them (a chunk beyond the row, the wavefront's share or the last token gets an offset behind
+    // the buffer and reads zeros, which change neither a maximum nor a sum of squares).  With a conditional load per
+    // step the compiler waits for each step's data before it issues the next step's loads: one memory round trip per
+    // step instead of one per row.  The buffer is the workgroup's RPB rows, so the 32-bit offsets hold for any M.
+    auto load_row_chunks = [&]() {
+        const int rows = M - (int)blockIdx.x * RPB < RPB ? M - (int)blockIdx.x * RPB : RPB;
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<__half *>(x + (size_t)blockIdx.x * RPB * ldx), 0,
+            (int)(((size_t)(rows - 1) * ldx + K) * sizeof(__half)), 0x00020000);
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const int c = (s0 + i) * CPS + cl;
+            const bool ok = i < per_wave && c < nchunks && valid;
+            const unsigned off = ok ? (unsigned)r * (unsigned)ldx * 2u + (unsigned)c * 32u : 0xFFFFFFE0u;
+            const v4u lo = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0));
+            const v4u hi = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(rs, off + 16u, 0, 0));
+            v[i].lo = uint4{lo[0], lo[1], lo[2], lo[3]};
+            v[i].hi = uint4{hi[0], hi[1], hi[2], hi[3]};
+        }
+    };
     // MODE 3 with the row in registers: the fp32 values themselves are kept (the transform costs ~45 vector
     // operations per element, twice that if it were recomputed for the codes: the kernel is ALU-bound)
     constexpr bool KEEP32 = MODE == 3 && NIT > 0;
@@ -133,14 +156,9 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
             for (int i = 0; i < 16; ++i) ss += (double)(f[i] * f[i]);   // the product is exact in fp32
         };
         if (NIT > 0) {
+            load_row_chunks();
 #pragma unroll
-            for (int i = 0; i < NIT; ++i) {
-                const int c = (s0 + i) * CPS + cl;
-                if (i < per_wave && c < nchunks && valid) {
-                    v[i] = row[c];
-                    add_squares(v[i]);
-                }
-            }
+            for (int i = 0; i < NIT; ++i) add_squares(v[i]);   // absent chunks hold zeros
         } else {
             for (int i = 0; i < per_wave; ++i) {
                 const int c = (s0 + i) * CPS + cl;
@@ -167,7 +185,13 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
                 if (c < nchunks && valid) mx = row_max(row[c], c, mx);
             }
         }
+    } else if (NIT > 0 && !SM) {
+        load_row_chunks();
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) mx = abs_max_bits(v[i], mx);   // absent chunks hold zeros
     } else if (NIT > 0) {
+        // (SmoothQuant: a step's scale vector is requested together with its chunk; with the chunks requested ahead of
+        // all the scale vectors the kernel measured 18 % slower at K = 11008)
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = (s0 + i) * CPS + cl;
@@ -326,6 +350,13 @@ __global__ void act_repack_kernel(const int8_t *__restrict__ xq_rm, int M, int K
 
 }  // namespace
 
+// the row-in-registers kernels address a workgroup's 8 rows with 32-bit byte offsets
+static int check_row_stride(int64_t ldx)
+{
+    if (ldx > ((int64_t)1 << 27)) return fail(QL_ERR_SHAPE, "row stride %lld beyond 2^27 elements", (long long)ldx);
+    return QL_OK;
+}
+
 template <int RPB, int MODE>
 static void launch_aq(const __half *x, int64_t ldx, int M, int K, const float *inv_smooth, const __half *gamma, float eps,
                       int8_t *xq_rm, int8_t *xq_kl, float *sx, hipStream_t st)
@@ -350,6 +381,7 @@ int launch_act_quant(const __half *x, int64_t ldx, int M, int K, int8_t *xq_rm, 
                      float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
+    QL_TRY(check_row_stride(ldx));
     if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 0>(x, ldx, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
     else launch_aq<8, 0>(x, ldx, M, K, nullptr, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant launch");
@@ -359,6 +391,7 @@ int launch_act_quant_smooth(const __half *x, int64_t ldx, int M, int K, const fl
                             int8_t *xq_kl, float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
+    QL_TRY(check_row_stride(ldx));
     if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 1>(x, ldx, M, K, inv_smooth, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
     else launch_aq<8, 1>(x, ldx, M, K, inv_smooth, nullptr, 0.0f, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant (smooth) launch");
@@ -394,6 +427,7 @@ int launch_act_quant_rmsnorm(const __half *x, int64_t ldx, int M, int K, const _
                              int8_t *xq_kl, float *sx, hipStream_t st)
 {
     if (M == 0) return QL_OK;
+    QL_TRY(check_row_stride(ldx));
     if (M <= SINGLE_TOKEN_MAX_M) launch_aq<1, 2>(x, ldx, M, K, nullptr, gamma, eps, xq_rm, xq_kl, sx, st);
     else launch_aq<8, 2>(x, ldx, M, K, nullptr, gamma, eps, xq_rm, xq_kl, sx, st);
     return check_hip(hipGetLastError(), "act_quant (rmsnorm) launch");
