@@ -63,7 +63,8 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, unsigned bytes
 // than the separate launch.
 constexpr int FQ_MAX_M = 4;
 constexpr size_t FQ_MAX_LDS = 24576;   // staged tokens (M + 1) * K bytes: four workgroups per CU still fit
-template <bool W4, int MH, int C, int EPI, int WAVES, bool XL, int FQ>
+// OVL (fused quantizer only): the first ring of weights is loaded without conditions, see the int8 loop.
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL, int FQ, bool OVL>
 __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 {
     static_assert(!FQ || (XL && EPI == EPI_F16), "fused quantization stages the tokens in LDS");
@@ -133,7 +134,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
 #pragma unroll
     for (int e = 0; e < 4; ++e) e_sw_raw[e] = 0, e_b_raw[e] = 0;
     auto request_finish_operands = [&]() {
-        if (EPI == EPI_F16 && wave < C) {   // wave-uniform
+        // (fused quantizer overlapping the first ring: every wavefront requests them, first of all -- without a branch
+        // around them the compiler can count them, so that the wait for the tokens does not include the weights)
+        if (EPI == EPI_F16 && ((FQ > 0 && OVL) || wave < C)) {   // wave-uniform
             const unsigned n0 = (unsigned)((rg0 + wave) * 16 + 4 * ch);
             const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.sx, (!FQ && p.sx) ? (unsigned)p.M * 4u : 0u);
             const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, (!W4 && p.sw) ? (unsigned)p.N * 4u : 0u);
@@ -147,7 +150,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
             }
         }
     };
-    if (COUNTED_RING) request_finish_operands();
+    if (COUNTED_RING || (FQ > 0 && OVL)) request_finish_operands();
 
     // byte offset of channel group rg0+j inside the weight blob, for this lane
     size_t wgo[C];
@@ -303,11 +306,29 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
                 }
             };
             if (FQ) load_tokens(th0, th1);
+            if constexpr (FQ > 0 && OVL) {
+                // Fused quantizer, at most one workgroup per CU (the host's choice): the first ring is loaded without
+                // conditions (a chunk past the wavefront's range repeats the last chunk of the matrix, an absent channel
+                // group reads group 0; neither is multiplied into anything that is stored).  With a branch around a load
+                // the compiler cannot count the loads in flight and waits for all of them -- the weights included --
+                // before the tokens are quantized; counted, the quantizer runs while the weights are on their way
+                // (O projection, one token: 6.7 -> 5.5 us).  With several workgroups per CU the conditional form
+                // measured faster (a CU then overlaps one workgroup's quantizer with another's wait anyway).
 #pragma unroll
-            for (int u = 0; u < U; ++u) fetch(u, c0 + u);
-            if (!COUNTED_RING) request_finish_operands();
-            if (FQ) quantize_tokens(th0, th1);
-            else if (XL && c0 < c1) stage_tokens(4 * c0, 4 * c1);
+                for (int u = 0; u < U; ++u) {
+                    const int c = c0 + u < nchunks ? c0 + u : nchunks - 1;
+#pragma unroll
+                    for (int j = 0; j < C; ++j)
+                        wv[u][j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(p.wq + wgo[j] + (size_t)c * 2048));
+                }
+                quantize_tokens(th0, th1);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) fetch(u, c0 + u);
+                if (!COUNTED_RING) request_finish_operands();
+                if (FQ) quantize_tokens(th0, th1);
+                else if (XL && c0 < c1) stage_tokens(4 * c0, 4 * c1);
+            }
             for (int c = c0; c < c1; c += U) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -417,9 +438,19 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
             }
         }
         __builtin_amdgcn_sched_barrier(0);             // keep these requests in front of the weights'
+        if constexpr (FQ > 0 && OVL) {   // unconditional first ring, as in the int8 loop
 #pragma unroll
-        for (int u = 0; u < U; ++u) fetch(u, g0 + u);
-        if (!COUNTED_RING) request_finish_operands();
+            for (int u = 0; u < U; ++u) {
+                const int g = g0 + u < G ? g0 + u : G - 1;
+#pragma unroll
+                for (int j = 0; j < C; ++j)
+                    wv[u][j] = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(p.wq + wgo[j] + (size_t)g * 2048));
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) fetch(u, g0 + u);
+        }
+        if (!COUNTED_RING && !(FQ > 0 && OVL)) request_finish_operands();
         if (g0 < g1) {
             if (s_regs) {
 #pragma unroll
@@ -581,7 +612,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_decode_kernel(DecodeParams p)
     }
 }
 
-template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false, int FQ = 0>
+template <bool W4, int MH, int C, int EPI, int WAVES, bool XL = false, int FQ = 0, bool OVL = false>
 int launch_one(const GemmArgs &a, hipStream_t st)
 {
     DecodeParams p;
@@ -610,11 +641,11 @@ int launch_one(const GemmArgs &a, hipStream_t st)
     if (XL || W4) {   // static reduction buffer + staged tokens/scales can exceed the default 64 KB limit
         // once per kernel and process; the initialisation of a function-local static is thread-safe
         static const hipError_t attr_status = hipFuncSetAttribute(
-            reinterpret_cast<const void *>(gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>),
+            reinterpret_cast<const void *>(gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ, OVL>),
             hipFuncAttributeMaxDynamicSharedMemorySize, 40960 + 32768);
         QL_TRY(check_hip(attr_status, "hipFuncSetAttribute(max dynamic LDS)"));
     }
-    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ>), dim3(grid, MH >= 2 ? ceil_div(a.M, 16 * MH) : 1),
+    hipLaunchKernelGGL((gemm_decode_kernel<W4, MH, C, EPI, WAVES, XL, FQ, OVL>), dim3(grid, MH >= 2 ? ceil_div(a.M, 16 * MH) : 1),
                        dim3(WAVES * 64), xs_bytes, st, p);
     return check_hip(hipGetLastError(), "gemm_decode launch");
 }
@@ -721,6 +752,13 @@ int by_m(const GemmArgs &a, int variant, hipStream_t st)
         const int mp = a.M <= 1 ? 1 : a.M <= 2 ? 2 : 4;
         if (pieces * mp > 128) return fail(QL_ERR_UNSUPPORTED, "fused quantization: unsupported shape");
         if constexpr (EPI == EPI_F16) {
+            // at most one workgroup per CU: the quantizer overlaps the first ring of weights (OVL)
+            if (ceil_div(round_up(a.N, TILE_ROWS) / 16, c) <= 256) {
+                if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, 2, true>(a, st);
+                if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, 2, true>(a, st);
+                if (c == 3) return launch_one<W4, 1, 3, EPI, 8, true, 2, true>(a, st);
+                return launch_one<W4, 1, 4, EPI, 8, true, 2, true>(a, st);
+            }
             if (c == 1) return launch_one<W4, 1, 1, EPI, 8, true, 2>(a, st);
             if (c == 2) return launch_one<W4, 1, 2, EPI, 8, true, 2>(a, st);
             if (c == 3) return launch_one<W4, 1, 3, EPI, 8, true, 2>(a, st);
