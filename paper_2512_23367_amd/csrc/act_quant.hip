@@ -52,6 +52,10 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
                                                                     float *__restrict__ sx)
 {
     constexpr bool SM = MODE != 0;   // the codes come from fp32 values
+    // MODE 2, up to 4 steps: the lane's chunks of gamma are requested with the row's and kept in registers (as
+    // conditional loads inside the maximum and the code loops each of them was a trip to L2 of its own, twice)
+    constexpr bool GREG = MODE == 2 && NIT > 0 && NIT <= 4;
+    const Half16 no_gamma = Half16{uint4{0, 0, 0, 0}, uint4{0, 0, 0, 0}};
     float rnorm = 0.0f;              // MODE 2: 1 / sqrt(mean(x^2) + eps) of this lane's token
     auto widen = [](const Half16 &h, float (&f)[16]) {
         const unsigned w[8] = {h.lo.x, h.lo.y, h.lo.z, h.lo.w, h.hi.x, h.hi.y, h.hi.z, h.hi.w};
@@ -62,7 +66,7 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
         }
     };
     const Half16 *row_up = nullptr;    // MODE 3: the up half of this lane's token
-    auto smoothed = [&](const Half16 &h, int c, float (&f)[16]) {
+    auto smoothed = [&](const Half16 &h, int c, float (&f)[16], const Half16 &gch) {
         if constexpr (MODE == 3) {
             float u[16];
             widen(h, f);
@@ -74,7 +78,8 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
         if constexpr (MODE == 2) {
             float g[16];
             widen(h, f);
-            widen(reinterpret_cast<const Half16 *>(gamma)[c], g);
+            if constexpr (GREG) widen(gch, g);
+            else widen(reinterpret_cast<const Half16 *>(gamma)[c], g);
 #pragma unroll
             for (int i = 0; i < 16; ++i) f[i] = (f[i] * rnorm) * g[i];
             return;
@@ -89,10 +94,10 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
             f[i + 3] = half_bits_to_float(w[i / 2 + 1] >> 16) * s4.w;
         }
     };
-    auto row_max = [&](const Half16 &h, int c, unsigned m) {
+    auto row_max = [&](const Half16 &h, int c, unsigned m, const Half16 &gch) {
         if (!SM) return abs_max_bits(h, m);
         float f[16];
-        smoothed(h, c, f);
+        smoothed(h, c, f, gch);
 #pragma unroll
         for (int i = 0; i < 16; ++i) m = max(m, __float_as_uint(fabsf(f[i])));
         return m;
@@ -109,6 +114,7 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     const int s0 = wave * per_wave;
 
     Half16 v[NIT > 0 ? NIT : 1];
+    Half16 gv[GREG ? NIT : 1];
     unsigned mx = 0;
     // Rows kept in registers: all NIT chunks of a lane are requested at once, through range-checked buffer loads
     // with no branch around them (a chunk beyond the row, the wavefront's share or the last token gets an offset behind
@@ -130,6 +136,19 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
             v[i].lo = uint4{lo[0], lo[1], lo[2], lo[3]};
             v[i].hi = uint4{hi[0], hi[1], hi[2], hi[3]};
         }
+        if constexpr (GREG) {
+            const __amdgpu_buffer_rsrc_t rg = __builtin_amdgcn_make_buffer_rsrc(const_cast<__half *>(gamma), 0,
+                                                                                K * (int)sizeof(__half), 0x00020000);
+#pragma unroll
+            for (int i = 0; i < NIT; ++i) {
+                const int c = (s0 + i) * CPS + cl;
+                const unsigned off = (i < per_wave && c < nchunks && valid) ? (unsigned)c * 32u : 0xFFFFFFE0u;
+                const v4u lo = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, 0));
+                const v4u hi = __builtin_bit_cast(v4u, __builtin_amdgcn_raw_buffer_load_b128(rg, off + 16u, 0, 0));
+                gv[i].lo = uint4{lo[0], lo[1], lo[2], lo[3]};
+                gv[i].hi = uint4{hi[0], hi[1], hi[2], hi[3]};
+            }
+        }
     };
     // MODE 3 with the row in registers: the fp32 values themselves are kept (the transform costs ~45 vector
     // operations per element, twice that if it were recomputed for the codes: the kernel is ALU-bound)
@@ -140,7 +159,7 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
         for (int i = 0; i < NIT; ++i) {
             const int c = (s0 + i) * CPS + cl;
             if (i < per_wave && c < nchunks && valid) {
-                smoothed(row[c], c, hv[i]);
+                smoothed(row[c], c, hv[i], no_gamma);
 #pragma unroll
                 for (int e = 0; e < 16; ++e) mx = max(mx, __float_as_uint(fabsf(hv[i][e])));
             }
@@ -177,12 +196,12 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
 #pragma unroll
             for (int i = 0; i < NIT; ++i) {
                 const int c = (s0 + i) * CPS + cl;
-                if (i < per_wave && c < nchunks && valid) mx = row_max(v[i], c, mx);
+                if (i < per_wave && c < nchunks && valid) mx = row_max(v[i], c, mx, gv[GREG ? i : 0]);
             }
         } else {
             for (int i = 0; i < per_wave; ++i) {
                 const int c = (s0 + i) * CPS + cl;
-                if (c < nchunks && valid) mx = row_max(row[c], c, mx);
+                if (c < nchunks && valid) mx = row_max(row[c], c, mx, no_gamma);
             }
         }
     } else if (NIT > 0 && !SM) {
@@ -197,13 +216,13 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
             const int c = (s0 + i) * CPS + cl;
             if (i < per_wave && c < nchunks && valid) {
                 v[i] = row[c];
-                mx = row_max(v[i], c, mx);
+                mx = row_max(v[i], c, mx, no_gamma);
             }
         }
     } else {
         for (int i = 0; i < per_wave; ++i) {
             const int c = (s0 + i) * CPS + cl;
-            if (c < nchunks && valid) mx = row_max(row[c], c, mx);
+            if (c < nchunks && valid) mx = row_max(row[c], c, mx, no_gamma);
         }
     }
 #pragma unroll
@@ -218,11 +237,11 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
     else token_scales(mx, scale, inv);
     if (wave == 0 && cl == 0 && valid) sx[m] = scale;
 
-    auto emit = [&](int c, const Half16 &h) {
+    auto emit = [&](int c, const Half16 &h, const Half16 &gch) {
         uint4 q;
         if (SM) {
             float f[16];
-            smoothed(h, c, f);
+            smoothed(h, c, f, gch);
             q = quant_chunk_f32(f, inv);
         } else {
             q = quant_chunk(h, inv);
@@ -244,12 +263,12 @@ __global__ __launch_bounds__(MAX_WAVES * 64) void act_quant_kernel(const __half 
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
             const int c = (s0 + i) * CPS + cl;
-            if (i < per_wave && c < nchunks && valid) emit(c, v[i]);
+            if (i < per_wave && c < nchunks && valid) emit(c, v[i], gv[GREG ? i : 0]);
         }
     } else {
         for (int i = 0; i < per_wave; ++i) {
             const int c = (s0 + i) * CPS + cl;
-            if (c < nchunks && valid) emit(c, row[c]);
+            if (c < nchunks && valid) emit(c, row[c], no_gamma);
         }
     }
 }
