@@ -163,24 +163,11 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     // their way one memory round trip after the kernel starts instead of four (one per operand, then the stages).
     // Range-checked buffer loads (an index beyond M / N, or an absent operand = a zero-length buffer, reads 0): no
     // branch, hence no wait where branches would join.
-    // (int8 kernels.  The int4 kernel keeps the plain form -- load, wait, store, operand by operand: with the early
-    // loads its main loop came out 3-4 % slower, the fill being a smaller share of its longer tiles anyway.)
     int r_sx[SXI], r_sw[SWI];
     short r_b[SWI];   // converted when it is written to LDS: a conversion here would wait for the load
-    if (W4 && EPI == EPI_F16) {
-        for (int t = threadIdx.x; t < TMB * 32; t += NW * 64) {
-            const int m = tm * TMB * 32 + t;
-            side_sx[t] = (m < p.M) ? p.sx[m] : 0.0f;
-        }
-        for (int t = threadIdx.x; t < TNB * 32; t += NW * 64) {
-            const int n = tn * TNB * 32 + t;
-            side_sw[t] = 0.0f;
-            side_b[t] = (p.bias && n < p.N) ? __half2float(p.bias[n]) : 0.0f;
-        }
-    }
-    if (!W4 && EPI == EPI_F16) {
+    if (EPI == EPI_F16) {
         const __amdgpu_buffer_rsrc_t rx = make_rsrc(p.sx, (unsigned)p.M * 4u);
-        const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, p.sw ? (unsigned)p.N * 4u : 0u);
+        const __amdgpu_buffer_rsrc_t rw = make_rsrc(p.sw, (!W4 && p.sw) ? (unsigned)p.N * 4u : 0u);
         const __amdgpu_buffer_rsrc_t rb = make_rsrc(p.bias, p.bias ? (unsigned)p.N * 2u : 0u);
 #pragma unroll
         for (int it = 0; it < SXI; ++it)
@@ -290,7 +277,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
     // prologue: STAGES-1 stages in flight
 #pragma unroll
     for (int s = 0; s < STAGES - 1; ++s) issue_stage(s);
-    if (!W4 && EPI == EPI_F16) {   // made visible by the barriers of the main loop / the one in front of the epilogue
+    if (EPI == EPI_F16) {   // made visible by the barriers of the main loop / the one in front of the epilogue
 #pragma unroll
         for (int it = 0; it < SXI; ++it) {
             side_sx[threadIdx.x + it * NW * 64] = __int_as_float(r_sx[it]);
