@@ -620,6 +620,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
             for (int i = 0; i < WN; ++i) read_channel_operands(i, i);
         }
     }
+    // int4 kernel (32x32x32 accumulators: one token per token block, four channel quads per channel block; no channel
+    // scales): the same, token scales and bias only
+    float sx4_r[W4 ? WM : 1];
+    float4 b4_r[W4 ? WN : 1][4];
+    if constexpr (W4) {
+#pragma unroll
+        for (int j = 0; j < WM; ++j) sx4_r[j] = side_sx[(wm * WM + j) * 32 + (lane & 31)] * 0.0625f;
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                b4_r[i][q] = *reinterpret_cast<const float4 *>(side_b + (wn * WN + i) * 32 + 8 * q + 4 * (lane >> 5));
+    }
 #pragma unroll
     for (int j = 0; j < WM; ++j) {
         if (!my_block(j)) continue;                        // wave-uniform
@@ -632,6 +645,8 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N *WK * 64, OCC) void gemm_prefill_k
                 float4 swq, bq;
                 if constexpr (MI16) {
                     sxm = sx_r[j][q & 1], swq = sw_r[ALL_CH ? i : 0][q >> 1], bq = b_r[ALL_CH ? i : 0][q >> 1];
+                } else if constexpr (W4) {
+                    sxm = sx4_r[j], swq = float4{0.0f, 0.0f, 0.0f, 0.0f}, bq = b4_r[i][q];
                 } else {
                     const int nl = (wn * WN + i) * 32 + ch_of(q);   // channel inside the tile
                     sxm = side_sx[(wm * WM + j) * 32 + tok_of(q)] * (W4 ? 0.0625f : 1.0f);
